@@ -1,0 +1,358 @@
+/*
+ * CHESS decode hot path -- plain CPU oracle.
+ *
+ * TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the tests, the smoke check and
+ * the benchmark's cpu_baseline leg may call into this file.  It shares no
+ * code, header, table or helper with the HIP library; it is written straight
+ * from the paper (CHESS, arxiv 2602.20732) so that a reader can check every
+ * function against the passage it cites.
+ *
+ * Arithmetic: every floating-point accumulation is fp64, taken in the index
+ * order the formula states; values the method stores (summary vectors, the
+ * attention output) are rounded once to fp32.
+ *
+ * What each function follows:
+ *   oracle_summarize  Sec. 3.1, Eq. 1 (page vector = mean of the page's key
+ *                     rows) and Eq. 2 (chunk / grid vector = mean of children)
+ *   oracle_scores     Sec. 3.2, Eq. 4 (dot product of probe and unit vector)
+ *   oracle_select     Sec. 3.2 cascade text and Alg. 1 stage 2 (grid -> chunk
+ *                     -> page, a child is ranked only if its parent was kept),
+ *                     then the union with sink and recent-window pages
+ *   oracle_attend     softmax attention restricted to the listed pages: the
+ *                     textbook definition, the paper's "Full-KV" when every
+ *                     page is listed (Sec. 5.1 Baselines)
+ *
+ * Readings where the paper is silent (all restated in the design notes):
+ *   - one layer, one page set per KV head; the probe of a KV head is the sum
+ *     of its query-group rows (a dot of concatenated heads is the sum of the
+ *     per-head dots, Eq. 1's Flatten restricted to the group);
+ *   - a partial tail page / last chunk / last grid is averaged over the
+ *     members that exist;
+ *   - "top rho fraction" keeps exactly ceil(rho * n) of the n units that are
+ *     active at that level (the reading under which Table 1's budgets are the
+ *     products of the three ratios); rank order is score descending, index
+ *     ascending; an inactive unit is never ranked (no zero fill);
+ *   - sink and window pages are not candidates at page level, the budget is
+ *     on top of them.
+ * Parity unpinned (our reading only, the paper cannot arbitrate): N_c / N_g
+ * defaults, ceil vs interpolated quantile count, group-sum probe, exclusion
+ * of safety pages from the candidates, partial-unit means, the oversampling
+ * factors of the budget plan.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_PLAN_BUDGET = 0, ORACLE_PLAN_RATIO = 1, ORACLE_PLAN_FLAT = 2 };
+
+typedef struct {
+    int32_t n_q_heads;       /* H_q                                        */
+    int32_t n_kv_heads;      /* H_kv, divides H_q                          */
+    int32_t head_dim;        /* d                                          */
+    int32_t page_size;       /* B tokens per page                          */
+    int32_t pages_per_chunk; /* N_c                                        */
+    int32_t chunks_per_grid; /* N_g                                        */
+    int32_t max_pages;       /* row stride of the block table and of the
+                                per-level summary arrays (in pages)        */
+} oracle_geom;
+
+typedef struct {
+    int32_t plan;          /* ORACLE_PLAN_*                                 */
+    int32_t sink_pages;    /* s                                             */
+    int32_t window_pages;  /* w                                             */
+    int32_t budget_pages;  /* > 0: k for every sequence                     */
+    int32_t budget_bp;     /* else k = max(1, ceil(P * bp / 10000))         */
+    int32_t over_chunk;    /* budget plan: chunk oversampling               */
+    int32_t over_grid;     /* budget plan: grid oversampling                */
+    int32_t rho_g_bp, rho_c_bp, rho_p_bp; /* ratio plan, basis points       */
+} oracle_plan;
+
+static double bf16_value(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+/* max row counts of the chunk and grid arrays for a given page stride */
+static int64_t chunk_stride(const oracle_geom *g) { return ceil_div(g->max_pages, g->pages_per_chunk); }
+static int64_t grid_stride(const oracle_geom *g) { return ceil_div(chunk_stride(g), g->chunks_per_grid); }
+
+/* K pool layout: [physical page][kv head][token in page][dim], bf16. */
+static double k_at(const uint16_t *k_pool, const oracle_geom *g, int64_t phys, int h, int tok, int dim)
+{
+    int64_t off = (((phys * g->n_kv_heads + h) * g->page_size) + tok) * g->head_dim + dim;
+    return bf16_value(k_pool[off]);
+}
+
+/* V pool layout: [physical page][kv head][dim][token in page], bf16. */
+static double v_at(const uint16_t *v_pool, const oracle_geom *g, int64_t phys, int h, int tok, int dim)
+{
+    int64_t off = (((phys * g->n_kv_heads + h) * g->head_dim) + dim) * g->page_size + tok;
+    return bf16_value(v_pool[off]);
+}
+
+/*
+ * Eq. 1 and Eq. 2.  page_vec [batch][H_kv][max_pages][d], chunk_vec
+ * [batch][H_kv][ceil(max_pages/N_c)][d], grid_vec [batch][H_kv][ceil(.../N_g)][d],
+ * all fp32; rows past a sequence's own counts are left untouched.
+ */
+void oracle_summarize(const uint16_t *k_pool, const int32_t *block_table, const int32_t *seq_lens,
+                      int32_t batch, const oracle_geom *g, float *page_vec, float *chunk_vec, float *grid_vec)
+{
+    const int d = g->head_dim, B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
+    const int64_t cs = chunk_stride(g), gs = grid_stride(g);
+    for (int b = 0; b < batch; ++b) {
+        const int64_t L = seq_lens[b];
+        const int64_t P = ceil_div(L, B), nc = ceil_div(P, Nc), ng = ceil_div(nc, Ng);
+        for (int h = 0; h < g->n_kv_heads; ++h) {
+            float *pv = page_vec + ((int64_t)b * g->n_kv_heads + h) * g->max_pages * d;
+            float *cv = chunk_vec + ((int64_t)b * g->n_kv_heads + h) * cs * d;
+            float *gv = grid_vec + ((int64_t)b * g->n_kv_heads + h) * gs * d;
+            for (int64_t j = 0; j < P; ++j) {                /* Eq. 1 */
+                const int64_t phys = block_table[(int64_t)b * g->max_pages + j];
+                const int64_t n = (j == P - 1) ? L - j * B : B;
+                for (int i = 0; i < d; ++i) {
+                    double acc = 0.0;
+                    for (int t = 0; t < n; ++t) acc += k_at(k_pool, g, phys, h, t, i);
+                    pv[j * d + i] = (float)(acc / (double)n);
+                }
+            }
+            for (int64_t c = 0; c < nc; ++c) {               /* Eq. 2, chunks */
+                const int64_t lo = c * Nc, hi = (lo + Nc < P) ? lo + Nc : P;
+                for (int i = 0; i < d; ++i) {
+                    double acc = 0.0;
+                    for (int64_t j = lo; j < hi; ++j) acc += (double)pv[j * d + i];
+                    cv[c * d + i] = (float)(acc / (double)(hi - lo));
+                }
+            }
+            for (int64_t k = 0; k < ng; ++k) {               /* Eq. 2, grids */
+                const int64_t lo = k * Ng, hi = (lo + Ng < nc) ? lo + Ng : nc;
+                for (int i = 0; i < d; ++i) {
+                    double acc = 0.0;
+                    for (int64_t c = lo; c < hi; ++c) acc += (double)cv[c * d + i];
+                    gv[k * d + i] = (float)(acc / (double)(hi - lo));
+                }
+            }
+        }
+    }
+}
+
+/* probe of KV head h: sum of its group's query rows, g ascending */
+static void probe_of(const uint16_t *q, const oracle_geom *g, int b, int h, double *probe)
+{
+    const int G = g->n_q_heads / g->n_kv_heads, d = g->head_dim;
+    for (int i = 0; i < d; ++i) {
+        double acc = 0.0;
+        for (int r = 0; r < G; ++r)
+            acc += bf16_value(q[((int64_t)b * g->n_q_heads + h * G + r) * d + i]);
+        probe[i] = acc;
+    }
+}
+
+static double dot_probe(const double *probe, const float *vec, int d)
+{
+    double acc = 0.0;
+    for (int i = 0; i < d; ++i) acc += probe[i] * (double)vec[i];
+    return acc;
+}
+
+/*
+ * Eq. 4 for every unit of every level (Alg. 1 stage 1 scores the whole
+ * hierarchy; the cascade below only ever looks at active units).
+ * Outputs fp64, same row strides as the summary arrays.
+ */
+void oracle_scores(const uint16_t *q, const float *page_vec, const float *chunk_vec, const float *grid_vec,
+                   const int32_t *seq_lens, int32_t batch, const oracle_geom *g,
+                   double *page_s, double *chunk_s, double *grid_s)
+{
+    const int d = g->head_dim, B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
+    const int64_t cs = chunk_stride(g), gs = grid_stride(g);
+    double *probe = (double *)malloc(sizeof(double) * d);
+    for (int b = 0; b < batch; ++b) {
+        const int64_t P = ceil_div(seq_lens[b], B), nc = ceil_div(P, Nc), ng = ceil_div(nc, Ng);
+        for (int h = 0; h < g->n_kv_heads; ++h) {
+            const int64_t row = (int64_t)b * g->n_kv_heads + h;
+            probe_of(q, g, b, h, probe);
+            for (int64_t j = 0; j < P; ++j)
+                page_s[row * g->max_pages + j] = dot_probe(probe, page_vec + (row * g->max_pages + j) * d, d);
+            for (int64_t c = 0; c < nc; ++c)
+                chunk_s[row * cs + c] = dot_probe(probe, chunk_vec + (row * cs + c) * d, d);
+            for (int64_t k = 0; k < ng; ++k)
+                grid_s[row * gs + k] = dot_probe(probe, grid_vec + (row * gs + k) * d, d);
+        }
+    }
+    free(probe);
+}
+
+typedef struct { double score; int64_t index; } ranked;
+
+/* rank order of the cascade: larger score first, then smaller index */
+static int ranked_cmp(const void *a, const void *b)
+{
+    const ranked *x = (const ranked *)a, *y = (const ranked *)b;
+    if (x->score > y->score) return -1;
+    if (x->score < y->score) return 1;
+    return (x->index > y->index) - (x->index < y->index);
+}
+
+/* keep the first k of n candidates in rank order; mark them in keep[index] */
+static void keep_top(ranked *cand, int64_t n, int64_t k, uint8_t *keep)
+{
+    qsort(cand, (size_t)n, sizeof *cand, ranked_cmp);
+    for (int64_t i = 0; i < k && i < n; ++i) keep[cand[i].index] = 1;
+}
+
+static int64_t ceil_bp(int64_t n, int64_t bp) { return (n * bp + 9999) / 10000; }
+static int64_t clamp_i(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/*
+ * The cascade of Sec. 3.2 / Alg. 1 stage 2, then the union with the safety
+ * pages.  page_ids [batch][H_kv][max_sel] ascending, padded with -1;
+ * n_selected [batch][H_kv].  Optional outputs (may be NULL): kept_grid /
+ * kept_chunk masks (uint8, summary-array strides) and counts[row*3 + {0,1,2}]
+ * = k_g, k_c, k_p actually used.
+ * Returns 0, or -1 if a row would need more than max_sel ids.
+ */
+int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_vec, const float *grid_vec,
+                  const int32_t *seq_lens, int32_t batch, const oracle_geom *g, const oracle_plan *pl,
+                  int32_t max_sel, int32_t *page_ids, int32_t *n_selected,
+                  uint8_t *kept_grid, uint8_t *kept_chunk, int32_t *counts)
+{
+    const int d = g->head_dim, B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
+    const int64_t cs = chunk_stride(g), gs = grid_stride(g);
+    const int64_t s = pl->sink_pages, w = pl->window_pages;
+    double *probe = (double *)malloc(sizeof(double) * d);
+    ranked *cand = (ranked *)malloc(sizeof(ranked) * (size_t)(g->max_pages + 1));
+    uint8_t *kg = (uint8_t *)malloc((size_t)gs + 1), *kc = (uint8_t *)malloc((size_t)cs + 1);
+    uint8_t *kp = (uint8_t *)malloc((size_t)g->max_pages + 1);
+    int rc = 0;
+
+    for (int b = 0; b < batch && rc == 0; ++b) {
+        const int64_t L = seq_lens[b];
+        const int64_t P = ceil_div(L, B), nc = ceil_div(P, Nc), ng = ceil_div(nc, Ng);
+        for (int h = 0; h < g->n_kv_heads; ++h) {
+            const int64_t row = (int64_t)b * g->n_kv_heads + h;
+            int32_t *ids = page_ids + row * max_sel;
+            for (int i = 0; i < max_sel; ++i) ids[i] = -1;
+            memset(kg, 0, (size_t)gs + 1); memset(kc, 0, (size_t)cs + 1); memset(kp, 0, (size_t)g->max_pages + 1);
+            int64_t k_g = 0, k_c = 0, k_p = 0, n = 0;
+
+            if (P <= s + w) {                       /* safety pages cover the sequence */
+                if (P > max_sel) { rc = -1; break; }
+                for (int64_t j = 0; j < P; ++j) ids[n++] = (int32_t)j;
+            } else {
+                const int64_t k = pl->budget_pages > 0 ? pl->budget_pages
+                                                       : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
+                const int64_t kc_target = ceil_div((int64_t)pl->over_chunk * k, Nc);
+                probe_of(q, g, b, h, probe);
+
+                /* level 1: every grid is a candidate */
+                int64_t m = 0;
+                for (int64_t u = 0; u < ng; ++u) {
+                    cand[m].score = dot_probe(probe, grid_vec + (row * gs + u) * d, d);
+                    cand[m++].index = u;
+                }
+                if (pl->plan == ORACLE_PLAN_RATIO) k_g = clamp_i(ceil_bp(m, pl->rho_g_bp), 1, m);
+                else if (pl->plan == ORACLE_PLAN_FLAT) k_g = m;
+                else k_g = clamp_i(ceil_div((int64_t)pl->over_grid * kc_target, Ng), 0, m);
+                keep_top(cand, m, k_g, kg);
+
+                /* level 2: chunks whose parent grid was kept */
+                m = 0;
+                for (int64_t u = 0; u < nc; ++u) if (kg[u / Ng]) {
+                    cand[m].score = dot_probe(probe, chunk_vec + (row * cs + u) * d, d);
+                    cand[m++].index = u;
+                }
+                if (pl->plan == ORACLE_PLAN_RATIO) k_c = clamp_i(ceil_bp(m, pl->rho_c_bp), 1, m);
+                else if (pl->plan == ORACLE_PLAN_FLAT) k_c = m;
+                else k_c = clamp_i(kc_target, 0, m);
+                keep_top(cand, m, k_c, kc);
+
+                /* level 3: pages whose parent chunk was kept, safety pages excluded */
+                m = 0;
+                for (int64_t u = s; u < P - w; ++u) if (kc[u / Nc]) {
+                    cand[m].score = dot_probe(probe, page_vec + (row * g->max_pages + u) * d, d);
+                    cand[m++].index = u;
+                }
+                if (pl->plan == ORACLE_PLAN_RATIO) k_p = m == 0 ? 0 : clamp_i(ceil_bp(m, pl->rho_p_bp), 1, m);
+                else k_p = clamp_i(k, 0, m);
+                keep_top(cand, m, k_p, kp);
+
+                /* union with sinks and the recent window, ascending */
+                if (s + k_p + w > max_sel) { rc = -1; break; }
+                for (int64_t j = 0; j < P; ++j)
+                    if (j < s || j >= P - w || kp[j]) ids[n++] = (int32_t)j;
+            }
+            n_selected[row] = (int32_t)n;
+            if (kept_grid) memcpy(kept_grid + row * gs, kg, (size_t)gs);
+            if (kept_chunk) memcpy(kept_chunk + row * cs, kc, (size_t)cs);
+            if (counts) { counts[row * 3] = (int32_t)k_g; counts[row * 3 + 1] = (int32_t)k_c; counts[row * 3 + 2] = (int32_t)k_p; }
+        }
+    }
+    free(probe); free(cand); free(kg); free(kc); free(kp);
+    return rc;
+}
+
+/*
+ * Softmax attention over the valid tokens of the listed pages, one query row
+ * per q head: z_t = sm_scale * q . K_t ; p = exp(z - max z) / sum ; out = sum p_t V_t.
+ * page_ids NULL means every page of the sequence (Full-KV).  weights (may be
+ * NULL) receives the normalised p of row 0 of the batch, q head `weights_head`,
+ * in listed-token order, for the softmax checks.  out fp32 [batch][H_q][d].
+ */
+void oracle_attend(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_pool,
+                   const int32_t *block_table, const int32_t *seq_lens,
+                   const int32_t *page_ids, const int32_t *n_selected, int32_t max_sel,
+                   int32_t batch, const oracle_geom *g, double sm_scale, float *out,
+                   double *weights, int32_t weights_head)
+{
+    const int d = g->head_dim, B = g->page_size, G = g->n_q_heads / g->n_kv_heads;
+    double *z = (double *)malloc(sizeof(double) * (size_t)g->max_pages * B + 8);
+    double *acc = (double *)malloc(sizeof(double) * d);
+    for (int b = 0; b < batch; ++b) {
+        const int64_t L = seq_lens[b], P = ceil_div(L, B);
+        for (int hq = 0; hq < g->n_q_heads; ++hq) {
+            const int h = hq / G;
+            const int64_t row = (int64_t)b * g->n_kv_heads + h;
+            const int64_t n_pages = page_ids ? n_selected[row] : P;
+            const uint16_t *qrow = q + ((int64_t)b * g->n_q_heads + hq) * d;
+            float *o = out + ((int64_t)b * g->n_q_heads + hq) * d;
+            int64_t T = 0;
+            double zmax = -INFINITY;
+            for (int64_t e = 0; e < n_pages; ++e) {
+                const int64_t j = page_ids ? page_ids[row * max_sel + e] : e;
+                const int64_t phys = block_table[(int64_t)b * g->max_pages + j];
+                const int64_t n = (j == P - 1) ? L - j * B : B;
+                for (int t = 0; t < n; ++t) {
+                    double s = 0.0;
+                    for (int i = 0; i < d; ++i) s += bf16_value(qrow[i]) * k_at(k_pool, g, phys, h, t, i);
+                    z[T] = sm_scale * s;
+                    if (z[T] > zmax) zmax = z[T];
+                    ++T;
+                }
+            }
+            double denom = 0.0;
+            for (int64_t t = 0; t < T; ++t) { z[t] = exp(z[t] - zmax); denom += z[t]; }
+            for (int i = 0; i < d; ++i) acc[i] = 0.0;
+            T = 0;
+            for (int64_t e = 0; e < n_pages; ++e) {
+                const int64_t j = page_ids ? page_ids[row * max_sel + e] : e;
+                const int64_t phys = block_table[(int64_t)b * g->max_pages + j];
+                const int64_t n = (j == P - 1) ? L - j * B : B;
+                for (int t = 0; t < n; ++t) {
+                    const double p = z[T] / denom;
+                    if (weights && b == 0 && hq == weights_head) weights[T] = p;
+                    for (int i = 0; i < d; ++i) acc[i] += p * v_at(v_pool, g, phys, h, t, i);
+                    ++T;
+                }
+            }
+            for (int i = 0; i < d; ++i) o[i] = (T > 0) ? (float)acc[i] : 0.0f;
+        }
+    }
+    free(z); free(acc);
+}
