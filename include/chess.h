@@ -1,0 +1,164 @@
+/*
+ * libchess -- the decode-step hot path of CHESS (context-aware hierarchical KV selection,
+ * arxiv 2602.20732) for AMD MI355X (gfx950): per-page key summaries over a paged bf16 KV cache,
+ * probe-against-summary scoring, Grid -> Chunk -> Page top-k page selection that always keeps
+ * sink and recent-window pages, and block-sparse decode attention that reads the selected pages
+ * in place (no KV copy, only page indices change: Sec. 1, Sec. 4.1, App. B "Zero-Copy Logic").
+ *
+ * C ABI.  Every data pointer is a DEVICE pointer owned by the caller unless it says "host".
+ * The library never allocates or frees device memory; K/V pools are read-only.  Every call is
+ * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream), does no
+ * host synchronisation, and can be captured in a HIP graph.
+ *
+ * Return value: 0 on success, a negative CHESS_E* code on misuse the host can detect (null
+ * pointers, shapes outside the configuration).  Data the host cannot see (sequence lengths,
+ * block-table entries) is trusted: block-table entries of existing pages must be valid physical
+ * page numbers.  A sequence of length 0 is defined: n_selected = 0, out = 0.
+ *
+ * Layouts (one layer; d = head_dim = 128, B = page_size, H = n_kv_heads, G = n_q_heads / H):
+ *   K pool       bf16 [physical page][H][B][d]
+ *   V pool       bf16 [physical page][H][d][B]        (token-minor inside a page)
+ *   block table  int32 [batch][max_pages_per_seq]     logical page -> physical page
+ *   seq_lens     int32 [batch]                        tokens in each sequence
+ *   q            bf16 [batch][n_q_heads][d]           q head hq belongs to KV head hq / G
+ *   summaries    fp32, three arrays in one buffer (byte offsets from chess_summary_layout):
+ *                  pages  [batch][H][max_pages_per_seq][d]
+ *                  chunks [batch][H][ceil(max_pages_per_seq / N_c)][d]
+ *                  grids  [batch][H][ceil(max_chunks / N_g)][d]       all in logical order
+ *   page_ids     int32 [batch][H][max_selected_pages] logical page numbers, ascending, -1 padded
+ *   n_selected   int32 [batch][H]
+ *   out          fp32 [batch][n_q_heads][d]
+ */
+#ifndef CHESS_H
+#define CHESS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHESS_OK        0
+#define CHESS_EINVAL   (-1)  /* null pointer, bad shape, size outside the configuration       */
+#define CHESS_ENOTSUP  (-2)  /* valid request this build cannot serve (e.g. too many candidates for LDS) */
+#define CHESS_EHIP     (-3)  /* the HIP runtime reported an error at launch                   */
+#define CHESS_ENOMEM   (-4)  /* host allocation of the context failed                         */
+
+/* How the per-level keep-counts of the cascade are derived (Sec. 3.2; Alg. 1 stage 2). */
+#define CHESS_PLAN_BUDGET 0  /* page budget k; chunk / grid counts from oversampling factors  */
+#define CHESS_PLAN_RATIO  1  /* the paper's retention ratios rho_g, rho_c, rho_p              */
+#define CHESS_PLAN_FLAT   2  /* keep every grid and chunk: plain top-k over pages             */
+
+typedef struct chess_ctx chess_ctx; /* opaque; small host-side state only */
+
+typedef struct {
+    int32_t n_q_heads;          /* multiple of n_kv_heads, group size G <= 16               */
+    int32_t n_kv_heads;
+    int32_t head_dim;           /* must be 128                                               */
+    int32_t page_size;          /* B: 16 or 32 tokens (Sec. 4.3 uses 16, Sec. 5.1 uses 32)   */
+    int32_t pages_per_chunk;    /* N_c (Sec. 3.1)                                            */
+    int32_t chunks_per_grid;    /* N_g (Sec. 3.1); N_c * N_g <= 256                          */
+    int32_t max_batch;
+    int32_t max_pages_per_seq;  /* row stride of the block table and of the page summaries   */
+    int32_t max_selected_pages; /* row stride of page_ids                                    */
+    float   sm_scale;           /* softmax scale; 0 means 1 / sqrt(head_dim)                 */
+} chess_config;
+
+typedef struct {
+    int32_t plan;               /* CHESS_PLAN_*                                              */
+    int32_t sink_pages;         /* s: pages [0, s) are always kept (Sec. 3.2, attention sinks) */
+    int32_t window_pages;       /* w: the last w pages are always kept (recent window)       */
+    int32_t budget_pages;       /* > 0: page budget k for every sequence                     */
+    int32_t budget_bp;          /* else k = max(1, ceil(P * budget_bp / 10000)), P = pages of the sequence */
+    int32_t over_chunk;         /* PLAN_BUDGET: keep ceil(over_chunk * k / N_c) chunks       */
+    int32_t over_grid;          /* PLAN_BUDGET: keep ceil(over_grid * that / N_g) grids      */
+    int32_t rho_g_bp;           /* PLAN_RATIO: ratios in basis points; a level keeps         */
+    int32_t rho_c_bp;           /*   clamp(ceil(n * rho), 1, n) of its n active units        */
+    int32_t rho_p_bp;
+} chess_select_plan;
+
+/* Create / destroy the host-side context.  `cfg` is a host pointer and is copied.  Queries the
+ * current HIP device once (LDS per workgroup, CU count).  CHESS_EINVAL on an unsupported shape. */
+int chess_create(const chess_config* cfg, chess_ctx** out);
+void chess_destroy(chess_ctx* ctx);
+
+/* Size in bytes of the summaries buffer (for max_batch sequences) the caller must allocate, and
+ * the byte offsets of its three level arrays. */
+int chess_summary_bytes(const chess_ctx* ctx, size_t* bytes);
+int chess_summary_layout(const chess_ctx* ctx, size_t* page_off, size_t* chunk_off, size_t* grid_off);
+
+/* Size in bytes of the decode workspace (split partials), 256-byte aligned allocation expected.
+ * Contents need no initialisation and carry nothing between calls. */
+int chess_workspace_bytes(const chess_ctx* ctx, size_t* bytes);
+
+/*
+ * Hierarchical summaries (Sec. 3.1).  Page vector = mean of the page's key rows (Eq. 1, per KV
+ * head of this layer); chunk / grid vector = mean of the child vectors that exist (Eq. 2).  A
+ * partial tail page is averaged over its own tokens.  Accumulation is fp64 in index order, one
+ * rounding to fp32 per stored vector.
+ * from_page: device int32 [batch] or NULL.  NULL recomputes everything.  Otherwise only pages
+ * >= from_page[b] and the chunks / grids containing them are recomputed; vectors below that must
+ * be valid from an earlier call on the same prefix.
+ */
+int chess_summarize(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                    int32_t batch, const int32_t* from_page, void* summaries, void* stream);
+
+/* The per-decode-step refresh: chess_summarize with from_page[b] = (pages of sequence b) - 1,
+ * i.e. the tail page and its chunk and grid, launched on batch * H workgroups only. */
+int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                         int32_t batch, void* summaries, void* stream);
+
+/*
+ * Coarse-to-fine selection (Sec. 3.2, Eq. 4, Alg. 1).  Per (sequence, KV head): the probe is the
+ * sum of the group's G query rows; a unit's score is probe . unit vector (fp64).  Level 1 keeps
+ * the top k_g grids; level 2 ranks only chunks of kept grids and keeps k_c; level 3 ranks only
+ * pages of kept chunks that are neither sink nor window pages and keeps k_p.  Rank order: score
+ * descending, then index ascending.  Result: sinks, kept pages, window pages as one ascending
+ * list of logical page numbers; if the sequence has at most s + w pages, all of them.
+ * `plan` is a host pointer.  CHESS_EINVAL if s + w + (largest possible k_p) exceeds
+ * max_selected_pages; CHESS_ENOTSUP if a level can have more candidates than fit in LDS.
+ */
+int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
+                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* stream);
+
+/*
+ * Block-sparse decode attention over the listed pages, read in place (Sec. 4.3 takes a paged
+ * decode kernel over page indices; App. B).  Per q head: softmax(sm_scale * q . K_t) weighted sum
+ * of V_t over the valid tokens of the listed pages.  bf16 inputs, fp32 accumulation, fp32 out.
+ * page_ids entries must be distinct valid logical pages of the sequence.
+ */
+int chess_sparse_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                        const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
+                        const int32_t* n_selected, int32_t batch, float* out, void* workspace, void* stream);
+
+/* The same attention over every page of each sequence: the paper's Full-KV baseline (Sec. 5.1). */
+int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                       const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
+                       void* workspace, void* stream);
+
+/*
+ * Per-kernel device timing for benchmarks.  With timing on, every launch is bracketed by HIP
+ * events on its own stream; chess_kernel_time sums the durations (ms) and launch counts recorded
+ * for kernel `which` since the last reset and synchronises on them.  Not for use under graph capture.
+ */
+#define CHESS_K_SUMMARIZE 0
+#define CHESS_K_SELECT    1
+#define CHESS_K_DECODE    2
+#define CHESS_K_MERGE     3
+#define CHESS_K_COUNT     4
+int chess_timing(chess_ctx* ctx, int32_t enable);          /* enable != 0 turns it on and resets */
+int chess_kernel_time(chess_ctx* ctx, int32_t which, double* total_ms, int64_t* launches);
+
+/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256], waves in
+ * {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
+ * not fit the workspace for max_batch sequences. */
+int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves);
+
+const char* chess_strerror(int code);
+int chess_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHESS_H */

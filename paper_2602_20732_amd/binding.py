@@ -1,0 +1,202 @@
+"""ctypes binding of ``libchess.so``: argument marshalling only.
+
+Every method of :class:`Chess` maps one-to-one onto the C entry point of the same name in
+``include/chess.h``; tensors are passed as raw device pointers and the launch goes onto torch's
+current HIP stream.  There is no fallback: if the library has not been built, loading fails."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
+K_SUMMARIZE, K_SELECT, K_DECODE, K_MERGE = 0, 1, 2, 3
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libchess.so")
+_lib = None
+
+EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes",
+           "chess_summarize", "chess_summarize_tail", "chess_select", "chess_sparse_decode", "chess_dense_decode",
+           "chess_timing", "chess_kernel_time", "chess_debug_force_splits", "chess_strerror", "chess_version"]
+
+
+class ChessError(RuntimeError):
+    pass
+
+
+class _CConfig(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_q_heads", "n_kv_heads", "head_dim", "page_size", "pages_per_chunk", "chunks_per_grid",
+                 "max_batch", "max_pages_per_seq", "max_selected_pages")] + [("sm_scale", ctypes.c_float)]
+
+
+class _CPlan(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("plan", "sink_pages", "window_pages", "budget_pages", "budget_bp", "over_chunk", "over_grid",
+                 "rho_g_bp", "rho_c_bp", "rho_p_bp")]
+
+
+@dataclass(frozen=True)
+class Config:
+    n_q_heads: int
+    n_kv_heads: int
+    page_size: int
+    max_batch: int
+    max_pages_per_seq: int
+    max_selected_pages: int
+    pages_per_chunk: int = 8
+    chunks_per_grid: int = 8
+    head_dim: int = 128
+    sm_scale: float = 0.0
+
+
+@dataclass(frozen=True)
+class SelectPlan:
+    plan: int = PLAN_BUDGET
+    sink_pages: int = 1
+    window_pages: int = 4
+    budget_pages: int = 0
+    budget_bp: int = 100
+    over_chunk: int = 10
+    over_grid: int = 5
+    rho_g_bp: int = 10000
+    rho_c_bp: int = 10000
+    rho_p_bp: int = 10000
+
+    def _c(self) -> _CPlan:
+        return _CPlan(self.plan, self.sink_pages, self.window_pages, self.budget_pages, self.budget_bp,
+                      self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load the built library; raises if it is missing (build it with ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ChessError(f"{_LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+        lib.chess_create.argtypes = [ctypes.POINTER(_CConfig), ctypes.POINTER(vp)]
+        lib.chess_destroy.argtypes = [vp]
+        lib.chess_destroy.restype = None
+        lib.chess_summary_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.chess_summary_layout.argtypes = [vp] + [ctypes.POINTER(ctypes.c_size_t)] * 3
+        lib.chess_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
+        lib.chess_summarize.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, i32p, vp, vp]
+        lib.chess_summarize_tail.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, vp, vp]
+        lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp]
+        lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
+        lib.chess_dense_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp, vp, vp]
+        lib.chess_timing.argtypes = [vp, ctypes.c_int32]
+        lib.chess_kernel_time.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
+        lib.chess_strerror.argtypes = [ctypes.c_int]
+        lib.chess_strerror.restype = ctypes.c_char_p
+        lib.chess_version.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Chess:
+    """One configured instance of the library (one layer's shapes).  Methods launch asynchronously on the
+    current torch stream and return nothing; outputs are the tensors passed in."""
+
+    def __init__(self, cfg: Config):
+        self.lib = load_library()
+        self.cfg = cfg
+        c = _CConfig(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_size, cfg.pages_per_chunk,
+                     cfg.chunks_per_grid, cfg.max_batch, cfg.max_pages_per_seq, cfg.max_selected_pages, cfg.sm_scale)
+        h = ctypes.c_void_p()
+        self._check(self.lib.chess_create(ctypes.byref(c), ctypes.byref(h)))
+        self._h = h
+        n = ctypes.c_size_t()
+        self._check(self.lib.chess_summary_bytes(h, ctypes.byref(n)))
+        self.summary_bytes = n.value
+        self._check(self.lib.chess_workspace_bytes(h, ctypes.byref(n)))
+        self.workspace_bytes = n.value
+        a, b, c3 = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+        self._check(self.lib.chess_summary_layout(h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c3)))
+        self.summary_offsets = (a.value, b.value, c3.value)
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.lib.chess_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != 0:
+            raise ChessError(f"libchess error {rc}: {self.lib.chess_strerror(rc).decode()}")
+
+    # ---- buffers the caller owns (torch is only the allocator here)
+    def new_summaries(self, device="cuda") -> torch.Tensor:
+        return torch.zeros(self.summary_bytes, dtype=torch.uint8, device=device)
+
+    def new_workspace(self, device="cuda") -> torch.Tensor:
+        return torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+
+    def summary_views(self, summaries: torch.Tensor):
+        """(pages, chunks, grids) fp32 views [max_batch, H_kv, units, d] of a summaries buffer."""
+        c = self.cfg
+        mc = -(-c.max_pages_per_seq // c.pages_per_chunk)
+        mg = -(-mc // c.chunks_per_grid)
+        out = []
+        for off, units in zip(self.summary_offsets, (c.max_pages_per_seq, mc, mg)):
+            n = c.max_batch * c.n_kv_heads * units * c.head_dim
+            out.append(summaries[off:off + 4 * n].view(torch.float32).view(c.max_batch, c.n_kv_heads, units, c.head_dim))
+        return tuple(out)
+
+    # ---- the C entry points
+    def summarize(self, k_pool, block_table, seq_lens, summaries, from_page=None):
+        self._check(self.lib.chess_summarize(self._h, _ptr(k_pool), _ptr(block_table), _ptr(seq_lens),
+                                             seq_lens.shape[0], _ptr(from_page), _ptr(summaries), _stream()))
+
+    def summarize_tail(self, k_pool, block_table, seq_lens, summaries):
+        self._check(self.lib.chess_summarize_tail(self._h, _ptr(k_pool), _ptr(block_table), _ptr(seq_lens),
+                                                  seq_lens.shape[0], _ptr(summaries), _stream()))
+
+    def select(self, q, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected):
+        p = plan._c()
+        self._check(self.lib.chess_select(self._h, _ptr(q), _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0],
+                                          ctypes.byref(p), _ptr(page_ids), _ptr(n_selected), _stream()))
+
+    def sparse_decode(self, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, out, workspace):
+        self._check(self.lib.chess_sparse_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                                 _ptr(seq_lens), _ptr(page_ids), _ptr(n_selected), seq_lens.shape[0],
+                                                 _ptr(out), _ptr(workspace), _stream()))
+
+    def dense_decode(self, q, k_pool, v_pool, block_table, seq_lens, out, workspace):
+        self._check(self.lib.chess_dense_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                                _ptr(seq_lens), seq_lens.shape[0], _ptr(out), _ptr(workspace), _stream()))
+
+    def debug_force_splits(self, n_splits: int, waves: int = 4):
+        self._check(self.lib.chess_debug_force_splits(self._h, n_splits, waves))
+
+    def timing(self, enable: bool):
+        self._check(self.lib.chess_timing(self._h, 1 if enable else 0))
+
+    def kernel_time(self, which: int):
+        """(total ms, launches) recorded for kernel ``which`` since timing was last switched on."""
+        ms, n = ctypes.c_double(), ctypes.c_int64()
+        self._check(self.lib.chess_kernel_time(self._h, which, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value

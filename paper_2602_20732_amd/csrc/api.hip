@@ -1,0 +1,303 @@
+// The C ABI of libchess: argument checks, buffer sizing and launch-shape decisions on the host;
+// every step of the path itself runs in the kernels of summarize.hip, select.hip and decode.hip.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <initializer_list>
+#include <new>
+
+#include "chess_internal.h"
+
+namespace {
+
+using chess::kHeadDim;
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t ceil_bp(int64_t n, int64_t bp) { return (n * bp + 9999) / 10000; }
+inline int64_t clampi(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : (x > hi ? hi : x); }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Largest keep-counts any sequence of at most max_pages pages can reach under `pl`.
+struct Bounds { int64_t kg, kc, kp, slots, lists; };
+
+bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
+{
+    const chess::Geom& g = ctx->geom;
+    const int64_t P = g.max_pages, nc = g.max_chunks, ng = g.max_grids;
+    if (pl->sink_pages < 0 || pl->window_pages < 0) return false;
+    const int64_t cand = std::max<int64_t>(0, P - pl->sink_pages - pl->window_pages);   // pages that may compete
+    int64_t kmax = 0;
+    if (pl->plan != CHESS_PLAN_RATIO) {
+        if (pl->budget_pages < 0 || (pl->budget_pages == 0 && (pl->budget_bp < 1 || pl->budget_bp > 10000))) return false;
+        kmax = pl->budget_pages > 0 ? pl->budget_pages : clampi(ceil_bp(P, pl->budget_bp), 1, P);
+    }
+    Bounds b{};
+    switch (pl->plan) {
+    case CHESS_PLAN_BUDGET: {
+        if (pl->over_chunk < 1 || pl->over_grid < 1) return false;
+        const int64_t kct = cdiv((int64_t)pl->over_chunk * kmax, g.n_c);
+        b.kg = std::min<int64_t>(ng, cdiv((int64_t)pl->over_grid * kct, g.n_g));
+        b.kc = std::min<int64_t>(std::min<int64_t>(nc, kct), b.kg * g.n_g);
+        b.kp = std::min<int64_t>(kmax, std::min<int64_t>(cand, b.kc * g.n_c));
+        break;
+    }
+    case CHESS_PLAN_RATIO: {
+        for (int32_t r : {pl->rho_g_bp, pl->rho_c_bp, pl->rho_p_bp})
+            if (r < 1 || r > 10000) return false;
+        b.kg = clampi(ceil_bp(ng, pl->rho_g_bp), 1, ng);
+        b.kc = clampi(ceil_bp(std::min<int64_t>(nc, b.kg * g.n_g), pl->rho_c_bp), 1, nc);
+        b.kp = cand == 0 ? 0 : clampi(ceil_bp(std::min<int64_t>(cand, b.kc * g.n_c), pl->rho_p_bp), 1, cand);
+        break;
+    }
+    case CHESS_PLAN_FLAT:
+        b.kg = ng; b.kc = nc; b.kp = std::min<int64_t>(kmax, cand);
+        break;
+    default:
+        return false;
+    }
+    b.slots = std::max<int64_t>(ng, std::max<int64_t>(b.kg * g.n_g, b.kc * g.n_c));
+    b.lists = std::max<int64_t>(b.kg, b.kc);
+    *out = b;
+    return true;
+}
+
+struct SplitShape { int n_splits, waves; };
+
+// Split-K shape: enough workgroups to cover the chip a few times over, never more splits than
+// there are tiles; small problems drop to one wave per workgroup so that tiles spread over more CUs.
+SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages)
+{
+    const chess::Geom& g = ctx->geom;
+    const int ppt = chess::kTileTokens / g.page_size;
+    const int64_t tiles = std::max<int64_t>(1, cdiv(max_list_pages, ppt));
+    const int64_t pairs = (int64_t)batch * g.n_kv_heads;
+    const int64_t target = 4LL * ctx->n_cu;
+    if (ctx->force_splits > 0) return {ctx->force_splits, ctx->force_waves};
+    int waves = 4;
+    if (pairs * cdiv(tiles, 4) < 2LL * ctx->n_cu) waves = 1;
+    int64_t ns = clampi(cdiv(target, pairs), 1, cdiv(tiles, waves));
+    ns = std::min<int64_t>(ns, ctx->max_splits);
+    while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
+    return {(int)ns, waves};
+}
+
+int decode_common(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool, const int32_t* block_table,
+                  const int32_t* seq_lens, const int32_t* page_ids, const int32_t* n_selected, int32_t batch,
+                  float* out, void* workspace, void* stream)
+{
+    if (!ctx || !q || !k_pool || !v_pool || !block_table || !seq_lens || !out || !workspace) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(q) |
+         reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace)) & 15) return CHESS_EINVAL;
+    const SplitShape sh = choose_splits(ctx, batch, page_ids ? ctx->geom.max_sel : ctx->geom.max_pages);
+    float* ws_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_acc_off);
+    float* ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_ml_off);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = chess::launch_decode(ctx, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_pool),
+                                        static_cast<const uint16_t*>(v_pool), block_table, seq_lens, page_ids,
+                                        n_selected, batch, sh.n_splits, sh.waves, out, ws_acc, ws_ml, s);
+    if (e == hipSuccess && sh.n_splits > 1) e = chess::launch_merge(ctx, batch, sh.n_splits, ws_acc, ws_ml, out, s);
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int chess_create(const chess_config* cfg, chess_ctx** out)
+{
+    if (!cfg || !out) return CHESS_EINVAL;
+    *out = nullptr;
+    if (cfg->head_dim != kHeadDim) return CHESS_EINVAL;
+    if (cfg->page_size != 16 && cfg->page_size != 32) return CHESS_EINVAL;
+    if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads) return CHESS_EINVAL;
+    if (cfg->n_q_heads / cfg->n_kv_heads > chess::kMaxGroup) return CHESS_EINVAL;
+    if (cfg->pages_per_chunk < 1 || cfg->chunks_per_grid < 1 ||
+        (int64_t)cfg->pages_per_chunk * cfg->chunks_per_grid > 256) return CHESS_EINVAL;
+    if (cfg->max_batch < 1 || cfg->max_pages_per_seq < 1 || cfg->max_selected_pages < 1) return CHESS_EINVAL;
+    if (cfg->max_selected_pages > cfg->max_pages_per_seq) return CHESS_EINVAL;
+    if (!(cfg->sm_scale >= 0.f) || !std::isfinite(cfg->sm_scale)) return CHESS_EINVAL;
+
+    chess_ctx* c = new (std::nothrow) chess_ctx();
+    if (!c) return CHESS_ENOMEM;
+    c->cfg = *cfg;
+    chess::Geom& g = c->geom;
+    g.n_q_heads = cfg->n_q_heads; g.n_kv_heads = cfg->n_kv_heads; g.group = cfg->n_q_heads / cfg->n_kv_heads;
+    g.page_size = cfg->page_size; g.n_c = cfg->pages_per_chunk; g.n_g = cfg->chunks_per_grid;
+    g.max_pages = cfg->max_pages_per_seq;
+    g.max_chunks = (int32_t)cdiv(g.max_pages, g.n_c);
+    g.max_grids = (int32_t)cdiv(g.max_chunks, g.n_g);
+    g.max_sel = cfg->max_selected_pages;
+    c->sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / std::sqrt((float)kHeadDim);
+
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { delete c; return CHESS_EHIP; }
+    c->device = dev;
+    c->n_cu = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0 ? v : 256;
+    c->lds_per_block = hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess && v > 0 ? v : 65536;
+
+    const size_t rows = (size_t)cfg->max_batch * g.n_kv_heads;
+    const size_t vec = kHeadDim * sizeof(float);
+    c->page_off = 0;
+    c->chunk_off = align_up(c->page_off + rows * g.max_pages * vec, 256);
+    c->grid_off = align_up(c->chunk_off + rows * g.max_chunks * vec, 256);
+    c->summary_bytes = align_up(c->grid_off + rows * g.max_grids * vec, 256);
+
+    c->max_splits = 256;
+    const size_t part_rows = (size_t)(4 * c->n_cu + rows) * g.group;       // see choose_splits
+    c->ws_acc_off = 0;
+    c->ws_ml_off = align_up(part_rows * vec, 256);
+    c->workspace_bytes = align_up(c->ws_ml_off + part_rows * 2 * sizeof(float), 256);
+    c->timing = false;
+    c->force_splits = 0;
+    c->force_waves = 4;
+    *out = c;
+    return CHESS_OK;
+}
+
+void chess_destroy(chess_ctx* ctx)
+{
+    if (!ctx) return;
+    for (auto& t : ctx->timers)
+        if (t.ready)
+            for (int i = 0; i < chess::KernelTimer::kRing; ++i) { (void)hipEventDestroy(t.start[i]); (void)hipEventDestroy(t.stop[i]); }
+    delete ctx;
+}
+
+int chess_summary_bytes(const chess_ctx* ctx, size_t* bytes)
+{
+    if (!ctx || !bytes) return CHESS_EINVAL;
+    *bytes = ctx->summary_bytes;
+    return CHESS_OK;
+}
+
+int chess_summary_layout(const chess_ctx* ctx, size_t* page_off, size_t* chunk_off, size_t* grid_off)
+{
+    if (!ctx || !page_off || !chunk_off || !grid_off) return CHESS_EINVAL;
+    *page_off = ctx->page_off; *chunk_off = ctx->chunk_off; *grid_off = ctx->grid_off;
+    return CHESS_OK;
+}
+
+int chess_workspace_bytes(const chess_ctx* ctx, size_t* bytes)
+{
+    if (!ctx || !bytes) return CHESS_EINVAL;
+    *bytes = ctx->workspace_bytes;
+    return CHESS_OK;
+}
+
+static int summarize_common(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                            int32_t batch, const int32_t* from_page, bool tail, void* summaries, void* stream)
+{
+    if (!ctx || !k_pool || !block_table || !seq_lens || !summaries) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(summaries)) & 15) return CHESS_EINVAL;
+    char* sb = static_cast<char*>(summaries);
+    hipError_t e = chess::launch_summarize(ctx, static_cast<const uint16_t*>(k_pool), block_table, seq_lens, batch,
+                                           from_page, tail, reinterpret_cast<float*>(sb + ctx->page_off),
+                                           reinterpret_cast<float*>(sb + ctx->chunk_off),
+                                           reinterpret_cast<float*>(sb + ctx->grid_off), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_summarize(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                    int32_t batch, const int32_t* from_page, void* summaries, void* stream)
+{
+    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, from_page, false, summaries, stream);
+}
+
+int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                         int32_t batch, void* summaries, void* stream)
+{
+    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, nullptr, true, summaries, stream);
+}
+
+int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
+                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* stream)
+{
+    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries)) & 15) return CHESS_EINVAL;
+    Bounds bd;
+    if (!plan_bounds(ctx, plan, &bd)) return CHESS_EINVAL;
+    if ((int64_t)plan->sink_pages + plan->window_pages + bd.kp > ctx->geom.max_sel) return CHESS_EINVAL;
+
+    chess::SelectParams sp{};
+    sp.plan = plan->plan; sp.sink = plan->sink_pages; sp.window = plan->window_pages;
+    sp.budget_pages = plan->budget_pages; sp.budget_bp = plan->budget_bp;
+    sp.over_chunk = plan->over_chunk; sp.over_grid = plan->over_grid;
+    sp.rho_g_bp = plan->rho_g_bp; sp.rho_c_bp = plan->rho_c_bp; sp.rho_p_bp = plan->rho_p_bp;
+    sp.slot_cap = (int32_t)bd.slots;
+    sp.list_cap = (int32_t)align_up((size_t)bd.lists, 2);
+    const size_t lds = (size_t)sp.slot_cap * 8 + (size_t)sp.list_cap * 2 * 4;
+    if (lds + 2048 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+
+    const char* sb = static_cast<const char*>(summaries);
+    hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
+                                        reinterpret_cast<const float*>(sb + ctx->page_off),
+                                        reinterpret_cast<const float*>(sb + ctx->chunk_off),
+                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, sp, lds,
+                                        page_ids, n_selected, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_sparse_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                        const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
+                        const int32_t* n_selected, int32_t batch, float* out, void* workspace, void* stream)
+{
+    if (!page_ids || !n_selected) return CHESS_EINVAL;
+    return decode_common(ctx, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, batch, out, workspace, stream);
+}
+
+int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                       const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
+                       void* workspace, void* stream)
+{
+    return decode_common(ctx, q, k_pool, v_pool, block_table, seq_lens, nullptr, nullptr, batch, out, workspace, stream);
+}
+
+int chess_timing(chess_ctx* ctx, int32_t enable)
+{
+    if (!ctx) return CHESS_EINVAL;
+    for (auto& t : ctx->timers) {
+        if (chess::drain_timer(t) != hipSuccess) return CHESS_EHIP;
+        t.total_ms = 0.0;
+        t.launches = 0;
+    }
+    ctx->timing = enable != 0;
+    return CHESS_OK;
+}
+
+int chess_kernel_time(chess_ctx* ctx, int32_t which, double* total_ms, int64_t* launches)
+{
+    if (!ctx || which < 0 || which >= CHESS_K_COUNT || !total_ms || !launches) return CHESS_EINVAL;
+    if (chess::drain_timer(ctx->timers[which]) != hipSuccess) return CHESS_EHIP;
+    *total_ms = ctx->timers[which].total_ms;
+    *launches = ctx->timers[which].launches;
+    return CHESS_OK;
+}
+
+int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves)
+{
+    if (!ctx || n_splits < 0 || n_splits > ctx->max_splits || (waves != 1 && waves != 4)) return CHESS_EINVAL;
+    const int64_t rows = (int64_t)ctx->cfg.max_batch * ctx->geom.n_kv_heads;
+    if (rows * n_splits > 4LL * ctx->n_cu + rows) return CHESS_EINVAL;
+    ctx->force_splits = n_splits;
+    ctx->force_waves = waves;
+    return CHESS_OK;
+}
+
+const char* chess_strerror(int code)
+{
+    switch (code) {
+    case CHESS_OK: return "ok";
+    case CHESS_EINVAL: return "invalid argument (null pointer, misaligned buffer, or shape outside the configuration)";
+    case CHESS_ENOTSUP: return "not supported (a selection level would have more candidates than fit in LDS)";
+    case CHESS_EHIP: return "HIP runtime error at kernel launch";
+    case CHESS_ENOMEM: return "out of host memory";
+    default: return "unknown error code";
+    }
+}
+
+int chess_version(void) { return 1; }
+
+}  // extern "C"

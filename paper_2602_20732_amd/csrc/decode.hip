@@ -1,0 +1,256 @@
+// Paged decode attention over a list of pages read in place (sparse: the selected page ids;
+// dense: every page), split-K with an online-softmax merge.
+//
+// Work unit: one wave, one tile of 32 tokens (two 16-token pages or one 32-token page), all G <= 16
+// query heads of the KV head at once, so both products are dense 16 x 16 x 32 bf16 MFMA tiles:
+//   S^T[token][head] = K[token][d] . Q^T[d][head]      4 MFMA per 16 tokens (d = 128)
+//   O^T[d][head]    += V^T[d][token] . P[token][head]   8 MFMA per tile and per half of P
+// K rows ([token][d], d contiguous) and V rows ([d][token], tokens contiguous) are both contiguous
+// along the contraction index, so every lane feeds its MFMA operands with plain 128-bit global
+// loads -- no LDS staging and no transpose.  The 16 token rows of the two K products are chosen so
+// that the 8 softmax weights a lane ends up holding are exactly the 8 contraction slots it must
+// supply to the P.V product: the weights never move between lanes.
+// P is split into a bf16 head and a bf16 remainder (two MFMAs), which keeps the weights to ~2^-17
+// relative; the row sum l uses the fp32 weights.
+//
+// Softmax state (m, l) of head j lives in the four lanes with lane % 16 == j; O^T accumulators are
+// 8 x float4 per lane.  Waves of a workgroup take tiles round-robin and are merged through LDS;
+// splits are merged by merge_kernel (skipped when there is a single split).
+#include "chess_internal.h"
+
+namespace chess {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr float kNegBig = -1.0e30f;     // "no token yet" running maximum (log2 domain), finite on purpose
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <int B>
+struct Tile {
+    uint4 k[2][4];      // [product c][d step]
+    uint4 v[8];         // [16-row block of d]
+    int ntok[32 / B];   // valid tokens of each page slot of the tile (0 = slot unused)
+};
+
+template <int B>
+__device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const int32_t* ids, const int32_t* bt_row,
+                                          const uint16_t* k_pool, const uint16_t* v_pool, int H, int h, int L, int P,
+                                          int m16, int grp)
+{
+    constexpr int PPT = 32 / B;
+    int64_t phys[PPT];
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) {
+        const int idx = t * PPT + s;
+        const bool ok = idx < n_pages;
+        const int use = ok ? idx : t * PPT;                       // unused slot: alias the tile's first page
+        int lp = ids ? ids[use] : use;
+        lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
+        phys[s] = __builtin_amdgcn_readfirstlane(bt_row[lp]);
+        tl.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
+    }
+    // K: row m16 of product c is token T = 8*(m16/4) + 4*c + m16%4 of the tile
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int T = 8 * (m16 >> 2) + 4 * c + (m16 & 3);
+        const int slot = T / B, tok = T % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint4* src = reinterpret_cast<const uint4*>(k_pool + ((pg * H + h) * B + tok) * kHeadDim) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) tl.k[c][st] = src[st * 4];  // d = 32*st + 8*grp
+    }
+    // V^T: row d = 16*blk + m16, tokens 8*grp .. 8*grp+7 of the tile
+    {
+        const int T0 = 8 * grp;
+        const int slot = T0 / B, tok0 = T0 % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint16_t* base = v_pool + ((pg * H + h) * kHeadDim + m16) * B + tok0;
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) tl.v[blk] = *reinterpret_cast<const uint4*>(base + (size_t)blk * 16 * B);
+    }
+}
+
+template <int B, int NW>
+__global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restrict__ q,
+                                                         const uint16_t* __restrict__ k_pool,
+                                                         const uint16_t* __restrict__ v_pool,
+                                                         const int32_t* __restrict__ block_table,
+                                                         const int32_t* __restrict__ seq_lens,
+                                                         const int32_t* __restrict__ page_ids,
+                                                         const int32_t* __restrict__ n_selected, Geom g,
+                                                         float scale_log2, int n_splits, float* __restrict__ out,
+                                                         float* __restrict__ ws_acc, float* __restrict__ ws_ml)
+{
+    constexpr int PPT = 32 / B;
+    __shared__ float lds_o[NW][kMaxGroup][kHeadDim];
+    __shared__ float lds_m[NW][kMaxGroup], lds_l[NW][kMaxGroup];
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m16 = lane & 15, grp = lane >> 4;
+    const int G = g.group, H = g.n_kv_heads;
+    const int L = min(max(seq_lens[b], 0), g.max_pages * B);
+    const int P = (L + B - 1) / B;
+    const size_t row = (size_t)b * H + h;
+    const int n_pages = P == 0 ? 0 : (page_ids ? min(max(n_selected[row], 0), g.max_sel) : P);
+    const int32_t* ids = page_ids ? page_ids + row * g.max_sel : nullptr;
+    const int32_t* bt_row = block_table + (size_t)b * g.max_pages;
+    const int n_tiles = (n_pages + PPT - 1) / PPT;
+    const int per = (n_tiles + n_splits - 1) / n_splits;
+    const int t0 = split * per, t1 = min(n_tiles, t0 + per);
+
+    // Q^T operand: head m16, d = 32*st + 8*grp .. +7; heads >= G are zero columns
+    bf16x8 qop[4];
+    {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        const uint4* src = reinterpret_cast<const uint4*>(q + ((size_t)b * g.n_q_heads + h * G + (m16 < G ? m16 : 0)) * kHeadDim) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) qop[st] = as_bf16x8(m16 < G ? src[st * 4] : z);
+    }
+
+    float m_run = kNegBig, l_run = 0.f;
+    f32x4 o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    Tile<B> cur;
+    int t = t0 + wave;
+    if (t < t1) load_tile<B>(cur, t, n_pages, ids, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+    for (; t < t1; t += NW) {
+        Tile<B> nxt;
+        const bool more = t + NW < t1;
+        if (more) load_tile<B>(nxt, t + NW, n_pages, ids, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+
+        // scores of this lane's head for tokens 8*grp + e, e = 0..7 (c = 0 gives e 0..3, c = 1 gives 4..7)
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.k[0][st]), qop[st], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.k[1][st]), qop[st], s1, 0, 0, 0);
+        }
+        const int slot = (8 * grp) / B, tok0 = (8 * grp) % B;
+        const int nt = PPT == 1 ? cur.ntok[0] : (slot ? cur.ntok[PPT - 1] : cur.ntok[0]);
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = (tok0 + e < nt) ? s0[e] * scale_log2 : -INFINITY;
+            x[4 + e] = (tok0 + 4 + e < nt) ? s1[e] * scale_log2 : -INFINITY;
+        }
+        float tmax = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, x[e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(x[e] - m_new); psum += p[e]; }
+        l_run = l_run * alpha + psum;
+        bf16x8 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const __bf16 hi = (__bf16)p[e];
+            ph[e] = hi;
+            pl[e] = (__bf16)(p[e] - (float)hi);
+        }
+        // a partly filled tile: unused token slots of V may hold anything (NaN included); zero them
+        bool partial = cur.ntok[0] < B;
+        if (PPT > 1) partial = partial || cur.ntok[PPT - 1] < B;
+        if (partial) {
+            uint32_t keep[4];
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd)
+                keep[wd] = ((tok0 + 2 * wd < nt) ? 0x0000ffffu : 0u) | ((tok0 + 2 * wd + 1 < nt) ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int blk = 0; blk < 8; ++blk) {
+                cur.v[blk].x &= keep[0]; cur.v[blk].y &= keep[1]; cur.v[blk].z &= keep[2]; cur.v[blk].w &= keep[3];
+            }
+        }
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) {
+            f32x4 acc = o[blk] * alpha;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.v[blk]), ph, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.v[blk]), pl, acc, 0, 0, 0);
+            o[blk] = acc;
+        }
+        if (more) cur = nxt;
+    }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+
+    // merge the waves of this workgroup through LDS: lane holds O^T[d = 16*blk + 4*grp + r][head m16]
+#pragma unroll
+    for (int blk = 0; blk < 8; ++blk)
+        *reinterpret_cast<f32x4*>(&lds_o[wave][m16][16 * blk + 4 * grp]) = o[blk];
+    if (grp == 0) { lds_m[wave][m16] = m_run; lds_l[wave][m16] = l_run; }
+    __syncthreads();
+
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 64 * NW) {
+        const int head = idx / kHeadDim, d = idx % kHeadDim;
+        float M = lds_m[0][head];
+#pragma unroll
+        for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, lds_m[wv][head]);
+        float acc = 0.f, l = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < NW; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(lds_m[wv][head] - M);
+            acc += lds_o[wv][head][d] * sc;
+            l += lds_l[wv][head] * sc;
+        }
+        if (n_splits == 1) {
+            out[((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d] = l > 0.f ? acc / l : 0.f;
+        } else {
+            const size_t pr = (row * n_splits + split) * G + head;
+            ws_acc[pr * kHeadDim + d] = acc;
+            if (d == 0) { ws_ml[pr * 2] = M; ws_ml[pr * 2 + 1] = l; }
+        }
+    }
+}
+
+// out[b][hq][:] = sum_s acc_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M)
+__global__ __launch_bounds__(kHeadDim) void merge_kernel(const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
+                                                         Geom g, int n_splits, float* __restrict__ out)
+{
+    const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+    const int h = hq / g.group, head = hq % g.group;
+    const size_t row = (size_t)b * g.n_kv_heads + h;
+    float M = kNegBig;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ws_ml[((row * n_splits + s) * g.group + head) * 2]);
+    float acc = 0.f, l = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+        const size_t pr = (row * n_splits + s) * g.group + head;
+        const float sc = __builtin_amdgcn_exp2f(ws_ml[pr * 2] - M);
+        acc += ws_acc[pr * kHeadDim + d] * sc;
+        l += ws_ml[pr * 2 + 1] * sc;
+    }
+    out[((size_t)b * g.n_q_heads + hq) * kHeadDim + d] = l > 0.f ? acc / l : 0.f;
+}
+
+hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
+                         const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
+                         const int32_t* n_selected, int batch, int n_splits, int waves, float* out,
+                         float* ws_acc, float* ws_ml, hipStream_t stream)
+{
+    const Geom& g = ctx->geom;
+    const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
+    const dim3 grid(n_splits, g.n_kv_heads, batch), block(64 * waves);
+    void (*kern)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
+                 const int32_t*, Geom, float, int, float*, float*, float*);
+    if (g.page_size == 16) kern = waves == 4 ? decode_kernel<16, 4> : decode_kernel<16, 1>;
+    else                   kern = waves == 4 ? decode_kernel<32, 4> : decode_kernel<32, 1>;
+    return timed_launch(ctx, CHESS_K_DECODE, kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
+                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml);
+}
+
+hipError_t launch_merge(chess_ctx* ctx, int batch, int n_splits, const float* ws_acc, const float* ws_ml,
+                        float* out, hipStream_t stream)
+{
+    const dim3 grid(ctx->geom.n_q_heads, batch), block(kHeadDim);
+    return timed_launch(ctx, CHESS_K_MERGE, merge_kernel, grid, block, 0, stream, ws_acc, ws_ml, ctx->geom, n_splits, out);
+}
+
+}  // namespace chess

@@ -1,0 +1,213 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element, on the same
+seeded inputs.  Bars: summaries and page lists bit-exact (near-ties under 1e-5 reported separately and not
+expected, both sides score in fp64); attention outputs within 1e-2 max-abs (bf16 inputs, fp32 accumulate).
+Small cases span several tiles and ragged tails; full-size cases run the benchmark's launch shapes."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_20732_amd as pk
+import workload
+from gpu_common import (assert_summaries_equal, classify_selection, config_of, gpu_plan, run_gpu, run_oracle,
+                        to_device)
+from helpers import geom_of, host_arrays, plan_of
+
+pytestmark = pytest.mark.gpu
+
+ATOL = 1e-2          # the stated bar for attention outputs
+ATOL_TIGHT = 2e-3    # what the arithmetic should achieve (bf16 inputs exact, fp32 accumulate, P split in two bf16)
+
+
+def check_all(sp, wl, plan, max_sel=None, dense=True, label=""):
+    max_sel = sp.max_selected if max_sel is None else max_sel
+    lib = pk.Chess(config_of(sp, max_selected=max_sel))
+    gpu = run_gpu(lib, wl, plan, dense=dense)
+    ref = run_oracle(wl, plan, max_sel, dense=dense)
+    sl = ref.host[4]
+    assert_summaries_equal(gpu, ref, sp, sl)
+    hard, near = classify_selection(gpu.ids, gpu.nsel, ref, wl, plan)
+    print(f"[{label}] selection rows: hard mismatches {len(hard)}, near-ties {len(near)}")
+    assert not hard, hard[:3]
+    assert not near, near[:3]
+    assert np.array_equal(gpu.nsel, ref.nsel)
+    err = np.abs(gpu.out - ref.out).max()
+    print(f"[{label}] sparse max|out - oracle| = {err:.3e}")
+    assert np.isfinite(gpu.out).all() and err <= ATOL and err <= ATOL_TIGHT
+    if dense:
+        derr = np.abs(gpu.dense - ref.dense).max()
+        print(f"[{label}] dense  max|out - oracle| = {derr:.3e}")
+        assert np.isfinite(gpu.dense).all() and derr <= ATOL and derr <= ATOL_TIGHT
+    lib.close()
+    return gpu, ref
+
+
+def test_cfg1_full_size():
+    sp = workload.spec("cfg1")
+    wl = workload.generate(sp, workload.default_seed("cfg1"))
+    check_all(sp, wl, plan_of(sp), label="cfg1")
+
+
+RAGGED = workload.WorkloadSpec("ragged", 5, (0, 3000), 8, 2, 16, ("fixed", 128), (2, 2), 1, 2, budget_bp=300,
+                               pages_per_chunk=4, chunks_per_grid=4)
+RAGGED_LENS = [3000, 1237, 641, 16, 0]
+
+
+@pytest.mark.parametrize("plan_kw", [
+    dict(plan=oracle.PLAN_BUDGET),
+    dict(plan=oracle.PLAN_BUDGET, budget_pages=9, over_chunk=2, over_grid=1),
+    dict(plan=oracle.PLAN_RATIO, rho_g_bp=5000, rho_c_bp=2000, rho_p_bp=1000),
+    dict(plan=oracle.PLAN_RATIO, rho_g_bp=8000, rho_c_bp=7000, rho_p_bp=7000),
+    dict(plan=oracle.PLAN_RATIO, rho_g_bp=9000, rho_c_bp=9000, rho_p_bp=9000),
+    dict(plan=oracle.PLAN_FLAT, budget_pages=16),
+    dict(plan=oracle.PLAN_RATIO),                                  # ratios 1,1,1: Full-KV through the sparse path
+])
+def test_ragged_batch_all_plans(plan_kw):
+    """GQA 4, ragged lengths incl. a partial tail page, partial chunk / grid, a one-page and an empty sequence."""
+    sp = RAGGED
+    wl = workload.generate(sp, 77, seq_lens=RAGGED_LENS)
+    check_all(sp, wl, plan_of(sp, **plan_kw), max_sel=sp.max_pages, label=f"ragged {plan_kw}")
+
+
+@pytest.mark.parametrize("nc,ng", [(2, 2), (8, 8), (4, 16), (1, 1), (16, 16)])
+def test_hierarchy_shapes(nc, ng):
+    sp = workload.WorkloadSpec("hier", 2, (500, 5000), 8, 2, 16, ("fixed", 128), (3, 3), 1, 4, budget_bp=200,
+                               pages_per_chunk=nc, chunks_per_grid=ng)
+    wl = workload.generate(sp, 31 + nc, seq_lens=[5000, 2049])
+    check_all(sp, wl, plan_of(sp), dense=False, label=f"hier {nc}x{ng}")
+
+
+def test_page32_gqa7_and_equal_norm_topics():
+    """The stress shape scaled down (page 32, 28 / 4 heads), plus its equal-norm variant (near-tied scores)."""
+    for name in ("cfg5", "cfg5adv"):
+        sp = workload.spec(name, scale=1 / 16)
+        wl = workload.generate(sp, workload.default_seed(name))
+        check_all(sp, wl, plan_of(sp), label=name + "/16")
+
+
+def test_exact_ties_go_to_lowest_index():
+    """All key rows identical: every score ties at every level; uniform softmax -> mean of listed V rows."""
+    sp = workload.WorkloadSpec("ties", 1, (2048, 2048), 4, 1, 16, ("fixed", 128), (1, 1), 1, 2, budget_pages=5,
+                               pages_per_chunk=2, chunks_per_grid=2)
+    wl = workload.generate(sp, 3)
+    row = wl.k_pool[wl.block_table[0, 0].item(), 0, 0].clone()
+    wl.k_pool[:] = row                                   # every token of every page gets the same key row
+    plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=1, window_pages=2, rho_g_bp=5000, rho_c_bp=5000, rho_p_bp=5000)
+    gpu, ref = check_all(sp, wl, plan, max_sel=sp.max_pages, dense=False, label="ties")
+    # 128 pages -> 64 chunks -> 32 grids; keeps grids 0..15, chunks 0..15, candidate pages 1..31 -> 16 lowest
+    assert gpu.ids[0, 0, :gpu.nsel[0, 0]].tolist() == list(range(0, 17)) + [126, 127]
+
+
+def test_short_and_boundary_lengths():
+    sp = workload.WorkloadSpec("short", 8, (0, 161), 4, 2, 16, ("fixed", 32), (1, 1), 2, 3, budget_pages=2,
+                               pages_per_chunk=2, chunks_per_grid=2)
+    wl = workload.generate(sp, 5, seq_lens=[0, 1, 15, 16, 17, 80, 96, 161])
+    check_all(sp, wl, plan_of(sp), label="short")
+
+
+def test_nan_in_unused_slots_is_never_read():
+    """The generator fills unused tail slots and spare pages with NaN; outputs must stay finite (checked in
+    check_all) and must not depend on what the unused slots hold."""
+    sp = workload.WorkloadSpec("nan", 2, (100, 1000), 8, 2, 32, ("fixed", 64), (2, 2), 1, 1, budget_bp=500,
+                               pages_per_chunk=2, chunks_per_grid=4)
+    wl = workload.generate(sp, 9, seq_lens=[1000 - 7, 333])
+    gpu, _ = check_all(sp, wl, plan_of(sp), label="nan")
+    wl.k_pool[wl.k_pool.isnan()] = 123.0
+    wl.v_pool[wl.v_pool.isnan()] = -55.0
+    lib = pk.Chess(config_of(sp))
+    gpu2 = run_gpu(lib, wl, plan_of(sp))
+    assert np.array_equal(gpu.out, gpu2.out) and np.array_equal(gpu.dense, gpu2.dense) and np.array_equal(gpu.ids, gpu2.ids)
+
+
+def test_incremental_and_tail_summaries_match_full_pass():
+    sp = RAGGED
+    lens0 = [2990, 1237, 630, 16, 0]
+    lens1 = [3000, 1239, 641, 17, 3]                      # grows within the page, across pages, from nothing
+    wl = to_device(workload.generate(sp, 77, seq_lens=lens1))
+    lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+    full = lib.new_summaries()
+    lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, full)
+    inc = lib.new_summaries()
+    l0 = torch.tensor(lens0, dtype=torch.int32, device="cuda")
+    lib.summarize(wl.k_pool, wl.block_table, l0, inc)                       # state before the new tokens
+    from_page = torch.tensor([max(0, n - 1) // sp.page_size for n in lens0], dtype=torch.int32, device="cuda")
+    lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, inc, from_page=from_page)
+    torch.cuda.synchronize()
+    B, Nc, Ng = sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    for a, b, per in zip(lib.summary_views(full), lib.summary_views(inc), (1, Nc, Nc * Ng)):
+        for i, L in enumerate(lens1):
+            n = -(-(-(-L // B)) // per)
+            assert torch.equal(a[i, :, :n], b[i, :, :n])
+    # tail refresh: one more token in the tail page of every sequence
+    tail = lib.new_summaries()
+    lm = torch.tensor([max(n - 1, 0) for n in lens1], dtype=torch.int32, device="cuda")   # incl. 16 -> 17: a new page
+    lib.summarize(wl.k_pool, wl.block_table, lm, tail)
+    lib.summarize_tail(wl.k_pool, wl.block_table, wl.seq_lens, tail)
+    torch.cuda.synchronize()
+    for a, b, per in zip(lib.summary_views(full), lib.summary_views(tail), (1, Nc, Nc * Ng)):
+        for i, L in enumerate(lens1):
+            n = -(-(-(-L // B)) // per)
+            assert torch.equal(a[i, :, :n], b[i, :, :n])
+
+
+def test_split_count_invariance_and_determinism():
+    sp = workload.spec("cfg2", scale=1 / 4)
+    wl = to_device(workload.generate(sp, workload.default_seed("cfg2")))
+    lib = pk.Chess(config_of(sp))
+    ws = lib.new_workspace()
+    outs = []
+    for n_splits, waves in ((1, 1), (1, 4), (2, 4), (7, 1), (16, 4), (64, 1), (0, 4)):
+        lib.debug_force_splits(n_splits, waves)
+        out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+        lib.dense_decode(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, out, ws)
+        out2 = torch.full_like(out, float("nan"))
+        lib.dense_decode(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, out2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, out2), "run-to-run bit identity at a fixed split shape"
+        outs.append(out.cpu().numpy())
+    for o in outs[1:]:
+        assert np.abs(o - outs[0]).max() < 1e-5
+    K, V, Q, bt, sl = host_arrays(wl)
+    ref = oracle.attend(Q, K, V, bt, sl, geom_of(sp))
+    assert np.abs(outs[0] - ref).max() <= ATOL_TIGHT
+
+
+def test_zero_copy_pools_untouched_and_placement_invariance():
+    sp = RAGGED
+    wl = workload.generate(sp, 78, seq_lens=RAGGED_LENS)
+    d = to_device(wl)
+    k0, v0 = d.k_pool.clone(), d.v_pool.clone()
+    lib = pk.Chess(config_of(sp))
+    plan = plan_of(sp)
+    a = run_gpu(lib, d, plan)
+    assert torch.equal(d.k_pool.view(torch.int16), k0.view(torch.int16)) and torch.equal(d.v_pool.view(torch.int16), v0.view(torch.int16))
+    perm = torch.randperm(d.k_pool.shape[0], generator=torch.Generator().manual_seed(1)).cuda()
+    k2, v2 = torch.empty_like(d.k_pool), torch.empty_like(d.v_pool)
+    k2[perm], v2[perm] = d.k_pool, d.v_pool
+    bt2 = torch.where(d.block_table >= 0, perm[d.block_table.clamp(min=0).long()].int(), d.block_table)
+    moved = workload.Workload(sp, 78, 0, k2, v2, bt2, d.seq_lens, d.q)
+    b = run_gpu(lib, moved, plan)
+    assert np.array_equal(a.ids, b.ids) and np.array_equal(a.nsel, b.nsel)
+    assert np.array_equal(a.pages, b.pages) and np.abs(a.out - b.out).max() <= 1e-6
+
+
+def test_error_codes():
+    sp = RAGGED
+    lib = pk.Chess(config_of(sp))
+    d = to_device(workload.generate(sp, 77, seq_lens=RAGGED_LENS))
+    summ = lib.new_summaries()
+    ids = torch.zeros((5, 2, sp.max_selected), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((5, 2), dtype=torch.int32, device="cuda")
+    with pytest.raises(pk.ChessError):       # budget + safety pages do not fit max_selected_pages
+        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(budget_pages=sp.max_selected), ids, nsel)
+    with pytest.raises(pk.ChessError):       # unknown plan
+        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(plan=9), ids, nsel)
+    with pytest.raises(pk.ChessError):       # batch beyond max_batch
+        big = torch.zeros(6, dtype=torch.int32, device="cuda")
+        lib.summarize(d.k_pool, d.block_table, big, summ)
+    with pytest.raises(pk.ChessError):
+        pk.Chess(pk.Config(8, 3, 16, 1, 64, 8))          # 8 q heads over 3 kv heads
+    with pytest.raises(pk.ChessError):
+        pk.Chess(pk.Config(8, 2, 24, 1, 64, 8))          # page size
