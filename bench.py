@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the CHESS decode hot path on one MI355X.
+
+A step is one pass of the whole path over one batch: tail-page summary refresh, cascade selection,
+block-sparse decode attention and the split merge, with K/V, summaries and queries already resident
+in HBM.  Consecutive steps rotate over independent KV pools ("layers") and query sets so that the
+bytes a step touches were not touched by the steps just before it (the set cycled through is larger
+than the last-level cache); the K timed steps are captured once as a HIP graph and replayed.
+
+Prints ONE JSON line: the step time in microseconds (the metric), the dominant kernel's HBM roofline
+from per-launch HIP-event durations, the dense full-KV kernel of this library on the same inputs,
+and the CPU oracle timed on the host cores for the same step.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E datasheet bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="cfg4a", choices=["cfg1", "cfg2", "cfg3", "cfg4a", "cfg4b", "cfg5"])
+    ap.add_argument("--pools", type=int, default=0, help="independent KV pools rotated through (0 = auto)")
+    ap.add_argument("--queries", type=int, default=0, help="query sets per pool (0 = auto)")
+    ap.add_argument("--eager", action="store_true", help="launch step by step instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense full-KV comparison")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(sp, seq_lens, nsel, counts):
+    """Bytes the method must move per step (one pool): select = vectors of the units it scores,
+    attention = K and V of the listed pages, summarize = the tail page + the child vectors re-read."""
+    d, B, Nc, Ng = sp.head_dim, sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    sel = 0
+    for b, L in enumerate(seq_lens):
+        P = -(-L // B)
+        ng = -(-(-(-P // Nc)) // Ng)
+        for h in range(sp.n_kv_heads):
+            kg, kc, _ = counts[b][h]
+            sel += (ng + kg * Ng + kc * Nc) * d * 4
+    attn = int(nsel.sum()) * B * d * 2 * 2
+    summ = len(seq_lens) * sp.n_kv_heads * (B * d * 2 + (Nc + Ng + 3) * d * 4)
+    return {"select": sel, "attention": attn, "summarize": summ, "step": sel + attn + summ}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2602_20732_amd as pk
+    import workload
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    sp = workload.spec(args.workload)
+    seed = workload.default_seed(args.workload)
+    pool_bytes = sp.batch * sp.ctx[1] * sp.n_kv_heads * sp.head_dim * 2 * 2
+    n_pools = args.pools or max(2, min(16, int(2.2e9 // pool_bytes)))          # ~2 GB of KV, at least 2 pools
+    n_q = args.queries or max(1, 16 // n_pools)
+
+    t0 = time.time()
+    lens = workload.seq_lengths(sp, seed)
+    pools = []
+    for l in range(n_pools):
+        wl = workload.generate(sp, seed, layer=l, device="cuda", seq_lens=lens)
+        qs = [wl.q] + [workload.extra_queries(wl, v) for v in range(1, n_q)]
+        pools.append((wl, qs))
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    cfg = pk.Config(sp.n_q_heads, sp.n_kv_heads, sp.page_size, sp.batch, sp.max_pages, sp.max_selected,
+                    sp.pages_per_chunk, sp.chunks_per_grid)
+    lib = pk.Chess(cfg)
+    plan = pk.SelectPlan(sink_pages=sp.sink_pages, window_pages=sp.window_pages, budget_pages=sp.budget_pages,
+                         budget_bp=sp.budget_bp)
+    summs = []
+    for wl, _ in pools:                                   # prefill-time full pass, outside the timed region
+        s = lib.new_summaries()
+        lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, s)
+        summs.append(s)
+    ws = lib.new_workspace()
+    ids = torch.empty((sp.batch, sp.n_kv_heads, sp.max_selected), dtype=torch.int32, device="cuda")
+    nsel = torch.empty((sp.batch, sp.n_kv_heads), dtype=torch.int32, device="cuda")
+    out = torch.empty((sp.batch, sp.n_q_heads, sp.head_dim), dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(i):
+        wl, qs = pools[i % n_pools]
+        q = qs[(i // n_pools) % n_q]
+        s = summs[i % n_pools]
+        lib.summarize_tail(wl.k_pool, wl.block_table, wl.seq_lens, s)
+        lib.select(q, s, wl.seq_lens, plan, ids, nsel)
+        lib.sparse_decode(q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out, ws)
+
+    def dense_step(i):
+        wl, qs = pools[i % n_pools]
+        lib.dense_decode(qs[(i // n_pools) % n_q], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, out, ws)
+
+    def timed(fn, steps, warmup, graph):
+        """Time exactly `steps` calls of fn after `warmup` untimed ones; returns ms per step."""
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            for i in range(warmup):
+                fn(i)
+            stream.synchronize()
+            g = None
+            if graph:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for i in range(steps):
+                        fn(warmup + i)
+                g.replay()                                 # untimed: first replay pays graph upload
+                stream.synchronize()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            t_wall = time.perf_counter()
+            e0.record(stream)
+            if g is not None:
+                g.replay()
+            else:
+                for i in range(steps):
+                    fn(warmup + i)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            wall_ms = (time.perf_counter() - t_wall) * 1e3
+        return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
+
+    ms_step, wall_ms_step = timed(step, args.steps, args.warmup, not args.eager)
+
+    # per-kernel durations: every launch bracketed by HIP events on its own stream (eager, separate pass)
+    lib.timing(True)
+    n_prof = min(args.steps, 64)
+    for i in range(n_prof):
+        step(i)
+    torch.cuda.synchronize()
+    kern = {}
+    for name, which in (("summarize_tail", pk.K_SUMMARIZE), ("select", pk.K_SELECT), ("sparse_decode", pk.K_DECODE),
+                        ("merge", pk.K_MERGE)):
+        ms, n = lib.kernel_time(which)
+        kern[name] = {"launches": n, "avg_us": (ms / n * 1e3) if n else None}
+    lib.timing(False)
+
+    # bytes: keep-counts and list lengths of the last profiled step, from the device results
+    nsel_h = nsel.cpu().numpy()
+    B, Nc, Ng = sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    counts = []
+    for b, L in enumerate(lens):
+        P = -(-L // B)
+        k = sp.budget_for(P)
+        kct = -(-plan.over_chunk * k // Nc)
+        nc = -(-P // Nc)
+        kg = min(-(-nc // Ng), -(-plan.over_grid * kct // Ng))
+        counts.append([(kg, min(kct, kg * Ng, nc), k)] * sp.n_kv_heads)
+    ab = algorithmic_bytes(sp, lens, nsel_h, counts)
+    dec_us = kern["sparse_decode"]["avg_us"]
+    achieved = ab["attention"] / (dec_us * 1e-6) / 1e9
+    result = {
+        "metric": "sparse decode attn us/step (tail summarize + select + sparse attention + merge), 1% KV budget",
+        "value": round(ms_step * 1e3, 3), "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 K/V/q, fp32 accumulate, fp64 scores", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": sp.batch, "context": list(sp.ctx), "n_q_heads": sp.n_q_heads,
+                   "n_kv_heads": sp.n_kv_heads, "page_size": sp.page_size, "budget_bp": sp.budget_bp,
+                   "budget_pages": sp.budget_pages, "sink_pages": sp.sink_pages, "window_pages": sp.window_pages,
+                   "pages_per_chunk": Nc, "chunks_per_grid": Ng, "kv_pools_rotated": n_pools,
+                   "query_sets_per_pool": n_q, "launch": "eager" if args.eager else "hip_graph"},
+        "step_gbs": round(ab["step"] / (ms_step * 1e-3) / 1e9, 1),
+        "step_frac_of_hbm_peak": round(ab["step"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "wall_us_per_step": round(wall_ms_step * 1e3, 3),
+        "algorithmic_bytes": ab,
+        "kernels": kern,
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel (sparse)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None},
+        "setup_seconds": round(gen_s, 1),
+    }
+
+    if not args.no_dense:
+        d_steps = max(8, min(args.steps, 32))
+        d_ms, _ = timed(dense_step, d_steps, 2, not args.eager)
+        dense_bytes = sum(-(-L // B) for L in lens) * sp.n_kv_heads * B * sp.head_dim * 4
+        result["dense"] = {"us_per_step": round(d_ms * 1e3, 2), "gbs": round(dense_bytes / (d_ms * 1e-3) / 1e9, 1),
+                           "frac_of_hbm_peak": round(dense_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                           "bytes": dense_bytes, "sparse_speedup": round(d_ms / ms_step, 2)}
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(sp, pools[0][0], plan)
+
+    print(json.dumps(result))
+
+
+def cpu_baseline(sp, wl, plan):
+    """The oracle as it stands, single-threaded, on the host cores: full summarize + select + sparse
+    attention for a bounded sample of the batch (whole sequences), scaled to the batch."""
+    import numpy as np
+
+    import oracle
+    import workload
+
+    n_seq = max(1, min(sp.batch, int(2 ** 21 // max(1, sp.ctx[1]))))      # ~2M tokens of summarize at most
+    geom = oracle.Geometry(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.page_size, sp.pages_per_chunk,
+                           sp.chunks_per_grid, sp.max_pages)
+    oplan = oracle.Plan(sink_pages=plan.sink_pages, window_pages=plan.window_pages, budget_pages=plan.budget_pages,
+                        budget_bp=plan.budget_bp)
+    bt = wl.block_table[:n_seq].cpu()
+    sl = wl.seq_lens[:n_seq].cpu().numpy()
+    # gather the sample's pages into a compact host pool (identity block table)
+    P = [-(-int(n) // sp.page_size) for n in sl]
+    phys = np.concatenate([bt[b, :P[b]].numpy() for b in range(n_seq)])
+    import torch
+    idx = torch.as_tensor(phys, dtype=torch.long, device=wl.k_pool.device)
+    K = workload.bf16_bits(wl.k_pool[idx])
+    V = workload.bf16_bits(wl.v_pool[idx])
+    Q = workload.bf16_bits(wl.q[:n_seq])
+    bt2 = np.full((n_seq, sp.max_pages), -1, np.int32)
+    off = 0
+    for b in range(n_seq):
+        bt2[b, :P[b]] = np.arange(off, off + P[b])
+        off += P[b]
+    oracle.build()
+    t0 = time.perf_counter()
+    pv, cv, gv = oracle.summarize(K, bt2, sl, geom)
+    t1 = time.perf_counter()
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, geom, oplan, sp.max_selected)
+    t2 = time.perf_counter()
+    oracle.attend(Q, K, V, bt2, sl, geom, ids, nsel)
+    t3 = time.perf_counter()
+    scale = sp.batch / n_seq
+    return {"value": round((t3 - t0) * scale * 1e6, 1), "unit": "us/step", "cores": 1, "kind": "oracle",
+            "sample": f"{n_seq} of {sp.batch} sequences, whole step (full-pass summarize {t1 - t0:.2f}s, select "
+                      f"{t2 - t1:.3f}s, sparse attention {t3 - t2:.3f}s), scaled x{scale:g} to the batch; the oracle "
+                      "has no incremental summarize, so its step re-summarizes the whole context",
+            "select_plus_attention_us": round((t3 - t1) * scale * 1e6, 1)}
+
+
+if __name__ == "__main__":
+    main()

@@ -202,6 +202,55 @@ def seq_lengths(sp: WorkloadSpec, seed: int) -> List[int]:
     return [lo + uniform_int(key, b, hi - lo + 1) for b in range(sp.batch)]
 
 
+def _topic_vectors(sp: WorkloadSpec, seed: int, layer: int, b: int, n_seg: int, dev) -> torch.Tensor:
+    """Topic vectors [n_seg][H_kv][d] of sequence b: one per (segment, kv head)."""
+    H, d = sp.n_kv_heads, sp.head_dim
+    tkey = stream_key(seed, STREAM_TOPIC, layer, b)
+    tidx = torch.arange(n_seg * H * d, dtype=torch.int64, device=dev)
+    topics = normal_from_counter(tkey, tidx).view(n_seg, H, d)
+    if sp.equal_norm:
+        topics = topics * (math.sqrt(d) / topics.norm(dim=-1, keepdim=True))
+    return topics
+
+
+def _query_rows(sp: WorkloadSpec, seed: int, layer: int, b: int, variant: int, topics, n_seg: int,
+                q: torch.Tensor, dev) -> List[List[int]]:
+    """Fill q[b]: every q head = sum of its chosen topic vectors (of its KV head) + noise.  ``variant``
+    draws another query for the same keys.  Returns the chosen segment ids per q head."""
+    d, G = sp.head_dim, sp.group
+    pkey = stream_key(seed, STREAM_PICK, layer, b, variant)
+    qkey = stream_key(seed, STREAM_QNOISE, layer, b, variant)
+    picks_b = []
+    for hq in range(sp.n_q_heads):
+        lo, hi = sp.topics_per_q
+        T = lo + uniform_int(pkey, hq * 64, hi - lo + 1)
+        chosen: List[int] = []
+        c = 1
+        while n_seg and len(chosen) < min(T, n_seg):
+            s_id = uniform_int(pkey, hq * 64 + c, n_seg)
+            c += 1
+            if s_id not in chosen:
+                chosen.append(s_id)
+        picks_b.append(chosen)
+        noise = normal_from_counter(qkey, torch.arange(hq * d, (hq + 1) * d, dtype=torch.int64, device=dev))
+        row = noise * sp.noise_std
+        for s_id in chosen:
+            row = row + topics[s_id, hq // G]
+        q[b, hq] = row.to(torch.bfloat16)
+    return picks_b
+
+
+def extra_queries(wl: "Workload", variant: int) -> torch.Tensor:
+    """Another seeded query batch [batch][H_q][d] for the keys of ``wl`` (same recipe, other topic picks)."""
+    sp, dev = wl.spec, wl.k_pool.device
+    q = torch.empty_like(wl.q)
+    for b in range(sp.batch):
+        n_seg = len(wl.segments[b])
+        topics = _topic_vectors(sp, wl.seed, wl.layer, b, n_seg, dev) if n_seg else None
+        _query_rows(sp, wl.seed, wl.layer, b, variant, topics, n_seg, q, dev)
+    return q
+
+
 def generate(sp: WorkloadSpec, seed: int, layer: int = 0, device="cpu", spare_pages: int = 3,
              seq_lens: Optional[List[int]] = None, block_elems: int = 1 << 24) -> Workload:
     """Build one layer's K/V pools, block table, lengths and query for ``sp``."""
@@ -235,33 +284,8 @@ def generate(sp: WorkloadSpec, seed: int, layer: int = 0, device="cpu", spare_pa
         starts = _segment_starts(sp, seed, layer, b, Lb) if Lb > 0 else []
         segments.append(starts)
         n_seg = len(starts)
-        # topic vectors, one per (segment, kv head)
-        if n_seg:
-            tkey = stream_key(seed, STREAM_TOPIC, layer, b)
-            tidx = torch.arange(n_seg * H * d, dtype=torch.int64, device=dev)
-            topics = normal_from_counter(tkey, tidx).view(n_seg, H, d)
-            if sp.equal_norm:
-                topics = topics * (math.sqrt(d) / topics.norm(dim=-1, keepdim=True))
-        # query rows: sum of the chosen topics of the row's KV head + noise
-        pkey = stream_key(seed, STREAM_PICK, layer, b)
-        qkey = stream_key(seed, STREAM_QNOISE, layer, b)
-        picks_b = []
-        for hq in range(sp.n_q_heads):
-            lo, hi = sp.topics_per_q
-            T = lo + uniform_int(pkey, hq * 64, hi - lo + 1)
-            chosen: List[int] = []
-            c = 1
-            while n_seg and len(chosen) < min(T, n_seg):
-                s_id = uniform_int(pkey, hq * 64 + c, n_seg)
-                c += 1
-                if s_id not in chosen:
-                    chosen.append(s_id)
-            picks_b.append(chosen)
-            noise = normal_from_counter(qkey, torch.arange(hq * d, (hq + 1) * d, dtype=torch.int64, device=dev))
-            row = noise * sp.noise_std
-            for s_id in chosen:
-                row = row + topics[s_id, hq // G]
-            q[b, hq] = row.to(torch.bfloat16)
+        topics = _topic_vectors(sp, seed, layer, b, n_seg, dev) if n_seg else None
+        picks_b = _query_rows(sp, seed, layer, b, 0, topics if n_seg else None, n_seg, q, dev)
         q_topics.append(picks_b)
         if Lb == 0:
             continue
