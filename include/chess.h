@@ -88,9 +88,13 @@ void chess_destroy(chess_ctx* ctx);
 int chess_summary_bytes(const chess_ctx* ctx, size_t* bytes);
 int chess_summary_layout(const chess_ctx* ctx, size_t* page_off, size_t* chunk_off, size_t* grid_off);
 
-/* Size in bytes of the decode workspace (split partials), 256-byte aligned allocation expected.
- * Contents need no initialisation and carry nothing between calls. */
+/* Size in bytes of the workspace (split partials of decode, published keys and kept-unit lists of
+ * select, arrival counters); allocate 256-byte aligned.  chess_workspace_init must run once on a
+ * fresh allocation (it clears the arrival counters with a small fill kernel; the kernels re-arm
+ * them themselves afterwards).  A workspace carries no results between calls, but two calls that
+ * share one must not overlap in time (use one workspace per stream). */
 int chess_workspace_bytes(const chess_ctx* ctx, size_t* bytes);
+int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream);
 
 /*
  * Hierarchical summaries (Sec. 3.1).  Page vector = mean of the page's key rows (Eq. 1, per KV
@@ -120,7 +124,8 @@ int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* bloc
  * max_selected_pages; CHESS_ENOTSUP if a level can have more candidates than fit in LDS.
  */
 int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
-                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* stream);
+                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace,
+                 void* stream);
 
 /*
  * Block-sparse decode attention over the listed pages, read in place (Sec. 4.3 takes a paged
@@ -137,21 +142,8 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
                        void* workspace, void* stream);
 
-/*
- * Per-kernel device timing for benchmarks.  With timing on, every launch is bracketed by HIP
- * events on its own stream; chess_kernel_time sums the durations (ms) and launch counts recorded
- * for kernel `which` since the last reset and synchronises on them.  Not for use under graph capture.
- */
-#define CHESS_K_SUMMARIZE 0
-#define CHESS_K_SELECT    1
-#define CHESS_K_DECODE    2
-#define CHESS_K_MERGE     3
-#define CHESS_K_COUNT     4
-int chess_timing(chess_ctx* ctx, int32_t enable);          /* enable != 0 turns it on and resets */
-int chess_kernel_time(chess_ctx* ctx, int32_t which, double* total_ms, int64_t* launches);
-
-/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256], waves in
- * {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
+/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 2048,
+ * waves in {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
  * not fit the workspace for max_batch sequences. */
 int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves);
 

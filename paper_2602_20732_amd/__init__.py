@@ -2,8 +2,7 @@
 
 The product is ``libchess.so`` (hand-written HIP kernels behind the C ABI declared in ``include/chess.h``);
 this package is the thin Python binding over it.  PyTorch is used only for device memory and streams."""
-from .binding import (PLAN_BUDGET, PLAN_FLAT, PLAN_RATIO, K_DECODE, K_MERGE, K_SELECT, K_SUMMARIZE, Chess, ChessError,
-                      Config, SelectPlan, library_path, load_library)
+from .binding import (PLAN_BUDGET, PLAN_FLAT, PLAN_RATIO, Chess, ChessError, Config, SelectPlan, library_path,
+                      load_library)
 
-__all__ = ["Chess", "ChessError", "Config", "SelectPlan", "PLAN_BUDGET", "PLAN_RATIO", "PLAN_FLAT", "K_SUMMARIZE",
-           "K_SELECT", "K_DECODE", "K_MERGE", "library_path", "load_library"]
+__all__ = ["Chess", "ChessError", "Config", "SelectPlan", "PLAN_BUDGET", "PLAN_RATIO", "PLAN_FLAT", "library_path", "load_library"]

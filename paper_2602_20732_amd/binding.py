@@ -12,15 +12,14 @@ from dataclasses import dataclass
 import torch
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
-K_SUMMARIZE, K_SELECT, K_DECODE, K_MERGE = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
-EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes",
+EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
            "chess_summarize", "chess_summarize_tail", "chess_select", "chess_sparse_decode", "chess_dense_decode",
-           "chess_timing", "chess_kernel_time", "chess_debug_force_splits", "chess_strerror", "chess_version"]
+           "chess_debug_force_splits", "chess_strerror", "chess_version"]
 
 
 class ChessError(RuntimeError):
@@ -91,11 +90,10 @@ def load_library() -> ctypes.CDLL:
         lib.chess_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         lib.chess_summarize.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, i32p, vp, vp]
         lib.chess_summarize_tail.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, vp, vp]
-        lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp]
+        lib.chess_workspace_init.argtypes = [vp, vp, vp]
+        lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_dense_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp, vp, vp]
-        lib.chess_timing.argtypes = [vp, ctypes.c_int32]
-        lib.chess_kernel_time.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
         lib.chess_strerror.argtypes = [ctypes.c_int]
         lib.chess_strerror.restype = ctypes.c_char_p
@@ -153,7 +151,9 @@ class Chess:
         return torch.zeros(self.summary_bytes, dtype=torch.uint8, device=device)
 
     def new_workspace(self, device="cuda") -> torch.Tensor:
-        return torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+        ws = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
+        self._check(self.lib.chess_workspace_init(self._h, _ptr(ws), _stream()))
+        return ws
 
     def summary_views(self, summaries: torch.Tensor):
         """(pages, chunks, grids) fp32 views [max_batch, H_kv, units, d] of a summaries buffer."""
@@ -175,10 +175,10 @@ class Chess:
         self._check(self.lib.chess_summarize_tail(self._h, _ptr(k_pool), _ptr(block_table), _ptr(seq_lens),
                                                   seq_lens.shape[0], _ptr(summaries), _stream()))
 
-    def select(self, q, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected):
+    def select(self, q, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected, workspace):
         p = plan._c()
         self._check(self.lib.chess_select(self._h, _ptr(q), _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0],
-                                          ctypes.byref(p), _ptr(page_ids), _ptr(n_selected), _stream()))
+                                          ctypes.byref(p), _ptr(page_ids), _ptr(n_selected), _ptr(workspace), _stream()))
 
     def sparse_decode(self, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, out, workspace):
         self._check(self.lib.chess_sparse_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
@@ -191,12 +191,3 @@ class Chess:
 
     def debug_force_splits(self, n_splits: int, waves: int = 4):
         self._check(self.lib.chess_debug_force_splits(self._h, n_splits, waves))
-
-    def timing(self, enable: bool):
-        self._check(self.lib.chess_timing(self._h, 1 if enable else 0))
-
-    def kernel_time(self, which: int):
-        """(total ms, launches) recorded for kernel ``which`` since timing was last switched on."""
-        ms, n = ctypes.c_double(), ctypes.c_int64()
-        self._check(self.lib.chess_kernel_time(self._h, which, ctypes.byref(ms), ctypes.byref(n)))
-        return ms.value, n.value

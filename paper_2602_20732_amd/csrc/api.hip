@@ -76,7 +76,7 @@ SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages
     int waves = 4;
     if (pairs * cdiv(tiles, 4) < 2LL * ctx->n_cu) waves = 1;
     int64_t ns = clampi(cdiv(target, pairs), 1, cdiv(tiles, waves));
-    ns = std::min<int64_t>(ns, ctx->max_splits);
+    ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 2048 / g.group));   // merge weights live in LDS
     while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
     return {(int)ns, waves};
 }
@@ -92,11 +92,11 @@ int decode_common(chess_ctx* ctx, const void* q, const void* k_pool, const void*
     const SplitShape sh = choose_splits(ctx, batch, page_ids ? ctx->geom.max_sel : ctx->geom.max_pages);
     float* ws_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_acc_off);
     float* ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_ml_off);
+    int32_t* arrivals = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + ctx->ws_cnt_off);
     hipStream_t s = static_cast<hipStream_t>(stream);
     hipError_t e = chess::launch_decode(ctx, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_pool),
                                         static_cast<const uint16_t*>(v_pool), block_table, seq_lens, page_ids,
-                                        n_selected, batch, sh.n_splits, sh.waves, out, ws_acc, ws_ml, s);
-    if (e == hipSuccess && sh.n_splits > 1) e = chess::launch_merge(ctx, batch, sh.n_splits, ws_acc, ws_ml, out, s);
+                                        n_selected, batch, sh.n_splits, sh.waves, out, ws_acc, ws_ml, arrivals, s);
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
@@ -147,22 +147,21 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     const size_t part_rows = (size_t)(4 * c->n_cu + rows) * g.group;       // see choose_splits
     c->ws_acc_off = 0;
     c->ws_ml_off = align_up(part_rows * vec, 256);
-    c->workspace_bytes = align_up(c->ws_ml_off + part_rows * 2 * sizeof(float), 256);
-    c->timing = false;
+    c->ws_keys_off = align_up(c->ws_ml_off + part_rows * 2 * sizeof(float), 256);
+    c->ws_kg_off = align_up(c->ws_keys_off + rows * g.max_pages * sizeof(uint64_t), 256);
+    c->ws_kc_off = align_up(c->ws_kg_off + rows * g.max_grids * sizeof(int32_t), 256);
+    c->ws_meta_off = align_up(c->ws_kc_off + rows * g.max_chunks * sizeof(int32_t), 256);
+    c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
+    c->workspace_bytes = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
+    c->ws_zero_off = c->ws_meta_off;
+    c->ws_zero_bytes = c->workspace_bytes - c->ws_meta_off;
     c->force_splits = 0;
     c->force_waves = 4;
     *out = c;
     return CHESS_OK;
 }
 
-void chess_destroy(chess_ctx* ctx)
-{
-    if (!ctx) return;
-    for (auto& t : ctx->timers)
-        if (t.ready)
-            for (int i = 0; i < chess::KernelTimer::kRing; ++i) { (void)hipEventDestroy(t.start[i]); (void)hipEventDestroy(t.stop[i]); }
-    delete ctx;
-}
+void chess_destroy(chess_ctx* ctx) { delete ctx; }
 
 int chess_summary_bytes(const chess_ctx* ctx, size_t* bytes)
 {
@@ -211,12 +210,21 @@ int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* bloc
     return summarize_common(ctx, k_pool, block_table, seq_lens, batch, nullptr, true, summaries, stream);
 }
 
-int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
-                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* stream)
+int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream)
 {
-    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected) return CHESS_EINVAL;
+    if (!ctx || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 15)) return CHESS_EINVAL;
+    hipError_t e = chess::launch_zero(ctx, reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + ctx->ws_zero_off),
+                                      ctx->ws_zero_bytes / sizeof(int32_t), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
+                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace, void* stream)
+{
+    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries)) & 15) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(workspace)) & 15)
+        return CHESS_EINVAL;
     Bounds bd;
     if (!plan_bounds(ctx, plan, &bd)) return CHESS_EINVAL;
     if ((int64_t)plan->sink_pages + plan->window_pages + bd.kp > ctx->geom.max_sel) return CHESS_EINVAL;
@@ -226,16 +234,22 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     sp.budget_pages = plan->budget_pages; sp.budget_bp = plan->budget_bp;
     sp.over_chunk = plan->over_chunk; sp.over_grid = plan->over_grid;
     sp.rho_g_bp = plan->rho_g_bp; sp.rho_c_bp = plan->rho_c_bp; sp.rho_p_bp = plan->rho_p_bp;
-    sp.slot_cap = (int32_t)bd.slots;
-    sp.list_cap = (int32_t)align_up((size_t)bd.lists, 2);
-    const size_t lds = (size_t)sp.slot_cap * 8 + (size_t)sp.list_cap * 2 * 4;
-    if (lds + 2048 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+    sp.cap2 = (int32_t)(bd.kg * ctx->geom.n_g);
+    sp.cap3 = (int32_t)(bd.kc * ctx->geom.n_c);
+    if ((size_t)bd.slots * 8 + 4096 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
 
+    char* wb = static_cast<char*>(workspace);
+    chess::SelectWs ws{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), reinterpret_cast<int32_t*>(wb + ctx->ws_kg_off),
+                       reinterpret_cast<int32_t*>(wb + ctx->ws_kc_off), reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off)
+#ifdef CHESS_PROF_LEVEL
+                       , reinterpret_cast<int32_t*>(wb + ctx->ws_acc_off)     // profiling builds borrow the decode partials
+#endif
+    };
     const char* sb = static_cast<const char*>(summaries);
     hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
                                         reinterpret_cast<const float*>(sb + ctx->page_off),
                                         reinterpret_cast<const float*>(sb + ctx->chunk_off),
-                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, sp, lds,
+                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, sp, ws,
                                         page_ids, n_selected, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
@@ -255,30 +269,10 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
     return decode_common(ctx, q, k_pool, v_pool, block_table, seq_lens, nullptr, nullptr, batch, out, workspace, stream);
 }
 
-int chess_timing(chess_ctx* ctx, int32_t enable)
-{
-    if (!ctx) return CHESS_EINVAL;
-    for (auto& t : ctx->timers) {
-        if (chess::drain_timer(t) != hipSuccess) return CHESS_EHIP;
-        t.total_ms = 0.0;
-        t.launches = 0;
-    }
-    ctx->timing = enable != 0;
-    return CHESS_OK;
-}
-
-int chess_kernel_time(chess_ctx* ctx, int32_t which, double* total_ms, int64_t* launches)
-{
-    if (!ctx || which < 0 || which >= CHESS_K_COUNT || !total_ms || !launches) return CHESS_EINVAL;
-    if (chess::drain_timer(ctx->timers[which]) != hipSuccess) return CHESS_EHIP;
-    *total_ms = ctx->timers[which].total_ms;
-    *launches = ctx->timers[which].launches;
-    return CHESS_OK;
-}
-
 int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves)
 {
     if (!ctx || n_splits < 0 || n_splits > ctx->max_splits || (waves != 1 && waves != 4)) return CHESS_EINVAL;
+    if (n_splits * ctx->geom.group > 2048) return CHESS_EINVAL;
     const int64_t rows = (int64_t)ctx->cfg.max_batch * ctx->geom.n_kv_heads;
     if (rows * n_splits > 4LL * ctx->n_cu + rows) return CHESS_EINVAL;
     ctx->force_splits = n_splits;

@@ -2,7 +2,6 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/chess.h"
@@ -25,18 +24,57 @@ struct Geom {
 
 struct SelectParams {
     int32_t plan, sink, window, budget_pages, budget_bp, over_chunk, over_grid, rho_g_bp, rho_c_bp, rho_p_bp;
-    int32_t slot_cap;                // u64 key slots available in LDS
-    int32_t list_cap;                // entries of each kept-parent list in LDS
+    int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
 };
 
-struct KernelTimer {                 // one per kernel kind; events recycled in a ring
-    static constexpr int kRing = 64;
-    hipEvent_t start[kRing], stop[kRing];
-    int pending = 0;
-    double total_ms = 0.0;
-    int64_t launches = 0;
-    bool ready = false;
+constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): kept grids, kept chunks, 3 arrival counters
+
+// Select scratch in the caller's workspace (device pointers).
+struct SelectWs {
+    uint64_t* keys;                  // [rows][max_pages]   published candidate keys of the current level
+    int32_t* kept_grids;             // [rows][max_grids]   ascending
+    int32_t* kept_chunks;            // [rows][max_chunks]  ascending
+    int32_t* meta;                   // [rows][kSelMetaStride]
+#ifdef CHESS_PROF_LEVEL
+    int32_t* prof;                   // [rows][8] timing ticks (profiling builds only)
+#endif
 };
+
+// Values that cross workgroups inside one launch travel as agent-scope atomics, which are coherent
+// across the per-XCD L2s; plain stores would need an L2 write-back / invalidate on each side.
+__device__ __forceinline__ void publish_u64(uint64_t* p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t observe_u64(const uint64_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void publish_f32(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float observe_f32(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Called by every thread of a workgroup after its publish_* stores.  Returns true (to every thread)
+// in the workgroup that arrives last of `expected`; that workgroup also re-arms the counter for the
+// next launch.  Nobody waits.  The counter must be 0 before the first launch.
+__device__ __forceinline__ bool arrive_last(int32_t* counter, int expected, int* lds_flag)
+{
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's published stores are acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = old == expected - 1;
+        if (last) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *lds_flag = last;
+    }
+    __syncthreads();
+    return *lds_flag != 0;
+}
 
 }  // namespace chess
 
@@ -51,53 +89,17 @@ struct chess_ctx {
     int max_splits;
     int force_splits, force_waves;                         // 0 = automatic
     size_t ws_acc_off, ws_ml_off, workspace_bytes;
-    bool timing;
-    chess::KernelTimer timers[CHESS_K_COUNT];
+    size_t ws_keys_off, ws_kg_off, ws_kc_off, ws_meta_off, ws_cnt_off;   // select scratch, decode arrival counters
+    size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
 };
 
 namespace chess {
 
-// Collect the finished event pairs of one timer into its totals (synchronises on them).
-inline hipError_t drain_timer(KernelTimer& t)
-{
-    for (int i = 0; i < t.pending; ++i) {
-        hipError_t e = hipEventSynchronize(t.stop[i]);
-        if (e != hipSuccess) return e;
-        float ms = 0.f;
-        e = hipEventElapsedTime(&ms, t.start[i], t.stop[i]);
-        if (e != hipSuccess) return e;
-        t.total_ms += ms;
-        t.launches += 1;
-    }
-    t.pending = 0;
-    return hipSuccess;
-}
-
-// Launch `kernel`; with timing on, bracket exactly this dispatch with start / stop events so the
-// elapsed time is the kernel's own duration (no launch gaps).
+// Launch `kernel` on `stream` and report the launch status.
 template <typename... KArgs, typename... Args>
-inline hipError_t timed_launch(chess_ctx* ctx, int which, void (*kernel)(KArgs...), dim3 grid, dim3 block,
-                               size_t lds, hipStream_t stream, Args... args)
+inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t stream, Args... args)
 {
-    if (!ctx->timing) {
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, args...);
-        return hipGetLastError();
-    }
-    KernelTimer& t = ctx->timers[which];
-    if (!t.ready) {
-        for (int i = 0; i < KernelTimer::kRing; ++i) {
-            hipError_t e = hipEventCreate(&t.start[i]);
-            if (e == hipSuccess) e = hipEventCreate(&t.stop[i]);
-            if (e != hipSuccess) return e;
-        }
-        t.ready = true;
-    }
-    if (t.pending == KernelTimer::kRing) {
-        hipError_t e = drain_timer(t);
-        if (e != hipSuccess) return e;
-    }
-    const int i = t.pending++;
-    hipExtLaunchKernelGGL(kernel, grid, block, lds, stream, t.start[i], t.stop[i], 0, args...);
+    hipLaunchKernelGGL(kernel, grid, block, lds, stream, args...);
     return hipGetLastError();
 }
 
@@ -108,15 +110,14 @@ hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_
 
 hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,
                          const float* grids, const int32_t* seq_lens, int batch, const SelectParams& sp,
-                         size_t lds_bytes, int32_t* page_ids, int32_t* n_selected, hipStream_t stream);
+                         const SelectWs& ws, int32_t* page_ids, int32_t* n_selected, hipStream_t stream);
+hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);
 
-// page_ids == nullptr: every page of the sequence.  n_splits >= 1; with n_splits == 1 the decode
-// kernel writes `out` itself and no merge is launched.
+// page_ids == nullptr: every page of the sequence.  n_splits >= 1; the last split of a (sequence,
+// KV head) to finish merges the partials and writes `out`.  `arrivals`: int32 [rows], zero before first use.
 hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
                          const int32_t* n_selected, int batch, int n_splits, int waves, float* out,
-                         float* ws_acc, float* ws_ml, hipStream_t stream);
-hipError_t launch_merge(chess_ctx* ctx, int batch, int n_splits, const float* ws_acc, const float* ws_ml,
-                        float* out, hipStream_t stream);
+                         float* ws_acc, float* ws_ml, int32_t* arrivals, hipStream_t stream);
 
 }  // namespace chess

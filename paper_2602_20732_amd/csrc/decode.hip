@@ -15,7 +15,7 @@
 //
 // Softmax state (m, l) of head j lives in the four lanes with lane % 16 == j; O^T accumulators are
 // 8 x float4 per lane.  Waves of a workgroup take tiles round-robin and are merged through LDS;
-// splits are merged by merge_kernel (skipped when there is a single split).
+// the last split of a (sequence, KV head) to finish merges all splits' partials, in split order.
 #include "chess_internal.h"
 
 namespace chess {
@@ -81,11 +81,13 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ page_ids,
                                                          const int32_t* __restrict__ n_selected, Geom g,
                                                          float scale_log2, int n_splits, float* __restrict__ out,
-                                                         float* __restrict__ ws_acc, float* __restrict__ ws_ml)
+                                                         float* __restrict__ ws_acc, float* __restrict__ ws_ml,
+                                                         int32_t* __restrict__ arrivals)
 {
     constexpr int PPT = 32 / B;
     __shared__ float lds_o[NW][kMaxGroup][kHeadDim];
     __shared__ float lds_m[NW][kMaxGroup], lds_l[NW][kMaxGroup];
+    __shared__ int lds_last;
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -189,6 +191,7 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     if (grp == 0) { lds_m[wave][m16] = m_run; lds_l[wave][m16] = l_run; }
     __syncthreads();
 
+    float* wgt = &lds_o[0][0][0];                     // reused by the merging workgroup: [n_splits][G]
     for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 64 * NW) {
         const int head = idx / kHeadDim, d = idx % kHeadDim;
         float M = lds_m[0][head];
@@ -205,52 +208,64 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
             out[((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d] = l > 0.f ? acc / l : 0.f;
         } else {
             const size_t pr = (row * n_splits + split) * G + head;
-            ws_acc[pr * kHeadDim + d] = acc;
-            if (d == 0) { ws_ml[pr * 2] = M; ws_ml[pr * 2 + 1] = l; }
+            publish_f32(ws_acc + pr * kHeadDim + d, acc);
+            if (d == 0) { publish_f32(ws_ml + pr * 2, M); publish_f32(ws_ml + pr * 2 + 1, l); }
         }
     }
-}
+    if (n_splits == 1) return;
+    if (!arrive_last(arrivals + row, n_splits, &lds_last)) return;
 
-// out[b][hq][:] = sum_s acc_s * 2^(m_s - M) / sum_s l_s * 2^(m_s - M)
-__global__ __launch_bounds__(kHeadDim) void merge_kernel(const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
-                                                         Geom g, int n_splits, float* __restrict__ out)
-{
-    const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
-    const int h = hq / g.group, head = hq % g.group;
-    const size_t row = (size_t)b * g.n_kv_heads + h;
-    float M = kNegBig;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ws_ml[((row * n_splits + s) * g.group + head) * 2]);
-    float acc = 0.f, l = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-        const size_t pr = (row * n_splits + s) * g.group + head;
-        const float sc = __builtin_amdgcn_exp2f(ws_ml[pr * 2] - M);
-        acc += ws_acc[pr * kHeadDim + d] * sc;
-        l += ws_ml[pr * 2 + 1] * sc;
+    // ---- the last split of this (sequence, KV head): out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M),
+    // always in split order, so the result does not depend on which workgroup happens to be last
+    for (int head = threadIdx.x; head < G; head += 64 * NW) {
+        float M = kNegBig;
+        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, observe_f32(ws_ml + ((row * n_splits + s) * G + head) * 2));
+        float l = 0.f;
+        for (int s = 0; s < n_splits; ++s) {
+            const size_t pr = (row * n_splits + s) * G + head;
+            l += observe_f32(ws_ml + pr * 2 + 1) * __builtin_amdgcn_exp2f(observe_f32(ws_ml + pr * 2) - M);
+        }
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        for (int s = 0; s < n_splits; ++s)
+            wgt[s * G + head] = __builtin_amdgcn_exp2f(observe_f32(ws_ml + ((row * n_splits + s) * G + head) * 2) - M) * inv;
     }
-    out[((size_t)b * g.n_q_heads + hq) * kHeadDim + d] = l > 0.f ? acc / l : 0.f;
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 64 * NW) {
+        const int head = idx / kHeadDim, d = idx % kHeadDim;
+        float acc = 0.f;
+        for (int s = 0; s < n_splits; ++s)
+            acc += observe_f32(ws_acc + ((row * n_splits + s) * G + head) * kHeadDim + d) * wgt[s * G + head];
+        out[((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d] = acc;
+    }
 }
 
 hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
                          const int32_t* n_selected, int batch, int n_splits, int waves, float* out,
-                         float* ws_acc, float* ws_ml, hipStream_t stream)
+                         float* ws_acc, float* ws_ml, int32_t* arrivals, hipStream_t stream)
 {
     const Geom& g = ctx->geom;
     const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     const dim3 grid(n_splits, g.n_kv_heads, batch), block(64 * waves);
     void (*kern)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
-                 const int32_t*, Geom, float, int, float*, float*, float*);
+                 const int32_t*, Geom, float, int, float*, float*, float*, int32_t*);
     if (g.page_size == 16) kern = waves == 4 ? decode_kernel<16, 4> : decode_kernel<16, 1>;
     else                   kern = waves == 4 ? decode_kernel<32, 4> : decode_kernel<32, 1>;
-    return timed_launch(ctx, CHESS_K_DECODE, kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
-                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml);
+    return launch(kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
+                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
 }
 
-hipError_t launch_merge(chess_ctx* ctx, int batch, int n_splits, const float* ws_acc, const float* ws_ml,
-                        float* out, hipStream_t stream)
+__global__ void zero_kernel(int32_t* p, size_t n)
 {
-    const dim3 grid(ctx->geom.n_q_heads, batch), block(kHeadDim);
-    return timed_launch(ctx, CHESS_K_MERGE, merge_kernel, grid, block, 0, stream, ws_acc, ws_ml, ctx->geom, n_splits, out);
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream)
+{
+    (void)ctx;
+    hipLaunchKernelGGL(zero_kernel, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, stream, p, n_words);
+    return hipGetLastError();
 }
 
 }  // namespace chess

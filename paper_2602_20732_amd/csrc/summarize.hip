@@ -125,7 +125,7 @@ hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    return timed_launch(ctx, CHESS_K_SUMMARIZE, kern, grid, block, lds, stream, k_pool, block_table, seq_lens,
+    return launch(kern, grid, block, lds, stream, k_pool, block_table, seq_lens,
                         from_page, tail_only ? 1 : 0, g, pages, chunks, grids);
 }
 

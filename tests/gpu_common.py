@@ -53,7 +53,7 @@ def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool
     out = torch.full((batch, c.n_q_heads, c.head_dim), float("nan"), dtype=torch.float32, device="cuda")
     dn = torch.full_like(out, float("nan"))
     lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
-    lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel)
+    lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
     torch.cuda.synchronize()
     P = (-(-d.seq_lens.long() // c.page_size)).view(-1, 1, 1)            # the list must be safe to walk
     assert bool(((nsel >= 0) & (nsel <= c.max_selected_pages)).all()), "n_selected out of range"

@@ -197,13 +197,13 @@ def test_error_codes():
     sp = RAGGED
     lib = pk.Chess(config_of(sp))
     d = to_device(workload.generate(sp, 77, seq_lens=RAGGED_LENS))
-    summ = lib.new_summaries()
+    summ, ws = lib.new_summaries(), lib.new_workspace()
     ids = torch.zeros((5, 2, sp.max_selected), dtype=torch.int32, device="cuda")
     nsel = torch.zeros((5, 2), dtype=torch.int32, device="cuda")
     with pytest.raises(pk.ChessError):       # budget + safety pages do not fit max_selected_pages
-        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(budget_pages=sp.max_selected), ids, nsel)
+        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(budget_pages=sp.max_selected), ids, nsel, ws)
     with pytest.raises(pk.ChessError):       # unknown plan
-        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(plan=9), ids, nsel)
+        lib.select(d.q, summ, d.seq_lens, pk.SelectPlan(plan=9), ids, nsel, ws)
     with pytest.raises(pk.ChessError):       # batch beyond max_batch
         big = torch.zeros(6, dtype=torch.int32, device="cuda")
         lib.summarize(d.k_pool, d.block_table, big, summ)

@@ -59,7 +59,7 @@ def test_null_context_is_rejected(lib):
     n = ctypes.c_size_t()
     assert lib.chess_summary_bytes(None, ctypes.byref(n)) == -1
     assert lib.chess_workspace_bytes(None, ctypes.byref(n)) == -1
-    assert lib.chess_timing(None, 1) == -1
-    assert lib.chess_select(None, None, None, None, 1, None, None, None, None) == -1
+    assert lib.chess_workspace_init(None, None, None) == -1
+    assert lib.chess_select(None, None, None, None, 1, None, None, None, None, None) == -1
     assert lib.chess_dense_decode(None, None, None, None, None, None, 1, None, None, None) == -1
     lib.chess_destroy(None)
