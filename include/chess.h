@@ -122,6 +122,7 @@ int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* bloc
  * list of logical page numbers; if the sequence has at most s + w pages, all of them.
  * `plan` is a host pointer.  CHESS_EINVAL if s + w + (largest possible k_p) exceeds
  * max_selected_pages; CHESS_ENOTSUP if a level can have more candidates than fit in LDS.
+ * Uses the workspace (published keys, cluster barrier counters).
  */
 int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
                  const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace,
@@ -142,7 +143,17 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
                        void* workspace, void* stream);
 
-/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 2048,
+/* Synchronous check (copies one word back, waits for the device): *flag is non-zero if any kernel
+ * using this workspace gave up a bounded wait -- which cannot happen unless the device was shared
+ * with work that kept this library's workgroups from becoming resident together.  Results written
+ * by such a launch are undefined; re-initialise the workspace before reuse. */
+int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag);
+
+/* Test hook: force the number of workgroups that cooperate on one (sequence, KV head) in
+ * chess_select (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
+int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster);
+
+/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 1024,
  * waves in {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
  * not fit the workspace for max_batch sequences. */
 int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves);

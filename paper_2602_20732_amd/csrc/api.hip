@@ -76,7 +76,7 @@ SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages
     int waves = 4;
     if (pairs * cdiv(tiles, 4) < 2LL * ctx->n_cu) waves = 1;
     int64_t ns = clampi(cdiv(target, pairs), 1, cdiv(tiles, waves));
-    ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 2048 / g.group));   // merge weights live in LDS
+    ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 1024 / g.group));   // the merge keeps (m, l) of every split in LDS
     while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
     return {(int)ns, waves};
 }
@@ -148,11 +148,14 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_acc_off = 0;
     c->ws_ml_off = align_up(part_rows * vec, 256);
     c->ws_keys_off = align_up(c->ws_ml_off + part_rows * 2 * sizeof(float), 256);
-    c->ws_kg_off = align_up(c->ws_keys_off + rows * g.max_pages * sizeof(uint64_t), 256);
-    c->ws_kc_off = align_up(c->ws_kg_off + rows * g.max_grids * sizeof(int32_t), 256);
-    c->ws_meta_off = align_up(c->ws_kc_off + rows * g.max_chunks * sizeof(int32_t), 256);
+    c->key_stride = (int64_t)g.max_grids * (1 + g.n_g) + (int64_t)g.max_chunks * g.n_c;
+    c->ws_meta_off = align_up(c->ws_keys_off + rows * c->key_stride * sizeof(uint64_t), 256);
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
-    c->workspace_bytes = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
+    c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
+    c->workspace_bytes = align_up(c->ws_err_off + 256, 256);
+    c->force_cluster = 0;
+    c->occ_lds = -1;
+    c->occ_blocks = 0;
     c->ws_zero_off = c->ws_meta_off;
     c->ws_zero_bytes = c->workspace_bytes - c->ws_meta_off;
     c->force_splits = 0;
@@ -236,12 +239,30 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     sp.rho_g_bp = plan->rho_g_bp; sp.rho_c_bp = plan->rho_c_bp; sp.rho_p_bp = plan->rho_p_bp;
     sp.cap2 = (int32_t)(bd.kg * ctx->geom.n_g);
     sp.cap3 = (int32_t)(bd.kc * ctx->geom.n_c);
-    if ((size_t)bd.slots * 8 + 4096 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+    sp.cap_keys = (int32_t)bd.slots;
+    sp.cap_kg = (int32_t)bd.kg;
+    sp.cap_kc = (int32_t)bd.kc;
+    const size_t lds = (size_t)sp.cap_keys * 8 + align_up((size_t)(sp.cap_kg + sp.cap_kc) * 4, 8);
+    if (lds + 4096 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+
+    // cluster size: every workgroup of the grid must be resident at once (the members of a cluster
+    // wait for each other), with half the device's capacity left as margin
+    if (ctx->occ_lds != (int)lds) {
+        int blocks = 0;
+        if (chess::select_occupancy((int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        ctx->occ_lds = (int)lds;
+        ctx->occ_blocks = blocks;
+    }
+    const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
+    const int64_t capacity = (int64_t)ctx->occ_blocks * ctx->n_cu;
+    int64_t cluster = std::min<int64_t>(capacity / (2 * pairs), cdiv(sp.cap3, 32));
+    if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
+    cluster = clampi(cluster, 1, 32);
 
     char* wb = static_cast<char*>(workspace);
-    chess::SelectWs ws{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), reinterpret_cast<int32_t*>(wb + ctx->ws_kg_off),
-                       reinterpret_cast<int32_t*>(wb + ctx->ws_kc_off), reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off)
-#ifdef CHESS_PROF_LEVEL
+    chess::SelectWs ws{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), ctx->key_stride,
+                       reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off), reinterpret_cast<int32_t*>(wb + ctx->ws_err_off)
+#ifdef CHESS_PROF
                        , reinterpret_cast<int32_t*>(wb + ctx->ws_acc_off)     // profiling builds borrow the decode partials
 #endif
     };
@@ -249,9 +270,23 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
                                         reinterpret_cast<const float*>(sb + ctx->page_off),
                                         reinterpret_cast<const float*>(sb + ctx->chunk_off),
-                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, sp, ws,
-                                        page_ids, n_selected, static_cast<hipStream_t>(stream));
+                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, (int)cluster,
+                                        sp, ws, lds, page_ids, n_selected, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag)
+{
+    if (!ctx || !workspace || !flag) return CHESS_EINVAL;
+    hipError_t e = hipMemcpy(flag, static_cast<const char*>(workspace) + ctx->ws_err_off, sizeof(int32_t), hipMemcpyDeviceToHost);
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster)
+{
+    if (!ctx || cluster < 0 || cluster > 32) return CHESS_EINVAL;
+    ctx->force_cluster = cluster;
+    return CHESS_OK;
 }
 
 int chess_sparse_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
@@ -272,7 +307,7 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
 int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves)
 {
     if (!ctx || n_splits < 0 || n_splits > ctx->max_splits || (waves != 1 && waves != 4)) return CHESS_EINVAL;
-    if (n_splits * ctx->geom.group > 2048) return CHESS_EINVAL;
+    if (n_splits * ctx->geom.group > 1024) return CHESS_EINVAL;
     const int64_t rows = (int64_t)ctx->cfg.max_batch * ctx->geom.n_kv_heads;
     if (rows * n_splits > 4LL * ctx->n_cu + rows) return CHESS_EINVAL;
     ctx->force_splits = n_splits;

@@ -25,18 +25,20 @@ struct Geom {
 struct SelectParams {
     int32_t plan, sink, window, budget_pages, budget_bp, over_chunk, over_grid, rho_g_bp, rho_c_bp, rho_p_bp;
     int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
+    int32_t cap_keys, cap_kg, cap_kc;   // LDS capacities: keys of one level, kept grids, kept chunks
 };
 
-constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): kept grids, kept chunks, 3 arrival counters
+constexpr int kSelThreads = 256;
+constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): [0] barrier arrivals, [1] members that left
 
 // Select scratch in the caller's workspace (device pointers).
 struct SelectWs {
-    uint64_t* keys;                  // [rows][max_pages]   published candidate keys of the current level
-    int32_t* kept_grids;             // [rows][max_grids]   ascending
-    int32_t* kept_chunks;            // [rows][max_chunks]  ascending
-    int32_t* meta;                   // [rows][kSelMetaStride]
-#ifdef CHESS_PROF_LEVEL
-    int32_t* prof;                   // [rows][8] timing ticks (profiling builds only)
+    uint64_t* keys;                  // [rows][key_stride]  published candidate keys: grids | chunk slots | page slots
+    int64_t key_stride;
+    int32_t* meta;                   // [rows][kSelMetaStride], zero between launches
+    int32_t* error;                  // one word: set if a cluster barrier was given up
+#ifdef CHESS_PROF
+    int32_t* prof;                   // [rows][16] phase durations in 10 ns ticks (profiling builds only)
 #endif
 };
 
@@ -89,7 +91,10 @@ struct chess_ctx {
     int max_splits;
     int force_splits, force_waves;                         // 0 = automatic
     size_t ws_acc_off, ws_ml_off, workspace_bytes;
-    size_t ws_keys_off, ws_kg_off, ws_kc_off, ws_meta_off, ws_cnt_off;   // select scratch, decode arrival counters
+    size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off;   // select scratch, decode arrival counters, error word
+    int64_t key_stride;
+    int force_cluster;                                     // 0 = automatic
+    int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
 };
 
@@ -109,8 +114,10 @@ hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_
                             float* pages, float* chunks, float* grids, hipStream_t stream);
 
 hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,
-                         const float* grids, const int32_t* seq_lens, int batch, const SelectParams& sp,
-                         const SelectWs& ws, int32_t* page_ids, int32_t* n_selected, hipStream_t stream);
+                         const float* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
+                         const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
+                         hipStream_t stream);
+hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);
 
 // page_ids == nullptr: every page of the sequence.  n_splits >= 1; the last split of a (sequence,

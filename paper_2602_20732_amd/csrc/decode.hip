@@ -14,7 +14,8 @@
 // relative; the row sum l uses the fp32 weights.
 //
 // Softmax state (m, l) of head j lives in the four lanes with lane % 16 == j; O^T accumulators are
-// 8 x float4 per lane.  Waves of a workgroup take tiles round-robin and are merged through LDS;
+// 8 x float4 per lane.  Tiles are dealt round-robin over splits and waves; the waves of a workgroup are
+// merged through LDS;
 // the last split of a (sequence, KV head) to finish merges all splits' partials, in split order.
 #include "chess_internal.h"
 
@@ -34,8 +35,18 @@ struct Tile {
     int ntok[32 / B];   // valid tokens of each page slot of the tile (0 = slot unused)
 };
 
+// The logical page numbers of tile t as stored in the list (speculative: the index is clamped into the
+// row, validity is decided later), so that this load does not wait for the list length.
 template <int B>
-__device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const int32_t* ids, const int32_t* bt_row,
+__device__ __forceinline__ void fetch_ids(int (&raw)[32 / B], int t, const int32_t* ids, int max_sel)
+{
+    constexpr int PPT = 32 / B;
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) raw[s] = ids ? ids[min(t * PPT + s, max_sel - 1)] : t * PPT + s;
+}
+
+template <int B>
+__device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const int (&raw)[32 / B], const int32_t* bt_row,
                                           const uint16_t* k_pool, const uint16_t* v_pool, int H, int h, int L, int P,
                                           int m16, int grp)
 {
@@ -43,10 +54,8 @@ __device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const
     int64_t phys[PPT];
 #pragma unroll
     for (int s = 0; s < PPT; ++s) {
-        const int idx = t * PPT + s;
-        const bool ok = idx < n_pages;
-        const int use = ok ? idx : t * PPT;                       // unused slot: alias the tile's first page
-        int lp = ids ? ids[use] : use;
+        const bool ok = t * PPT + s < n_pages;
+        int lp = ok ? raw[s] : raw[0];                            // unused slot: alias the tile's first page
         lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
         phys[s] = __builtin_amdgcn_readfirstlane(bt_row[lp]);
         tl.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
@@ -93,15 +102,22 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m16 = lane & 15, grp = lane >> 4;
     const int G = g.group, H = g.n_kv_heads;
-    const int L = min(max(seq_lens[b], 0), g.max_pages * B);
-    const int P = (L + B - 1) / B;
     const size_t row = (size_t)b * H + h;
-    const int n_pages = P == 0 ? 0 : (page_ids ? min(max(n_selected[row], 0), g.max_sel) : P);
     const int32_t* ids = page_ids ? page_ids + row * g.max_sel : nullptr;
     const int32_t* bt_row = block_table + (size_t)b * g.max_pages;
+    // tiles are dealt round-robin: tile = split + n_splits * (wave + NW * i), so the first tile of a wave
+    // is known before the list length is, and its page numbers can be fetched alongside the lengths
+    const int stride = n_splits * NW;
+    int t = split + n_splits * wave;
+    int raw_cur[PPT], raw_nxt[PPT];
+    const int L_raw = seq_lens[b];
+    const int n_raw = page_ids ? n_selected[row] : 0;
+    fetch_ids<B>(raw_cur, t, ids, g.max_sel);
+    fetch_ids<B>(raw_nxt, t + stride, ids, g.max_sel);
+    const int L = min(max(L_raw, 0), g.max_pages * B);
+    const int P = (L + B - 1) / B;
+    const int n_pages = P == 0 ? 0 : (page_ids ? min(max(n_raw, 0), g.max_sel) : P);
     const int n_tiles = (n_pages + PPT - 1) / PPT;
-    const int per = (n_tiles + n_splits - 1) / n_splits;
-    const int t0 = split * per, t1 = min(n_tiles, t0 + per);
 
     // Q^T operand: head m16, d = 32*st + 8*grp .. +7; heads >= G are zero columns
     bf16x8 qop[4];
@@ -118,12 +134,14 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     Tile<B> cur;
-    int t = t0 + wave;
-    if (t < t1) load_tile<B>(cur, t, n_pages, ids, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
-    for (; t < t1; t += NW) {
+    if (t < n_tiles) load_tile<B>(cur, t, n_pages, raw_cur, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+    for (; t < n_tiles; t += stride) {
         Tile<B> nxt;
-        const bool more = t + NW < t1;
-        if (more) load_tile<B>(nxt, t + NW, n_pages, ids, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+        const bool more = t + stride < n_tiles;
+        if (more) {
+            load_tile<B>(nxt, t + stride, n_pages, raw_nxt, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+            fetch_ids<B>(raw_nxt, t + 2 * stride, ids, g.max_sel);
+        }
 
         // scores of this lane's head for tokens 8*grp + e, e = 0..7 (c = 0 gives e 0..3, c = 1 gives 4..7)
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -191,51 +209,72 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     if (grp == 0) { lds_m[wave][m16] = m_run; lds_l[wave][m16] = l_run; }
     __syncthreads();
 
-    float* wgt = &lds_o[0][0][0];                     // reused by the merging workgroup: [n_splits][G]
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 64 * NW) {
-        const int head = idx / kHeadDim, d = idx % kHeadDim;
+    // combine this workgroup's waves; one thread per pair of adjacent d
+    float2* ml_buf = reinterpret_cast<float2*>(&lds_o[0][0][0]);   // reused by the merging workgroup: [n_splits][G]
+    uint64_t* acc_g = reinterpret_cast<uint64_t*>(ws_acc);           // partial rows as pairs of floats
+    uint64_t* ml_g = reinterpret_cast<uint64_t*>(ws_ml);             // (m, l) per partial row
+    for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += 64 * NW) {
+        const int head = idx / (kHeadDim / 2), d = 2 * (idx % (kHeadDim / 2));
         float M = lds_m[0][head];
 #pragma unroll
         for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, lds_m[wv][head]);
-        float acc = 0.f, l = 0.f;
+        float a0 = 0.f, a1 = 0.f, l = 0.f;
 #pragma unroll
         for (int wv = 0; wv < NW; ++wv) {
             const float sc = __builtin_amdgcn_exp2f(lds_m[wv][head] - M);
-            acc += lds_o[wv][head][d] * sc;
+            a0 += lds_o[wv][head][d] * sc;
+            a1 += lds_o[wv][head][d + 1] * sc;
             l += lds_l[wv][head] * sc;
         }
         if (n_splits == 1) {
-            out[((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d] = l > 0.f ? acc / l : 0.f;
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            *reinterpret_cast<float2*>(out + ((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d) = make_float2(a0 * inv, a1 * inv);
         } else {
             const size_t pr = (row * n_splits + split) * G + head;
-            publish_f32(ws_acc + pr * kHeadDim + d, acc);
-            if (d == 0) { publish_f32(ws_ml + pr * 2, M); publish_f32(ws_ml + pr * 2 + 1, l); }
+            publish_u64(acc_g + pr * (kHeadDim / 2) + d / 2, __builtin_bit_cast(uint64_t, make_float2(a0, a1)));
+            if (d == 0) publish_u64(ml_g + pr, __builtin_bit_cast(uint64_t, make_float2(M, l)));
         }
     }
     if (n_splits == 1) return;
     if (!arrive_last(arrivals + row, n_splits, &lds_last)) return;
 
-    // ---- the last split of this (sequence, KV head): out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M),
-    // always in split order, so the result does not depend on which workgroup happens to be last
-    for (int head = threadIdx.x; head < G; head += 64 * NW) {
-        float M = kNegBig;
-        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, observe_f32(ws_ml + ((row * n_splits + s) * G + head) * 2));
-        float l = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-            const size_t pr = (row * n_splits + s) * G + head;
-            l += observe_f32(ws_ml + pr * 2 + 1) * __builtin_amdgcn_exp2f(observe_f32(ws_ml + pr * 2) - M);
-        }
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-        for (int s = 0; s < n_splits; ++s)
-            wgt[s * G + head] = __builtin_amdgcn_exp2f(observe_f32(ws_ml + ((row * n_splits + s) * G + head) * 2) - M) * inv;
+    // ---- the last split of this (sequence, KV head) to finish merges all of them:
+    // out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), always in split order, so the result does not
+    // depend on which workgroup happens to be last
+    for (int idx = threadIdx.x; idx < n_splits * G; idx += 64 * NW) {
+        const int sidx = idx / G, head = idx % G;
+        ml_buf[idx] = __builtin_bit_cast(float2, observe_u64(ml_g + (row * n_splits + sidx) * G + head));
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += 64 * NW) {
-        const int head = idx / kHeadDim, d = idx % kHeadDim;
-        float acc = 0.f;
-        for (int s = 0; s < n_splits; ++s)
-            acc += observe_f32(ws_acc + ((row * n_splits + s) * G + head) * kHeadDim + d) * wgt[s * G + head];
-        out[((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + d] = acc;
+    if ((int)threadIdx.x < G) {
+        const int head = threadIdx.x;
+        float M = kNegBig, l = 0.f;
+        for (int sidx = 0; sidx < n_splits; ++sidx) M = fmaxf(M, ml_buf[sidx * G + head].x);
+        for (int sidx = 0; sidx < n_splits; ++sidx) l += ml_buf[sidx * G + head].y * __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M);
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        for (int sidx = 0; sidx < n_splits; ++sidx)
+            ml_buf[sidx * G + head].x = __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M) * inv;   // weight of split sidx
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += 64 * NW) {
+        const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
+        float a0 = 0.f, a1 = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += 4) {
+            uint64_t v[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                v[x] = s0 + x < n_splits ? observe_u64(acc_g + ((row * n_splits + s0 + x) * G + head) * (kHeadDim / 2) + d2) : 0ull;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                if (s0 + x < n_splits) {
+                    const float2 f = __builtin_bit_cast(float2, v[x]);
+                    const float wt = ml_buf[(s0 + x) * G + head].x;
+                    a0 += f.x * wt;
+                    a1 += f.y * wt;
+                }
+            }
+        }
+        *reinterpret_cast<float2*>(out + ((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + 2 * d2) = make_float2(a0, a1);
     }
 }
 

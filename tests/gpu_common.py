@@ -41,7 +41,8 @@ def to_device(wl: workload.Workload):
         wl.q.cuda(), wl.segments, wl.q_topics)
 
 
-def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool = True, ids_override=None) -> GpuRun:
+def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool = True, ids_override=None,
+            cluster: int = 0) -> GpuRun:
     """summarize -> select -> sparse decode (+ dense decode) on the GPU; results as numpy arrays."""
     d = to_device(wl)
     c = lib.cfg
@@ -53,6 +54,7 @@ def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool
     out = torch.full((batch, c.n_q_heads, c.head_dim), float("nan"), dtype=torch.float32, device="cuda")
     dn = torch.full_like(out, float("nan"))
     lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    lib.debug_force_cluster(cluster)
     lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
     torch.cuda.synchronize()
     P = (-(-d.seq_lens.long() // c.page_size)).view(-1, 1, 1)            # the list must be safe to walk
@@ -66,6 +68,7 @@ def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool
     if dense:
         lib.dense_decode(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, dn, ws)
     torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0, "a kernel gave up a bounded wait"
     pv, cv, gv = (t[:batch].cpu().numpy() for t in lib.summary_views(summ))
     return GpuRun(pv, cv, gv, ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dn.cpu().numpy())
 

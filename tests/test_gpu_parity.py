@@ -79,6 +79,28 @@ def test_hierarchy_shapes(nc, ng):
     check_all(sp, wl, plan_of(sp), dense=False, label=f"hier {nc}x{ng}")
 
 
+@pytest.mark.parametrize("cluster", [1, 2, 3, 8, 32])
+def test_cluster_sizes_give_the_same_page_lists(cluster):
+    """The number of workgroups cooperating on one (sequence, head) must not change anything; twice in a row
+    on one workspace, so the barrier counters are shown to re-arm."""
+    sp = workload.spec("cfg2", scale=1 / 2)
+    wl = workload.generate(sp, workload.default_seed("cfg2"))
+    plan = plan_of(sp)
+    lib = pk.Chess(config_of(sp))
+    ref = run_oracle(wl, plan, sp.max_selected, dense=False)
+    d = to_device(wl)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    lib.debug_force_cluster(cluster)
+    for _ in range(2):
+        ids = torch.full((1, sp.n_kv_heads, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+        nsel = torch.full((1, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+        lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
+        torch.cuda.synchronize()
+        assert lib.workspace_error(ws) == 0
+        assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+
+
 def test_page32_gqa7_and_equal_norm_topics():
     """The stress shape scaled down (page 32, 28 / 4 heads), plus its equal-norm variant (near-tied scores)."""
     for name in ("cfg5", "cfg5adv"):
