@@ -52,12 +52,58 @@ __device__ __forceinline__ int wave_scan(int v, const int identity, Op op)
     return v;
 }
 
+constexpr int kBins = 1024;                 // linear score bins of the first cut pass
+constexpr int kMaxMembers = 256;            // most keys the bin at the cut may hold for the exact ranking
+
 struct Shared {
-    int hist[256];
+    int hist[kBins];
+    uint64_t mem_key[kMaxMembers];
+    int mem_slot[kMaxMembers];
     int wave_a[kSelWaves], wave_b[kSelWaves];
-    int digit, rem, cnt, n_valid, ok;
+    int digit, rem, cnt, n_valid, ok, n_mem;
     unsigned int or_lo, or_hi, and_lo, and_hi;
+    unsigned long long kmin, kmax, thr;
 };
+
+// order_key's inverse, for binning
+__device__ __forceinline__ double key_score(uint64_t key)
+{
+    const uint64_t u = (key >> 63) ? (key & 0x7fffffffffffffffull) : ~key;
+    return __longlong_as_double((long long)u);
+}
+
+// Minimum / maximum of a 64-bit value over the wave (DPP, no LDS); the result is in lane 63.
+template <bool kMin>
+__device__ __forceinline__ uint64_t wave_minmax(uint64_t v)
+{
+    const int id = kMin ? -1 : 0;
+#define CHESS_MM_STEP(ctrl, rows)                                                                      \
+    {                                                                                                  \
+        const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(id, (int)(unsigned)v, ctrl, rows, 0xf, false); \
+        const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(id, (int)(unsigned)(v >> 32), ctrl, rows, 0xf, false); \
+        const uint64_t o = ((uint64_t)hi << 32) | lo;                                                  \
+        v = kMin ? (o < v ? o : v) : (o > v ? o : v);                                                  \
+    }
+    CHESS_MM_STEP(0x111, 0xf) CHESS_MM_STEP(0x112, 0xf) CHESS_MM_STEP(0x114, 0xf) CHESS_MM_STEP(0x118, 0xf)
+    CHESS_MM_STEP(0x142, 0xa) CHESS_MM_STEP(0x143, 0xc)
+#undef CHESS_MM_STEP
+    return v;
+}
+
+// Sum of a double over each row of 16 lanes (DPP row shifts); the total is in lane 15 of the row.
+__device__ __forceinline__ double row16_sum(double d)
+{
+#define CHESS_RS_STEP(ctrl)                                                                            \
+    {                                                                                                  \
+        const uint64_t b = (uint64_t)__double_as_longlong(d);                                          \
+        const unsigned lo = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)b, ctrl, 0xf, 0xf, false); \
+        const unsigned hi = (unsigned)__builtin_amdgcn_update_dpp(0, (int)(unsigned)(b >> 32), ctrl, 0xf, 0xf, false); \
+        d += __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));                             \
+    }
+    CHESS_RS_STEP(0x111) CHESS_RS_STEP(0x112) CHESS_RS_STEP(0x114) CHESS_RS_STEP(0x118)
+#undef CHESS_RS_STEP
+    return d;
+}
 
 struct Cut {
     uint64_t thr;   // in the shifted domain: key << shift
@@ -65,11 +111,10 @@ struct Cut {
     int shift;
 };
 
-// Find the cut of the top-k among the non-empty keys in LDS.  k = k_of(number of non-empty keys).
-// A non-empty slot is kept iff (key << shift) > thr, or (key << shift) == thr and it is among the
-// first `ties` such slots.  Uniform over the workgroup; every thread must call it.
+// Cut of the top-k among the non-empty keys in LDS by radix select alone: the fallback of find_cut for
+// score distributions that pile more than kMaxMembers keys into one linear bin.  Same contract.
 template <class KFn>
-__device__ __forceinline__ Cut find_cut(const uint64_t* keys, int n_slots, KFn k_of, Shared& sh)
+__device__ __forceinline__ Cut find_cut_radix(const uint64_t* keys, int n_slots, KFn k_of, Shared& sh)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // what the keys have in common: OR, AND and the number of non-empty ones
@@ -141,6 +186,104 @@ __device__ __forceinline__ Cut find_cut(const uint64_t* keys, int n_slots, KFn k
     return cut;
 }
 
+// Find the cut of the top-k among the non-empty keys in LDS.  k = k_of(number of non-empty keys).
+// A non-empty slot is kept iff (key << shift) > thr, or (key << shift) == thr and it is among the
+// first `ties` such slots.  Uniform over the workgroup; every thread must call it.
+//
+// One histogram pass over kBins bins that are LINEAR in the score between the smallest and the largest
+// (a monotone map, so a higher bin means a strictly larger score), a scan from the top finds the bin
+// the k-th largest key falls in, and the few keys of that bin are ranked exactly by (key, slot).
+template <class KFn>
+__device__ __forceinline__ Cut find_cut(const uint64_t* keys, int n_slots, KFn k_of, Shared& sh)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    auto f_add = [](int a, int b) { return a + b; };
+    uint64_t lo_k = ~0ull, hi_k = 0ull;
+    int nv = 0;
+    for (int i = tid; i < n_slots; i += kSelThreads) {
+        const uint64_t k = keys[i];
+        if (k) { lo_k = k < lo_k ? k : lo_k; hi_k = k > hi_k ? k : hi_k; ++nv; }
+    }
+    if (tid == 0) { sh.kmin = ~0ull; sh.kmax = 0ull; sh.n_valid = 0; sh.n_mem = 0; }
+#pragma unroll
+    for (int j = 0; j < kBins / kSelThreads; ++j) sh.hist[tid + j * kSelThreads] = 0;
+    __syncthreads();
+    lo_k = wave_minmax<true>(lo_k);
+    hi_k = wave_minmax<false>(hi_k);
+    nv = wave_scan(nv, 0, f_add);
+    if (lane == 63) {
+        atomicMin(&sh.kmin, (unsigned long long)lo_k);
+        atomicMax(&sh.kmax, (unsigned long long)hi_k);
+        atomicAdd(&sh.n_valid, nv);
+    }
+    __syncthreads();
+    const int n_valid = sh.n_valid;
+    const uint64_t kmin = sh.kmin, kmax = sh.kmax;
+    const int k = k_of(n_valid);
+    Cut cut;
+    cut.shift = 0;
+    if (k <= 0) { cut.thr = ~0ull; cut.ties = 0; return cut; }
+    if (k >= n_valid) { cut.thr = 0ull; cut.ties = kKeepAll; return cut; }
+    if (kmin == kmax) { cut.thr = kmin; cut.ties = k; return cut; }      // every key is the same: first k slots
+    const double smin = key_score(kmin);
+    const double scale = (double)kBins / (key_score(kmax) - smin);
+    auto bin_of = [&](uint64_t key) {
+        const int b = (int)((key_score(key) - smin) * scale);
+        return min(max(b, 0), kBins - 1);
+    };
+    for (int i = tid; i < n_slots; i += kSelThreads) {
+        const uint64_t key = keys[i];
+        if (key) atomicAdd(&sh.hist[bin_of(key)], 1);
+    }
+    __syncthreads();
+    // thread t owns bins kBins-1-4t .. kBins-4-4t, so thread order is score order descending
+    constexpr int kPer = kBins / kSelThreads;
+    int c[kPer], own = 0;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) { c[j] = sh.hist[kBins - 1 - kPer * tid - j]; own += c[j]; }
+    const int incl_w = wave_scan(own, 0, f_add);
+    if (lane == 63) sh.wave_a[wave] = incl_w;
+    __syncthreads();
+    int above = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) above += w < wave ? sh.wave_a[w] : 0;
+    above += incl_w - own;                                    // keys in bins above this thread's
+    if (above < k && k <= above + own) {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) {
+            if (above < k && k <= above + c[j]) { sh.digit = kBins - 1 - kPer * tid - j; sh.rem = k - above; sh.cnt = c[j]; }
+            above += c[j];
+        }
+    }
+    __syncthreads();
+    const int bin = sh.digit, want = sh.rem, cnt = sh.cnt;
+    if (cnt > kMaxMembers) return find_cut_radix(keys, n_slots, k_of, sh);
+    for (int i = tid; i < n_slots; i += kSelThreads) {
+        const uint64_t key = keys[i];
+        if (key && bin_of(key) == bin) {
+            const int at = atomicAdd(&sh.n_mem, 1);
+            sh.mem_key[at] = key;
+            sh.mem_slot[at] = i;
+        }
+    }
+    __syncthreads();
+    if (tid < cnt) {                                          // exact rank of member tid by (key desc, slot asc)
+        const uint64_t mine = sh.mem_key[tid];
+        const int my_slot = sh.mem_slot[tid];
+        int rank = 0, n_gt = 0;
+        for (int j = 0; j < cnt; ++j) {
+            const uint64_t kj = sh.mem_key[j];
+            n_gt += kj > mine;
+            rank += kj > mine || (kj == mine && sh.mem_slot[j] < my_slot);
+        }
+        if (rank == want - 1) { sh.thr = mine; sh.rem = want - n_gt; }
+    }
+    __syncthreads();
+    cut.thr = sh.thr;
+    cut.ties = sh.rem;
+    return cut;
+}
+
 // Ordered compaction: emit(pos, slot) for the kept slots in ascending slot order; returns their number.
 // Wave w owns a contiguous quarter of the slots and walks it 64 slots at a time with ballots.
 template <class Out>
@@ -208,32 +351,34 @@ template <bool kDirect, class Map>
 __device__ __forceinline__ void score_range(const float* __restrict__ base, int lo, int hi, Map unit_of,
                                             const double (&pr)[8], uint64_t* dst)
 {
+#ifndef CHESS_FLY
+#define CHESS_FLY 8
+#endif
+    constexpr int kFly = CHESS_FLY;                  // units per 16-lane group in flight
     const int g16 = threadIdx.x >> 4, ln = threadIdx.x & 15;
-    for (int s0 = lo; s0 < hi; s0 += 64) {           // 4 units per 16-lane group in flight
-        int slot[4], unit[4];
-        float4 va[4], vb[4];
+    for (int s0 = lo; s0 < hi; s0 += 16 * kFly) {
+        int slot[kFly], unit[kFly];
+        float4 va[kFly], vb[kFly];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
+        for (int x = 0; x < kFly; ++x) {
             slot[x] = s0 + 16 * x + g16;
             unit[x] = slot[x] < hi ? unit_of(slot[x]) : -1;
-            va[x] = make_float4(0, 0, 0, 0);
-            vb[x] = va[x];
-            if (unit[x] >= 0) {
-                const float4* p = reinterpret_cast<const float4*>(base + (size_t)unit[x] * kHeadDim) + ln * 2;
-                va[x] = p[0];
-                vb[x] = p[1];
-            }
+            // always load (unit 0 when the slot has no unit): a branch here would make the compiler wait
+            // for each vector before asking for the next
+            const float4* p = reinterpret_cast<const float4*>(base + (size_t)max(unit[x], 0) * kHeadDim) + ln * 2;
+            va[x] = p[0];
+            vb[x] = p[1];
         }
 #pragma unroll
-        for (int x = 0; x < 4; ++x) {
+        for (int x = 0; x < kFly; ++x) {
+            if (s0 + 16 * x >= hi) break;             // uniform over the workgroup
             double d = 0.0;
             d = fma(pr[0], (double)va[x].x, d); d = fma(pr[1], (double)va[x].y, d);
             d = fma(pr[2], (double)va[x].z, d); d = fma(pr[3], (double)va[x].w, d);
             d = fma(pr[4], (double)vb[x].x, d); d = fma(pr[5], (double)vb[x].y, d);
             d = fma(pr[6], (double)vb[x].z, d); d = fma(pr[7], (double)vb[x].w, d);
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) d += __shfl_xor(d, off);
-            if (ln == 0 && slot[x] < hi) {
+            d = row16_sum(d);
+            if (ln == 15 && slot[x] < hi) {
                 const uint64_t key = unit[x] >= 0 ? order_key(d) : 0ull;
                 if (kDirect) dst[slot[x]] = key;
                 else publish_u64(dst + slot[x], key);
@@ -275,7 +420,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     uint64_t* pub3 = pub2 + sp.cap2;                                 //   page slots
     int32_t* ids = page_ids + row * g.max_sel;
     const int B = g.page_size;
-    const int L = min(max(seq_lens[b], 0), g.max_pages * B);
+    const int L_raw = seq_lens[b];
+    // probe: sum of the group's query rows (dims 8*ln .. 8*ln+7 of this lane), g ascending; requested
+    // before anything waits on the length
+    double pr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int r = 0; r < g.group; ++r) {
+        const uint4 v = *reinterpret_cast<const uint4*>(q + ((size_t)b * g.n_q_heads + h * g.group + r) * kHeadDim + (tid & 15) * 8);
+        pr[0] += (double)__uint_as_float(v.x << 16); pr[1] += (double)__uint_as_float(v.x & 0xffff0000u);
+        pr[2] += (double)__uint_as_float(v.y << 16); pr[3] += (double)__uint_as_float(v.y & 0xffff0000u);
+        pr[4] += (double)__uint_as_float(v.z << 16); pr[5] += (double)__uint_as_float(v.z & 0xffff0000u);
+        pr[6] += (double)__uint_as_float(v.w << 16); pr[7] += (double)__uint_as_float(v.w & 0xffff0000u);
+    }
+    const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
     if (P <= s + w) {                                                 // safety pages cover the sequence
@@ -287,18 +443,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     }
     const int nc = ceil_div_i(P, g.n_c), ng = ceil_div_i(nc, g.n_g);
 
-    // probe: sum of the group's query rows (dims 8*ln .. 8*ln+7 of this lane), g ascending
-    double pr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    {
-        const int ln = tid & 15;
-        for (int r = 0; r < g.group; ++r) {
-            const uint4 v = *reinterpret_cast<const uint4*>(q + ((size_t)b * g.n_q_heads + h * g.group + r) * kHeadDim + ln * 8);
-            pr[0] += (double)__uint_as_float(v.x << 16); pr[1] += (double)__uint_as_float(v.x & 0xffff0000u);
-            pr[2] += (double)__uint_as_float(v.y << 16); pr[3] += (double)__uint_as_float(v.y & 0xffff0000u);
-            pr[4] += (double)__uint_as_float(v.z << 16); pr[5] += (double)__uint_as_float(v.z & 0xffff0000u);
-            pr[6] += (double)__uint_as_float(v.w << 16); pr[7] += (double)__uint_as_float(v.w & 0xffff0000u);
-        }
-    }
     const int k_budget = sp.budget_pages > 0 ? sp.budget_pages : clamp_i(ceil_bp(P, sp.budget_bp), 1, P);
     const int kc_target = ceil_div_i(sp.over_chunk * k_budget, g.n_c);
     const int plan = sp.plan;
@@ -309,19 +453,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
         *lo = min(n_slots, m * per);
         *hi = min(n_slots, *lo + per);
     };
-    // barrier p of this launch, then pull the level's published keys into LDS
-    auto meet_and_pull = [&](int p, const uint64_t* pub, int n_slots) -> bool {
-        if (kSolo) { __syncthreads(); return true; }
-        if (!cluster_barrier(&meta[0], p * C, sh)) {
-            if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return false;
-        }
+    // pull a level's published keys into LDS
+    auto pull = [&](const uint64_t* pub, int n_slots) {
         for (int i0 = 0; i0 < n_slots; i0 += 4 * kSelThreads) {
             uint64_t v[4];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
                 const int i = i0 + x * kSelThreads + tid;
-                v[x] = i < n_slots ? observe_u64(pub + i) : 0ull;
+                v[x] = observe_u64(pub + min(i, n_slots - 1));        // unconditional: all four stay in flight
             }
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
@@ -330,6 +469,15 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
             }
         }
         __syncthreads();
+    };
+    // barrier p of this launch, then pull
+    auto meet_and_pull = [&](int p, const uint64_t* pub, int n_slots) -> bool {
+        if (kSolo) { __syncthreads(); return true; }
+        if (!cluster_barrier(&meta[0], p * C, sh)) {
+            if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
+        }
+        pull(pub, n_slots);
         return true;
     };
     int lo, hi;
@@ -393,7 +541,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
             }
         }
         if (!ok || m != 0) return;
-        for (int i = tid; i < slots3; i += kSelThreads) keys[i] = observe_u64(pub3 + i);
+        pull(pub3, slots3);
     }
     __syncthreads();
     PROF_MARK();                                                      // 11: barrier + pull
