@@ -75,7 +75,9 @@ SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages
     if (ctx->force_splits > 0) return {ctx->force_splits, ctx->force_waves};
     int waves = 4;
     if (pairs * cdiv(tiles, 4) < 2LL * ctx->n_cu) waves = 1;
-    int64_t ns = clampi(cdiv(target, pairs), 1, cdiv(tiles, waves));
+    // all workgroups resident at once: a second round of workgroups would double a short kernel
+    const int64_t resident = (int64_t)(waves == 4 ? ctx->dec_blocks4 : ctx->dec_blocks1) * ctx->n_cu;
+    int64_t ns = clampi(std::min<int64_t>(cdiv(target, pairs), std::max<int64_t>(1, resident / pairs)), 1, cdiv(tiles, waves));
     ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 1024 / g.group));   // the merge keeps (m, l) of every split in LDS
     while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
     return {(int)ns, waves};
@@ -153,6 +155,9 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
     c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
     c->workspace_bytes = align_up(c->ws_err_off + 256, 256);
+    c->dec_blocks4 = c->dec_blocks1 = 2;
+    if (chess::decode_occupancy(g.page_size, 4, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
+    if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
     c->force_cluster = 0;
     c->occ_lds = -1;
     c->occ_blocks = 0;

@@ -94,6 +94,7 @@ struct chess_ctx {
     size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
+    int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
     int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
 };
@@ -118,6 +119,7 @@ hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, 
                          const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
+hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);
 
 // page_ids == nullptr: every page of the sequence.  n_splits >= 1; the last split of a (sequence,

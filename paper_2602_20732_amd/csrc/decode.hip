@@ -91,7 +91,11 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
                                                          const int32_t* __restrict__ n_selected, Geom g,
                                                          float scale_log2, int n_splits, float* __restrict__ out,
                                                          float* __restrict__ ws_acc, float* __restrict__ ws_ml,
-                                                         int32_t* __restrict__ arrivals)
+                                                         int32_t* __restrict__ arrivals
+#ifdef CHESS_PROF
+                                                         , int32_t* __restrict__ prof
+#endif
+                                                         )
 {
     constexpr int PPT = 32 / B;
     __shared__ float lds_o[NW][kMaxGroup][kHeadDim];
@@ -100,6 +104,14 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#ifdef CHESS_PROF
+    long long prof_t[8];
+    int prof_n = 0;
+#define DPROF_MARK() prof_t[prof_n++] = wall_clock64()
+#else
+#define DPROF_MARK()
+#endif
+    DPROF_MARK();
     const int m16 = lane & 15, grp = lane >> 4;
     const int G = g.group, H = g.n_kv_heads;
     const size_t row = (size_t)b * H + h;
@@ -133,6 +145,7 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    DPROF_MARK();                                     // 1: lengths and first page numbers known
     Tile<B> cur;
     if (t < n_tiles) load_tile<B>(cur, t, n_pages, raw_cur, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
     for (; t < n_tiles; t += stride) {
@@ -201,6 +214,7 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
+    DPROF_MARK();                                     // 2: tiles done
 
     // merge the waves of this workgroup through LDS: lane holds O^T[d = 16*blk + 4*grp + r][head m16]
 #pragma unroll
@@ -236,11 +250,25 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
         }
     }
     if (n_splits == 1) return;
+    DPROF_MARK();                                     // 3: waves combined, partial published
     if (!arrive_last(arrivals + row, n_splits, &lds_last)) return;
+    DPROF_MARK();                                     // 4: arrived (last split only from here)
 
     // ---- the last split of this (sequence, KV head) to finish merges all of them:
     // out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), always in split order, so the result does not
     // depend on which workgroup happens to be last
+    constexpr int kChunk = 8;                          // partial rows in flight per output pair
+    const int n_items = G * (kHeadDim / 2);
+    // the first rows of this thread's first output pair are requested together with the (m, l) pairs,
+    // so the merge costs one round trip to memory, not two
+    uint64_t first[kChunk];
+    {
+        const int idx = min((int)threadIdx.x, n_items - 1);
+        const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
+#pragma unroll
+        for (int x = 0; x < kChunk; ++x)
+            first[x] = observe_u64(acc_g + ((row * n_splits + min(x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
+    }
     for (int idx = threadIdx.x; idx < n_splits * G; idx += 64 * NW) {
         const int sidx = idx / G, head = idx % G;
         ml_buf[idx] = __builtin_bit_cast(float2, observe_u64(ml_g + (row * n_splits + sidx) * G + head));
@@ -256,16 +284,18 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
             ml_buf[sidx * G + head].x = __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M) * inv;   // weight of split sidx
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += 64 * NW) {
+    for (int idx = threadIdx.x; idx < n_items; idx += 64 * NW) {
         const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
         float a0 = 0.f, a1 = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += 4) {
-            uint64_t v[4];
+        for (int s0 = 0; s0 < n_splits; s0 += kChunk) {
+            uint64_t v[kChunk];
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                v[x] = s0 + x < n_splits ? observe_u64(acc_g + ((row * n_splits + s0 + x) * G + head) * (kHeadDim / 2) + d2) : 0ull;
+            for (int x = 0; x < kChunk; ++x) {
+                if (s0 == 0 && idx == (int)threadIdx.x) v[x] = first[x];
+                else v[x] = observe_u64(acc_g + ((row * n_splits + min(s0 + x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
+            }
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
+            for (int x = 0; x < kChunk; ++x) {
                 if (s0 + x < n_splits) {
                     const float2 f = __builtin_bit_cast(float2, v[x]);
                     const float wt = ml_buf[(s0 + x) * G + head].x;
@@ -276,6 +306,11 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
         }
         *reinterpret_cast<float2*>(out + ((size_t)b * g.n_q_heads + h * G + head) * kHeadDim + 2 * d2) = make_float2(a0, a1);
     }
+#ifdef CHESS_PROF
+    DPROF_MARK();                                     // 5: merged
+    if (threadIdx.x == 0)
+        for (int i = 1; i < prof_n; ++i) prof[row * 8 + i] = (int)(prof_t[i] - prof_t[i - 1]);
+#endif
 }
 
 hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
@@ -287,11 +322,28 @@ hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_po
     const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     const dim3 grid(n_splits, g.n_kv_heads, batch), block(64 * waves);
     void (*kern)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
-                 const int32_t*, Geom, float, int, float*, float*, float*, int32_t*);
+                 const int32_t*, Geom, float, int, float*, float*, float*, int32_t*
+#ifdef CHESS_PROF
+                 , int32_t*
+#endif
+                 );
     if (g.page_size == 16) kern = waves == 4 ? decode_kernel<16, 4> : decode_kernel<16, 1>;
     else                   kern = waves == 4 ? decode_kernel<32, 4> : decode_kernel<32, 1>;
     return launch(kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
-                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
+                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals
+#ifdef CHESS_PROF
+                        , reinterpret_cast<int32_t*>(ws_ml) + (1 << 16)       // profiling builds: a corner of the workspace
+#endif
+                        );
+}
+
+hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu)
+{
+    if (page_size == 16)
+        return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 4>, 256, 0)
+                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 1>, 64, 0);
+    return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 4>, 256, 0)
+                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1>, 64, 0);
 }
 
 __global__ void zero_kernel(int32_t* p, size_t n)
