@@ -260,7 +260,9 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     }
     const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
     const int64_t capacity = (int64_t)ctx->occ_blocks * ctx->n_cu;
-    int64_t cluster = std::min<int64_t>(capacity / (2 * pairs), cdiv(sp.cap3, 32));
+    // ... and no more members than leave each about 13 vectors per 16-lane group at page level: beyond that the
+    // barrier skew grows faster than the scoring time shrinks (measured at 64 pairs: 4 members beat 6 and 8)
+    int64_t cluster = std::min<int64_t>(capacity / (2 * pairs), cdiv(sp.cap3, 208));
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, 32);
 

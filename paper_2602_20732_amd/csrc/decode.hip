@@ -146,25 +146,17 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     DPROF_MARK();                                     // 1: lengths and first page numbers known
-    Tile<B> cur;
-    if (t < n_tiles) load_tile<B>(cur, t, n_pages, raw_cur, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
-    for (; t < n_tiles; t += stride) {
-        Tile<B> nxt;
-        const bool more = t + stride < n_tiles;
-        if (more) {
-            load_tile<B>(nxt, t + stride, n_pages, raw_nxt, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
-            fetch_ids<B>(raw_nxt, t + 2 * stride, ids, g.max_sel);
-        }
-
+    // one tile: scores, online softmax, P.V
+    auto process = [&](Tile<B>& tl) {
         // scores of this lane's head for tokens 8*grp + e, e = 0..7 (c = 0 gives e 0..3, c = 1 gives 4..7)
         f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
-            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.k[0][st]), qop[st], s0, 0, 0, 0);
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.k[1][st]), qop[st], s1, 0, 0, 0);
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.k[0][st]), qop[st], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.k[1][st]), qop[st], s1, 0, 0, 0);
         }
         const int slot = (8 * grp) / B, tok0 = (8 * grp) % B;
-        const int nt = PPT == 1 ? cur.ntok[0] : (slot ? cur.ntok[PPT - 1] : cur.ntok[0]);
+        const int nt = PPT == 1 ? tl.ntok[0] : (slot ? tl.ntok[PPT - 1] : tl.ntok[0]);
         float x[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -191,8 +183,8 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
             pl[e] = (__bf16)(p[e] - (float)hi);
         }
         // a partly filled tile: unused token slots of V may hold anything (NaN included); zero them
-        bool partial = cur.ntok[0] < B;
-        if (PPT > 1) partial = partial || cur.ntok[PPT - 1] < B;
+        bool partial = tl.ntok[0] < B;
+        if (PPT > 1) partial = partial || tl.ntok[PPT - 1] < B;
         if (partial) {
             uint32_t keep[4];
 #pragma unroll
@@ -200,17 +192,40 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
                 keep[wd] = ((tok0 + 2 * wd < nt) ? 0x0000ffffu : 0u) | ((tok0 + 2 * wd + 1 < nt) ? 0xffff0000u : 0u);
 #pragma unroll
             for (int blk = 0; blk < 8; ++blk) {
-                cur.v[blk].x &= keep[0]; cur.v[blk].y &= keep[1]; cur.v[blk].z &= keep[2]; cur.v[blk].w &= keep[3];
+                tl.v[blk].x &= keep[0]; tl.v[blk].y &= keep[1]; tl.v[blk].z &= keep[2]; tl.v[blk].w &= keep[3];
             }
         }
 #pragma unroll
         for (int blk = 0; blk < 8; ++blk) {
             f32x4 acc = o[blk] * alpha;
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.v[blk]), ph, acc, 0, 0, 0);
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(cur.v[blk]), pl, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.v[blk]), ph, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.v[blk]), pl, acc, 0, 0, 0);
             o[blk] = acc;
         }
-        if (more) cur = nxt;
+    };
+    // The next tile is always requested before the current one is computed, in the same straight-line block, so
+    // the compiler waits only for the older loads (a load under its own branch would force a wait for everything
+    // outstanding).  After the last tile the "next" request repeats the current tile: it hits in cache and is dropped.
+    if (t < n_tiles) {
+        Tile<B> cur, nxt;
+        load_tile<B>(cur, t, n_pages, raw_cur, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+#ifdef CHESS_PROF_WAIT
+        DPROF_MARK();                                 // block table entry read, K/V requested
+        __builtin_amdgcn_s_waitcnt(0);
+        DPROF_MARK();                                 // first tile arrived
+#endif
+        for (; t < n_tiles; t += stride) {
+            const bool more = t + stride < n_tiles;
+            int raw_use[PPT];
+#pragma unroll
+            for (int s = 0; s < PPT; ++s) raw_use[s] = more ? raw_nxt[s] : raw_cur[s];
+            load_tile<B>(nxt, more ? t + stride : t, n_pages, raw_use, bt_row, k_pool, v_pool, H, h, L, P, m16, grp);
+            fetch_ids<B>(raw_nxt, t + 2 * stride, ids, g.max_sel);
+            process(cur);
+            cur = nxt;
+#pragma unroll
+            for (int s = 0; s < PPT; ++s) raw_cur[s] = raw_use[s];
+        }
     }
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
@@ -332,7 +347,7 @@ hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_po
     return launch(kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
                         page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals
 #ifdef CHESS_PROF
-                        , reinterpret_cast<int32_t*>(ws_ml) + (1 << 16)       // profiling builds: a corner of the workspace
+                        , reinterpret_cast<int32_t*>(ws_ml) - 1024            // profiling builds: the unused end of the partial rows
 #endif
                         );
 }
