@@ -169,7 +169,7 @@ def main():
                           slot_nsel[j], out, ws)
 
     kern = {}
-    for name, fn, launches in (("summarize_tail", only_tail, 1), ("select (3 level kernels)", only_select, 3),
+    for name, fn, launches in (("summarize_tail", only_tail, 1), ("select", only_select, 1),
                                ("sparse_decode", only_decode, 1)):
         ms, _ = timed(fn, args.steps, min(args.warmup, 8), not args.eager)
         kern[name] = {"us_per_step": round(ms * 1e3, 3), "kernel_launches_per_step": launches}
