@@ -128,3 +128,23 @@ def classify_selection(gpu_ids, gpu_n, ref: OracleRun, wl, plan: oracle.Plan):
                 0 <= p < ps.shape[2] and abs(ps[b, h, p] - cut) < 1e-5 * max(1.0, abs(cut)) for p in diff)
             (near if ok else hard).append((b, h, sorted(diff)))
     return hard, near
+
+
+def host_subset(wl: workload.Workload, seqs):
+    """Host arrays (K bits, V bits, Q bits, block table, seq lens) of the chosen sequences only, with their pages
+    gathered into a compact pool (the oracle does not care where pages live)."""
+    sp = wl.spec
+    bt = wl.block_table.cpu().numpy()
+    sl = wl.seq_lens.cpu().numpy()[list(seqs)]
+    P = [-(-int(n) // sp.page_size) for n in sl]
+    phys = np.concatenate([bt[b, :P[i]] for i, b in enumerate(seqs)]) if sum(P) else np.zeros(0, np.int64)
+    idx = torch.as_tensor(phys, dtype=torch.long, device=wl.k_pool.device)
+    K = workload.bf16_bits(wl.k_pool[idx])
+    V = workload.bf16_bits(wl.v_pool[idx])
+    Q = workload.bf16_bits(wl.q[list(seqs)])
+    bt2 = np.full((len(seqs), sp.max_pages), -1, np.int32)
+    off = 0
+    for i in range(len(seqs)):
+        bt2[i, :P[i]] = np.arange(off, off + P[i])
+        off += P[i]
+    return K, V, Q, bt2, sl.astype(np.int32)
