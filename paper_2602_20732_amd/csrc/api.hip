@@ -73,11 +73,14 @@ SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages
     const int64_t pairs = (int64_t)batch * g.n_kv_heads;
     const int64_t target = 4LL * ctx->n_cu;
     if (ctx->force_splits > 0) return {ctx->force_splits, ctx->force_waves};
-    int waves = 4;
-    if (pairs * cdiv(tiles, 4) < 2LL * ctx->n_cu) waves = 1;
+    const int waves = 4;
     // all workgroups resident at once: a second round of workgroups would double a short kernel
-    const int64_t resident = (int64_t)(waves == 4 ? ctx->dec_blocks4 : ctx->dec_blocks1) * ctx->n_cu;
-    int64_t ns = clampi(std::min<int64_t>(cdiv(target, pairs), std::max<int64_t>(1, resident / pairs)), 1, cdiv(tiles, waves));
+    const int64_t resident = (int64_t)ctx->dec_blocks4 * ctx->n_cu;
+    // the workgroup that finishes last merges ns partial rows per output; tile time falls as 1/ns and merge
+    // time grows as G*ns/32 (in units of one memory round trip), so the best split count is about sqrt(8*tiles/G)
+    int64_t ns = (int64_t)std::llround(std::sqrt(8.0 * (double)tiles / g.group));
+    ns = std::min<int64_t>(ns, std::max<int64_t>(1, resident / pairs));
+    ns = clampi(ns, 1, cdiv(tiles, waves));
     ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 1024 / g.group));   // the merge keeps (m, l) of every split in LDS
     while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
     return {(int)ns, waves};
