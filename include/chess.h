@@ -153,6 +153,11 @@ int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag);
  * chess_select (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
 int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster);
 
+/* Test hook: on = 1 makes every level of chess_select find its cut by the general path (radix select
+ * on the keys in LDS) that otherwise only serves tied or very large levels; 0 restores the automatic
+ * choice.  The selected pages are the same either way. */
+int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on);
+
 /* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 1024,
  * waves in {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
  * not fit the workspace for max_batch sequences. */

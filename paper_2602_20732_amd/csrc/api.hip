@@ -162,10 +162,11 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     if (chess::decode_occupancy(g.page_size, 4, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
     if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
     c->force_cluster = 0;
+    c->force_general_cut = 0;
     c->occ_lds = -1;
     c->occ_blocks = 0;
-    c->ws_zero_off = c->ws_meta_off;
-    c->ws_zero_bytes = c->workspace_bytes - c->ws_meta_off;
+    c->ws_zero_off = c->ws_keys_off;
+    c->ws_zero_bytes = c->workspace_bytes - c->ws_keys_off;
     c->force_splits = 0;
     c->force_waves = 4;
     *out = c;
@@ -250,11 +251,12 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     sp.cap_keys = (int32_t)bd.slots;
     sp.cap_kg = (int32_t)bd.kg;
     sp.cap_kc = (int32_t)bd.kc;
-    const size_t lds = (size_t)sp.cap_keys * 8 + align_up((size_t)(sp.cap_kg + sp.cap_kc) * 4, 8);
-    if (lds + 4096 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+    sp.general_cut = ctx->force_general_cut;
+    const size_t lds = chess::select_lds_bytes(sp, ctx->geom.max_sel);
+    if (lds + 8192 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;   // the kernel's static LDS is below 8 KB
 
-    // cluster size: every workgroup of the grid must be resident at once (the members of a cluster
-    // wait for each other), with half the device's capacity left as margin
+    // cluster size: the members of a cluster wait for each other's keys, so every workgroup of the grid has to fit
+    // on the device at once
     if (ctx->occ_lds != (int)lds) {
         int blocks = 0;
         if (chess::select_occupancy((int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
@@ -263,11 +265,10 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     }
     const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
     const int64_t capacity = (int64_t)ctx->occ_blocks * ctx->n_cu;
-    // ... and no more members than leave each about 13 vectors per 16-lane group at page level: beyond that the
-    // barrier skew grows faster than the scoring time shrinks (measured at 64 pairs: 4 members beat 6 and 8)
-    int64_t cluster = std::min<int64_t>(capacity / (2 * pairs), cdiv(sp.cap3, 208));
+    // ... and no more members than leave each a full request (8 vectors per 16-lane group) at page level
+    int64_t cluster = std::min<int64_t>(capacity / pairs, cdiv(sp.cap3, 128));
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
-    cluster = clampi(cluster, 1, 32);
+    cluster = clampi(cluster, 1, chess::kSelMaxCluster);
 
     char* wb = static_cast<char*>(workspace);
     chess::SelectWs ws{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), ctx->key_stride,
@@ -294,8 +295,15 @@ int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag)
 
 int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster)
 {
-    if (!ctx || cluster < 0 || cluster > 32) return CHESS_EINVAL;
+    if (!ctx || cluster < 0 || cluster > chess::kSelMaxCluster) return CHESS_EINVAL;
     ctx->force_cluster = cluster;
+    return CHESS_OK;
+}
+
+int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on)
+{
+    if (!ctx || (on != 0 && on != 1)) return CHESS_EINVAL;
+    ctx->force_general_cut = on;
     return CHESS_OK;
 }
 

@@ -26,17 +26,19 @@ struct SelectParams {
     int32_t plan, sink, window, budget_pages, budget_bp, over_chunk, over_grid, rho_g_bp, rho_c_bp, rho_p_bp;
     int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
     int32_t cap_keys, cap_kg, cap_kc;   // LDS capacities: keys of one level, kept grids, kept chunks
+    int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
 };
 
 constexpr int kSelThreads = 256;
-constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): [0] barrier arrivals, [1] members that left
+constexpr int kSelMaxCluster = 32;   // most workgroups per (sequence, KV head)
+constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): [0] members that are done with the published keys
 
 // Select scratch in the caller's workspace (device pointers).
 struct SelectWs {
-    uint64_t* keys;                  // [rows][key_stride]  published candidate keys: grids | chunk slots | page slots
-    int64_t key_stride;
+    uint64_t* keys;                  // [rows][key_stride]  published candidate keys: grids | chunk slots | page slots;
+    int64_t key_stride;              //   all zero between launches
     int32_t* meta;                   // [rows][kSelMetaStride], zero between launches
-    int32_t* error;                  // one word: set if a cluster barrier was given up
+    int32_t* error;                  // one word: set if a wait for published keys was given up
 #ifdef CHESS_PROF
     int32_t* prof;                   // [rows][16] phase durations in 10 ns ticks (profiling builds only)
 #endif
@@ -94,6 +96,7 @@ struct chess_ctx {
     size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
+    int force_general_cut;                                 // 0 = automatic
     int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
     int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
@@ -119,6 +122,7 @@ hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, 
                          const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
+size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);
 

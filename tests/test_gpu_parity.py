@@ -122,6 +122,36 @@ def test_exact_ties_go_to_lowest_index():
     assert gpu.ids[0, 0, :gpu.nsel[0, 0]].tolist() == list(range(0, 17)) + [126, 127]
 
 
+def test_tie_groups_at_the_cut():
+    """Three distinct key rows dealt by page number: every level has a few large groups of exactly tied scores,
+    so a cut falls inside a group (lowest indices win), with fewer and with more tied keys than the
+    in-register ranking of the select kernel holds."""
+    sp = workload.WorkloadSpec("groups", 2, (8192, 8192), 4, 1, 16, ("fixed", 128), (1, 1), 1, 2, budget_pages=5,
+                               pages_per_chunk=2, chunks_per_grid=2)
+    wl = workload.generate(sp, 9, seq_lens=[8192, 5000])
+    rows = [wl.k_pool[wl.block_table[0, j].item(), 0, 0].clone() for j in (0, 1, 2)]
+    for b in range(2):
+        for j in range(-(-int(wl.seq_lens[b]) // 16)):
+            wl.k_pool[wl.block_table[b, j].item(), 0, :] = rows[j % 3]
+    for bp in (5000, 3000, 9000):
+        plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=1, window_pages=2, rho_g_bp=bp, rho_c_bp=5000, rho_p_bp=bp)
+        check_all(sp, wl, plan, max_sel=sp.max_pages, dense=False, label=f"tie groups {bp}")
+
+
+@pytest.mark.parametrize("cluster", [1, 4])
+def test_general_cut_gives_the_same_page_lists(cluster):
+    """The cut that tied or very large levels fall back to (radix select in LDS), forced on every level."""
+    for sp, wl in ((workload.spec("cfg2", scale=1 / 2), None), (RAGGED, RAGGED_LENS)):
+        wl = workload.generate(sp, 123, seq_lens=wl)
+        plan = plan_of(sp)
+        lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+        lib.debug_force_general_cut(True)
+        gpu = run_gpu(lib, wl, plan, dense=False, cluster=cluster)
+        ref = run_oracle(wl, plan, sp.max_pages, dense=False)
+        assert np.array_equal(gpu.ids, ref.ids) and np.array_equal(gpu.nsel, ref.nsel)
+        lib.close()
+
+
 def test_short_and_boundary_lengths():
     sp = workload.WorkloadSpec("short", 8, (0, 161), 4, 2, 16, ("fixed", 32), (1, 1), 2, 3, budget_pages=2,
                                pages_per_chunk=2, chunks_per_grid=2)
