@@ -29,7 +29,10 @@ struct SelectParams {
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
 };
 
-constexpr int kSelThreads = 256;
+#ifndef CHESS_SEL_THREADS
+#define CHESS_SEL_THREADS 256
+#endif
+constexpr int kSelThreads = CHESS_SEL_THREADS;   // workgroup of the selection kernels
 constexpr int kSelMaxCluster = 32;   // most workgroups per (sequence, KV head)
 constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): [0] members that are done with the published keys
 

@@ -32,8 +32,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     const int L_raw = seq_lens[b];
     double pr[8];
     load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);   // requested before anything waits on the length
-#pragma unroll
-    for (int j = 0; j < kBins / kSelThreads; ++j) sh.hist[tid + j * kSelThreads] = 0;   // as cut_in_registers wants it
+    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;

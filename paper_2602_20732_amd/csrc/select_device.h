@@ -111,12 +111,15 @@ __device__ __forceinline__ uint64_t lane_read64(uint64_t v, int src)
 }
 
 constexpr int kBins = 1024;                 // linear score bins of the cut
-#ifndef CHESS_MAX_FLY
-#define CHESS_MAX_FLY 8
+#ifdef CHESS_MAX_FLY
+constexpr int kMaxFly = CHESS_MAX_FLY;
+#else
+constexpr int kMaxFly = kSelThreads >= 1024 ? 4 : 8;   // units a 16-lane group requests before it waits
 #endif
-constexpr int kMaxFly = CHESS_MAX_FLY;      // most units a 16-lane group requests before it waits
+constexpr int kSelGroups = kSelThreads / 16;  // 16-lane groups of a workgroup
 constexpr int kFastMembers = 64;            // most keys the bin at the cut may hold on the register path
-constexpr int kRegsSmall = 4, kRegsLarge = 17;   // keys per thread the register path is built for
+constexpr int kRegsSmall = 1024 / kSelThreads;                           // keys per thread the register path is built
+constexpr int kRegsLarge = (4352 + kSelThreads - 1) / kSelThreads;       //   for: levels of up to 1024 / 4352+ slots
 constexpr int kMaxRuns = kRegsLarge * kSelWaves;  // 64-slot runs of the largest level the register path holds
 
 struct Shared {
@@ -127,7 +130,7 @@ struct Shared {
     int wave_a[kSelWaves], wave_b[kSelWaves];
     int digit, rem, cnt, n_valid, n_mem, flag;
     unsigned int or_lo, or_hi, and_lo, and_hi;
-    uint64_t st_min[kSelWaves], st_max[kSelWaves];   // the waves' smallest / largest key of a level
+    unsigned st_min[kSelWaves], st_max[kSelWaves];   // upper halves of the waves' smallest / largest key of a level
     int st_cnt[kSelWaves];
 };
 
@@ -190,7 +193,7 @@ __device__ __forceinline__ Cut find_cut_radix(const uint64_t* keys, int n_slots,
     uint64_t prefix = 0;
     int want = k;
     for (int p = 0; p < n_pass; ++p) {
-        sh.hist[tid] = 0;                              // kSelThreads == 256 bins
+        if (tid < 256) sh.hist[tid] = 0;               // 256 digits
         __syncthreads();
         for (int i = tid; i < n_slots; i += kSelThreads) {
             const uint64_t key = keys[i];
@@ -200,7 +203,7 @@ __device__ __forceinline__ Cut find_cut_radix(const uint64_t* keys, int n_slots,
         }
         __syncthreads();
         // thread t looks at digit 255 - t, so thread order is digit order descending
-        const int c = sh.hist[255 - tid];
+        const int c = tid < 256 ? sh.hist[255 - tid] : 0;
         const int incl_w = wave_scan(c, 0, f_add);
         if (lane == 63) sh.wave_a[wave] = incl_w;
         __syncthreads();
@@ -267,48 +270,75 @@ __device__ __forceinline__ int compact_kept(const uint64_t* keys, int n_slots, c
     return total;
 }
 
-// Smallest key, largest key and number of non-empty keys of a level from the registers of the workgroup.
-// One workgroup barrier.
+// Minimum / maximum of a 32-bit unsigned value over the wave (DPP, no LDS); the result is in lane 63.
+template <bool kMin>
+__device__ __forceinline__ unsigned wave_minmax32(unsigned v)
+{
+    const int id = kMin ? -1 : 0;
+#define CHESS_MM_STEP(ctrl, rows)                                                                      \
+    {                                                                                                  \
+        const unsigned o = (unsigned)__builtin_amdgcn_update_dpp(id, (int)v, ctrl, rows, 0xf, false);  \
+        v = kMin ? min(v, o) : max(v, o);                                                              \
+    }
+    CHESS_MM_STEP(0x111, 0xf) CHESS_MM_STEP(0x112, 0xf) CHESS_MM_STEP(0x114, 0xf) CHESS_MM_STEP(0x118, 0xf)
+    CHESS_MM_STEP(0x142, 0xa) CHESS_MM_STEP(0x143, 0xc)
+#undef CHESS_MM_STEP
+    return v;
+}
+
+// A key at or below the smallest key, a key at or above the largest key (both from the upper halves of
+// the keys: bounds are all the binning needs) and the number of non-empty keys of a level, from the
+// registers of the workgroup.  One workgroup barrier.
 template <int R>
 __device__ __forceinline__ void level_stats(const uint64_t (&key)[R], Shared& sh, uint64_t* kmin, uint64_t* kmax, int* n_valid)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint64_t a = ~0ull, b = 0ull;
-    int n = 0;
+    unsigned a = ~0u, b = 0u;
+    int n = 0;                                        // wave-uniform
 #pragma unroll
-    for (int x = 0; x < R; ++x)
-        if (key[x] != 0) { a = key[x] < a ? key[x] : a; b = key[x] > b ? key[x] : b; ++n; }
-    a = wave_minmax<true>(a);
-    b = wave_minmax<false>(b);
-    n = wave_scan(n, 0, [](int x, int y) { return x + y; });
+    for (int x = 0; x < R; ++x) {
+        const bool valid = key[x] != 0;
+        const unsigned hi = (unsigned)(key[x] >> 32);
+        a = valid ? min(a, hi) : a;
+        b = valid ? max(b, hi) : b;
+        n += __popcll(__ballot(valid));
+    }
+    a = wave_minmax32<true>(a);
+    b = wave_minmax32<false>(b);
     if (lane == 63) { sh.st_min[wave] = a; sh.st_max[wave] = b; sh.st_cnt[wave] = n; }
     __syncthreads();
-    a = ~0ull; b = 0ull; n = 0;
+    a = ~0u; b = 0u; n = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
-        const uint64_t wa = sh.st_min[w], wb = sh.st_max[w];
-        a = wa < a ? wa : a;
-        b = wb > b ? wb : b;
+        a = min(a, sh.st_min[w]);
+        b = max(b, sh.st_max[w]);
         n += sh.st_cnt[w];
     }
-    *kmin = a; *kmax = b; *n_valid = n;
+    *kmin = (uint64_t)a << 32;
+    *kmax = ((uint64_t)b << 32) | 0xffffffffull;
+    *n_valid = n;
 }
+
+// Where bin b of the histogram is stored: lane l of a wave owns bins 16 (63 - l) .. 16 (63 - l) + 15 (lane 0
+// the highest scores) and reads its j-th bin from word 64 j + l, so the 64 lanes hit 64 different banks.
+__device__ __forceinline__ int hist_word(int b) { return ((b & 15) << 6) | (63 - (b >> 4)); }
 
 // Cut and ordered compaction of one level whose keys the workgroup holds in registers: thread t has
 // slot x * 256 + t in key[x] (0 = empty).  k = k_of(n_valid) of the n_valid non-empty keys are kept, by
 // (key descending, slot ascending); emit(pos, slot) is called for each kept slot with its position in
 // ascending slot order.  Returns the number kept, or -1, having emitted nothing, when this path does not
-// apply (all keys equal, or more than kFastMembers keys share the bin at the cut).  Uniform over the
-// workgroup: every thread must call it.  sh.hist must be all zero and sh.n_mem zero on entry, and they
-// are again on a return >= 0.
+// apply (more than kFastMembers keys share the bin at the cut).  Uniform over the workgroup: every thread
+// must call it.  sh.hist must be all zero and sh.n_mem zero on entry, and they are again on a return >= 0.
 //
-// The kBins bins are LINEAR in the score between kmin and kmax (a monotone map, so a higher bin means a
-// strictly larger score); a scan from the top finds the bin the k-th largest key falls in, and the few
-// keys of that bin are ranked exactly by (key, slot).
+// The kBins bins are LINEAR in the score between the scores of klo and khi (klo <= every key <= khi): a
+// monotone map, so a higher bin means a strictly larger score; the scale only has to be positive, not exact.
+// A scan from the top finds the bin the k-th largest key falls in, and the few keys of that bin are ranked
+// exactly by (key, slot).
 template <int R, class KFn, class Out>
-__device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_slots, uint64_t kmin, uint64_t kmax,
+__device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_slots, uint64_t klo, uint64_t khi,
                                                 int n_valid, KFn k_of, Out emit, Shared& sh, Prof& prof)
 {
+    static_assert(kBins == 16 * kWave, "a lane owns 16 bins");
     static_assert(R * kSelWaves <= kMaxRuns && R * kSelWaves <= 128, "run prefix is held in two values per lane");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -317,44 +347,42 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
     const int k = k_of(n_valid);
     if (k <= 0) { __syncthreads(); return 0; }
     const bool all = k >= n_valid;
-    if (!all && kmin == kmax) return -1;
 
     int bin[R];
     int cutbin = -1, want = 0, cnt = 0;
     if (!all) {
-        const double smin = key_score(kmin);
-        const double scale = (double)kBins / (key_score(kmax) - smin);
+        const double smin = key_score(klo);
+        const double scale = (double)kBins * __builtin_amdgcn_rcp(key_score(khi) - smin);
 #pragma unroll
         for (int x = 0; x < R; ++x) {
             bin[x] = -1;
             if (x * kSelThreads < n_slots && key[x] != 0) {
                 const int bx = (int)((key_score(key[x]) - smin) * scale);
                 bin[x] = min(max(bx, 0), kBins - 1);
-                atomicAdd(&sh.hist[bin[x]], 1);
+                atomicAdd(&sh.hist[hist_word(bin[x])], 1);
             }
         }
         __syncthreads();
         prof.mark();
-        // every wave scans the whole histogram from the top: lane l owns bins kBins-1-16l .. kBins-16-16l
-        constexpr int kPer = kBins / kWave;
-        int c[kPer], own = 0;
+        // every wave scans the whole histogram from the top
+        int own = 0;
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) { c[j] = sh.hist[kBins - kPer * (lane + 1) + j]; own += c[j]; }
+        for (int j = 0; j < 16; ++j) own += sh.hist[64 * j + lane];
         const int incl = wave_scan(own, 0, f_add);
-        int above = incl - own;                                   // keys in bins above this lane's
-        const bool here = above < k && k <= incl;                 // true in exactly one lane
-        int my_bin = 0, my_want = 0, my_cnt = 0;
-        if (here) {
-#pragma unroll
-            for (int j = kPer - 1; j >= 0; --j) {
-                if (above < k && k <= above + c[j]) { my_bin = kBins - kPer * (lane + 1) + j; my_want = k - above; my_cnt = c[j]; }
-                above += c[j];
-            }
-        }
+        const bool here = incl - own < k && k <= incl;            // true in exactly one lane
         const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(here)) - 1);
-        cutbin = __builtin_amdgcn_readlane(my_bin, src);
-        want = __builtin_amdgcn_readlane(my_want, src);
-        cnt = __builtin_amdgcn_readlane(my_cnt, src);
+        const int k_rem = k - (__builtin_amdgcn_readlane(incl, src) - __builtin_amdgcn_readlane(own, src));
+        // the 16 bins of that lane, highest first, one per lane of the first row
+        const int c = lane < 16 ? sh.hist[64 * (15 - lane) + src] : 0;
+        int ci = c;
+        ci += __builtin_amdgcn_update_dpp(0, ci, 0x111, 0xf, 0xf, false);
+        ci += __builtin_amdgcn_update_dpp(0, ci, 0x112, 0xf, 0xf, false);
+        ci += __builtin_amdgcn_update_dpp(0, ci, 0x114, 0xf, 0xf, false);
+        ci += __builtin_amdgcn_update_dpp(0, ci, 0x118, 0xf, 0xf, false);
+        const int at = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(lane < 16 && ci >= k_rem)) - 1);
+        cutbin = 16 * (63 - src) + 15 - at;
+        cnt = __builtin_amdgcn_readlane(c, at);
+        want = k_rem - (__builtin_amdgcn_readlane(ci, at) - cnt);
         if (cnt > kFastMembers) return -1;
         prof.mark();
     } else {
@@ -383,11 +411,10 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
     prof.mark();
 
     // leave the histogram clean for the next level (its readers are past the barrier above)
-#pragma unroll
-    for (int j = 0; j < kBins / kSelThreads; ++j) sh.hist[tid + j * kSelThreads] = 0;
+    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     if (tid == 0) sh.n_mem = 0;
 
-    // every wave ranks the cut bin's keys: lane j takes member j
+    // every wave ranks the cut bin's keys: lane j takes member j and meets the others through lane reads
     uint64_t thr = 0;
     int thr_slot = -1, my_slot = 0;
     uint64_t kept_mask = 0;
@@ -396,8 +423,8 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
         my_slot = lane < cnt ? sh.mem_slot[lane] : 0;
         int rank = 0;
         for (int i = 0; i < cnt; ++i) {
-            const uint64_t ki = sh.mem_key[i];
-            const int si = sh.mem_slot[i];
+            const uint64_t ki = lane_read64(mine, i);
+            const int si = __builtin_amdgcn_readlane(my_slot, i);
             rank += ki > mine || (ki == mine && si < my_slot);
         }
         kept_mask = __ballot(lane < cnt && rank < want);
@@ -419,9 +446,14 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
     // sure keys in earlier runs
     const int n_runs = (n_slots + kWave - 1) / kWave;
     const int c0 = lane < n_runs ? sh.run_gt[lane] : 0;
-    const int c1 = lane + kWave < n_runs ? sh.run_gt[min(lane + kWave, kMaxRuns - 1)] : 0;
-    const int i0 = wave_scan(c0, 0, f_add), i1 = wave_scan(c1, 0, f_add);
-    const int e0 = i0 - c0, e1 = i1 - c1 + __builtin_amdgcn_readlane(i0, 63);
+    const int i0 = wave_scan(c0, 0, f_add);
+    const int e0 = i0 - c0;
+    int e1 = 0;
+    if (R * kSelWaves > kWave) {
+        const int c1 = lane + kWave < n_runs ? sh.run_gt[min(lane + kWave, kMaxRuns - 1)] : 0;
+        const int i1 = wave_scan(c1, 0, f_add);
+        e1 = i1 - c1 + __builtin_amdgcn_readlane(i0, 63);
+    }
 #pragma unroll
     for (int x = 0; x < R; ++x) {
         if (x * kSelThreads >= n_slots) break;                    // uniform
@@ -444,12 +476,12 @@ __device__ __forceinline__ void score_rows(const float* __restrict__ base, int l
                                            const double (&pr)[8], uint64_t* dst)
 {
     const int g16 = threadIdx.x >> 4, ln = threadIdx.x & 15;
-    for (int s0 = lo; s0 < hi; s0 += 16 * kFly) {
+    for (int s0 = lo; s0 < hi; s0 += kSelGroups * kFly) {
         int slot[kFly], unit[kFly];
         float4 va[kFly], vb[kFly];
 #pragma unroll
         for (int x = 0; x < kFly; ++x) {
-            slot[x] = s0 + 16 * x + g16;
+            slot[x] = s0 + kSelGroups * x + g16;
             unit[x] = slot[x] < hi ? unit_of(slot[x]) : -1;
             // always load (unit 0 when the slot has no unit): a branch here would make the compiler wait
             // for each vector before asking for the next
@@ -459,7 +491,7 @@ __device__ __forceinline__ void score_rows(const float* __restrict__ base, int l
         }
 #pragma unroll
         for (int x = 0; x < kFly; ++x) {
-            if (s0 + 16 * x >= hi) break;             // uniform over the workgroup
+            if (s0 + kSelGroups * x >= hi) break;             // uniform over the workgroup
             double d = 0.0;
             d = fma(pr[0], (double)va[x].x, d); d = fma(pr[1], (double)va[x].y, d);
             d = fma(pr[2], (double)va[x].z, d); d = fma(pr[3], (double)va[x].w, d);
@@ -595,8 +627,7 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
     __syncthreads();
     const Cut cut = find_cut_radix(keys, n_slots, k_of, sh);
     n = compact_kept(keys, n_slots, cut, emit, sh);
-#pragma unroll
-    for (int j = 0; j < kBins / kSelThreads; ++j) sh.hist[threadIdx.x + j * kSelThreads] = 0;
+    for (int i = threadIdx.x; i < kBins; i += kSelThreads) sh.hist[i] = 0;
     if (threadIdx.x == 0) sh.n_mem = 0;
     __syncthreads();
     return n;
