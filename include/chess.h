@@ -122,7 +122,7 @@ int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* bloc
  * list of logical page numbers; if the sequence has at most s + w pages, all of them.
  * `plan` is a host pointer.  CHESS_EINVAL if s + w + (largest possible k_p) exceeds
  * max_selected_pages; CHESS_ENOTSUP if a level can have more candidates than fit in LDS.
- * Uses the workspace (published keys, cluster barrier counters).
+ * Uses the workspace (published keys, a counter per sequence and KV head).
  */
 int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
                  const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace,
@@ -143,6 +143,20 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
                        void* workspace, void* stream);
 
+/*
+ * One decode step of a layer in a single launch: chess_select followed by chess_sparse_decode over the
+ * list it produces (Sec. 3.2 then Sec. 4.3), with the same results as the two calls: the page list is
+ * the one chess_select writes, `out` is attention over exactly those pages.  The list stays on chip
+ * between the two stages; it is also written to page_ids / n_selected unless those are NULL (pass them
+ * to reuse the list in later steps, as the paper does between reselections, Sec. 3.3).
+ * Arguments, layouts and errors as for the two calls.  The summaries must be current
+ * (chess_summarize_tail first, when the tail page has grown).
+ */
+int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                      const int32_t* block_table, const int32_t* seq_lens, const void* summaries, int32_t batch,
+                      const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
+                      void* workspace, void* stream);
+
 /* Synchronous check (copies one word back, waits for the device): *flag is non-zero if any kernel
  * using this workspace gave up a bounded wait -- which cannot happen unless the device was shared
  * with work that kept this library's workgroups from becoming resident together.  Results written
@@ -150,7 +164,7 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
 int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag);
 
 /* Test hook: force the number of workgroups that cooperate on one (sequence, KV head) in
- * chess_select (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
+ * chess_select and chess_decode_step (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
 int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster);
 
 /* Test hook: on = 1 makes every level of chess_select find its cut by the general path (radix select

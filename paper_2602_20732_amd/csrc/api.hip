@@ -157,7 +157,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_meta_off = align_up(c->ws_keys_off + rows * c->key_stride * sizeof(uint64_t), 256);
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
     c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
-    c->workspace_bytes = align_up(c->ws_err_off + 256, 256);
+    c->ws_prof_off = align_up(c->ws_err_off + 256, 256);            // profiling builds only: 48 words per row
+    c->workspace_bytes = align_up(c->ws_prof_off + rows * 48 * sizeof(int32_t), 256);
     c->dec_blocks4 = c->dec_blocks1 = 2;
     if (chess::decode_occupancy(g.page_size, 4, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
     if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
@@ -165,6 +166,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->force_general_cut = 0;
     c->occ_lds = -1;
     c->occ_blocks = 0;
+    c->step_occ_lds = -1;
+    c->step_occ_blocks = 0;
     c->ws_zero_off = c->ws_keys_off;
     c->ws_zero_bytes = c->workspace_bytes - c->ws_keys_off;
     c->force_splits = 0;
@@ -230,17 +233,12 @@ int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream)
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
-int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
-                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace, void* stream)
+// Checks a plan against the configuration and fills the kernel-side parameters.
+static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::SelectParams* out)
 {
-    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
-    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(workspace)) & 15)
-        return CHESS_EINVAL;
     Bounds bd;
     if (!plan_bounds(ctx, plan, &bd)) return CHESS_EINVAL;
     if ((int64_t)plan->sink_pages + plan->window_pages + bd.kp > ctx->geom.max_sel) return CHESS_EINVAL;
-
     chess::SelectParams sp{};
     sp.plan = plan->plan; sp.sink = plan->sink_pages; sp.window = plan->window_pages;
     sp.budget_pages = plan->budget_pages; sp.budget_bp = plan->budget_bp;
@@ -252,6 +250,30 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     sp.cap_kg = (int32_t)bd.kg;
     sp.cap_kc = (int32_t)bd.kc;
     sp.general_cut = ctx->force_general_cut;
+    *out = sp;
+    return CHESS_OK;
+}
+
+static chess::SelectWs select_ws(const chess_ctx* ctx, void* workspace)
+{
+    char* wb = static_cast<char*>(workspace);
+    return chess::SelectWs{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), ctx->key_stride,
+                           reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off), reinterpret_cast<int32_t*>(wb + ctx->ws_err_off)
+#ifdef CHESS_PROF
+                           , reinterpret_cast<int32_t*>(wb + ctx->ws_prof_off)
+#endif
+    };
+}
+
+int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
+                 const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace, void* stream)
+{
+    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(workspace)) & 15)
+        return CHESS_EINVAL;
+    chess::SelectParams sp;
+    if (int rc = prepare_select(ctx, plan, &sp)) return rc;
     const size_t lds = chess::select_lds_bytes(sp, ctx->geom.max_sel);
     if (lds + 8192 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;   // the kernel's static LDS is below 8 KB
 
@@ -270,19 +292,60 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, chess::kSelMaxCluster);
 
-    char* wb = static_cast<char*>(workspace);
-    chess::SelectWs ws{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), ctx->key_stride,
-                       reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off), reinterpret_cast<int32_t*>(wb + ctx->ws_err_off)
-#ifdef CHESS_PROF
-                       , reinterpret_cast<int32_t*>(wb + ctx->ws_acc_off)     // profiling builds borrow the decode partials
-#endif
-    };
+    const chess::SelectWs ws = select_ws(ctx, workspace);
     const char* sb = static_cast<const char*>(summaries);
     hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
                                         reinterpret_cast<const float*>(sb + ctx->page_off),
                                         reinterpret_cast<const float*>(sb + ctx->chunk_off),
                                         reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, (int)cluster,
                                         sp, ws, lds, page_ids, n_selected, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                      const int32_t* block_table, const int32_t* seq_lens, const void* summaries, int32_t batch,
+                      const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
+                      void* workspace, void* stream)
+{
+    if (!ctx || !q || !k_pool || !v_pool || !block_table || !seq_lens || !summaries || !plan || !out || !workspace)
+        return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
+         reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace)) & 15)
+        return CHESS_EINVAL;
+    chess::SelectParams sp;
+    if (int rc = prepare_select(ctx, plan, &sp)) return rc;
+    int union_off = 0;
+    const size_t lds = chess::step_lds_bytes(sp, ctx->geom.max_sel, &union_off);
+    if (lds + 8192 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;
+
+    if (ctx->step_occ_lds != (int)lds) {
+        int blocks = 0;
+        if (chess::step_occupancy(ctx->geom.page_size, (int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        ctx->step_occ_lds = (int)lds;
+        ctx->step_occ_blocks = blocks;
+    }
+    if (ctx->step_occ_blocks < 1) return CHESS_ENOTSUP;
+    const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
+    const int64_t capacity = (int64_t)ctx->step_occ_blocks * ctx->n_cu;
+    // members: enough that a member's share of the page-level candidates is one request (8 vectors per 16-lane
+    // group) and that every wave of the cluster has at most one tile of the list to attend to, as far as all
+    // workgroups of the grid fit on the device at once
+    const int64_t tiles = cdiv(ctx->geom.max_sel, chess::kTileTokens / ctx->geom.page_size);
+    int64_t cluster = std::min<int64_t>(capacity / pairs, std::max<int64_t>(cdiv(sp.cap3, 128), cdiv(tiles, 4)));
+    if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
+    cluster = clampi(cluster, 1, chess::kSelMaxCluster);
+    if (pairs * cluster > 4LL * ctx->n_cu + pairs) return CHESS_ENOTSUP;   // partial rows of the workspace
+
+    const chess::SelectWs ws = select_ws(ctx, workspace);
+    const char* sb = static_cast<const char*>(summaries);
+    char* wb = static_cast<char*>(workspace);
+    chess::StepLaunch sl{static_cast<const uint16_t*>(q), reinterpret_cast<const float*>(sb + ctx->page_off),
+                         reinterpret_cast<const float*>(sb + ctx->chunk_off), reinterpret_cast<const float*>(sb + ctx->grid_off),
+                         static_cast<const uint16_t*>(k_pool), static_cast<const uint16_t*>(v_pool), block_table, seq_lens,
+                         page_ids, n_selected, out, reinterpret_cast<float*>(wb + ctx->ws_acc_off),
+                         reinterpret_cast<float*>(wb + ctx->ws_ml_off), reinterpret_cast<int32_t*>(wb + ctx->ws_cnt_off)};
+    hipError_t e = chess::launch_step(ctx, sl, batch, (int)cluster, sp, ws, lds, union_off, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

@@ -96,12 +96,13 @@ struct chess_ctx {
     int max_splits;
     int force_splits, force_waves;                         // 0 = automatic
     size_t ws_acc_off, ws_ml_off, workspace_bytes;
-    size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off;   // select scratch, decode arrival counters, error word
+    size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off, ws_prof_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
     int force_general_cut;                                 // 0 = automatic
     int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
     int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
+    int step_occ_lds, step_occ_blocks;                     // ... and of the fused step kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
 };
 
@@ -124,6 +125,27 @@ hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, 
                          const float* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
                          const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
+// Device pointers of one fused decode-step launch.
+struct StepLaunch {
+    const uint16_t* q;
+    const float* pages;
+    const float* chunks;
+    const float* grids;
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const int32_t* block_table;
+    const int32_t* seq_lens;
+    int32_t* page_ids;
+    int32_t* n_selected;
+    float* out;
+    float* ws_acc;
+    float* ws_ml;
+    int32_t* arrivals;
+};
+hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
+                       const SelectWs& ws, size_t lds_bytes, int union_off, hipStream_t stream);
+size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off);
+hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu);
 hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
 size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);

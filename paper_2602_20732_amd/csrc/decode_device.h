@@ -1,0 +1,317 @@
+// Device-side building blocks of paged decode attention over a list of pages read in place (Sec. 4.3,
+// App. B), shared by the decode kernels and the fused decode-step kernel.
+//
+// Work unit: one wave, one tile of 32 tokens (two 16-token pages or one 32-token page), all G <= 16
+// query heads of the KV head at once, so both products are dense 16 x 16 x 32 bf16 MFMA tiles:
+//   S^T[token][head] = K[token][d] . Q^T[d][head]      4 MFMA per 16 tokens (d = 128)
+//   O^T[d][head]    += V^T[d][token] . P[token][head]   8 MFMA per tile and per half of P
+// K rows ([token][d], d contiguous) and V rows ([d][token], tokens contiguous) are both contiguous
+// along the contraction index, so every lane feeds its MFMA operands with plain 128-bit global
+// loads -- no LDS staging and no transpose.  The 16 token rows of the two K products are chosen so
+// that the 8 softmax weights a lane ends up holding are exactly the 8 contraction slots it must
+// supply to the P.V product: the weights never move between lanes.
+// P is split into a bf16 head and a bf16 remainder (two MFMAs), which keeps the weights to ~2^-17
+// relative; the row sum l uses the fp32 weights.
+//
+// Softmax state (m, l) of head j lives in the four lanes with lane % 16 == j; O^T accumulators are
+// 8 x float4 per lane.  Tiles are dealt round-robin over splits and waves; the waves of a workgroup are
+// merged through LDS; the last split of a (sequence, KV head) to finish merges all splits' partials, in
+// split order.
+#pragma once
+
+#include "chess_internal.h"
+
+namespace chess {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr float kNegBig = -1.0e30f;     // "no token yet" running maximum (log2 domain), finite on purpose
+
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <int B>
+struct Tile {
+    uint4 k[2][4];      // [product c][d step]
+    uint4 v[8];         // [16-row block of d]
+    int ntok[32 / B];   // valid tokens of each page slot of the tile (0 = slot unused)
+};
+
+// The logical page numbers of tile t as stored in the list (speculative: the index is clamped into the
+// row, validity is decided later), so that this load does not wait for the list length.
+template <int B>
+__device__ __forceinline__ void fetch_ids(int (&raw)[32 / B], int t, const int32_t* ids, int max_sel)
+{
+    constexpr int PPT = 32 / B;
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) raw[s] = ids ? ids[min(t * PPT + s, max_sel - 1)] : t * PPT + s;
+}
+
+// Request the K and V operands of tile t.  The physical page of a listed page comes from the block table, or,
+// when the caller has them at hand, from `phys_list` (physical pages in list order, n_pages >= 1 entries).
+template <int B>
+__device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const int (&raw)[32 / B], const int32_t* bt_row,
+                                          const int32_t* phys_list, const uint16_t* k_pool, const uint16_t* v_pool, int H,
+                                          int h, int L, int P, int m16, int grp)
+{
+    constexpr int PPT = 32 / B;
+    int64_t phys[PPT];
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) {
+        const bool ok = t * PPT + s < n_pages;
+        int lp = ok ? raw[s] : raw[0];                            // unused slot: alias the tile's first page
+        lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
+        const int pp = phys_list ? phys_list[min(ok ? t * PPT + s : t * PPT, n_pages - 1)] : bt_row[lp];
+        phys[s] = __builtin_amdgcn_readfirstlane(pp);
+        tl.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
+    }
+    // K: row m16 of product c is token T = 8*(m16/4) + 4*c + m16%4 of the tile
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int T = 8 * (m16 >> 2) + 4 * c + (m16 & 3);
+        const int slot = T / B, tok = T % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint4* src = reinterpret_cast<const uint4*>(k_pool + ((pg * H + h) * B + tok) * kHeadDim) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) tl.k[c][st] = src[st * 4];  // d = 32*st + 8*grp
+    }
+    // V^T: row d = 16*blk + m16, tokens 8*grp .. 8*grp+7 of the tile
+    {
+        const int T0 = 8 * grp;
+        const int slot = T0 / B, tok0 = T0 % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint16_t* base = v_pool + ((pg * H + h) * kHeadDim + m16) * B + tok0;
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) tl.v[blk] = *reinterpret_cast<const uint4*>(base + (size_t)blk * 16 * B);
+    }
+}
+
+// Online-softmax state of one wave: all G heads of one KV head.
+template <int B>
+struct WaveAcc {
+    static constexpr int PPT = 32 / B;
+    bf16x8 qop[4];      // Q^T operand: head m16, d = 32*st + 8*grp .. +7; heads >= G are zero columns
+    float m_run, l_run;
+    f32x4 o[8];
+
+    __device__ __forceinline__ void init(const uint16_t* __restrict__ q_rows, int G, int m16, int grp)
+    {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        const uint4* src = reinterpret_cast<const uint4*>(q_rows + (size_t)(m16 < G ? m16 : 0) * kHeadDim) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) qop[st] = as_bf16x8(m16 < G ? src[st * 4] : z);
+        m_run = kNegBig;
+        l_run = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // one tile: scores, online softmax, P.V
+    __device__ __forceinline__ void process(Tile<B>& tl, float scale_log2, int grp)
+    {
+        // scores of this lane's head for tokens 8*grp + e, e = 0..7 (c = 0 gives e 0..3, c = 1 gives 4..7)
+        f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.k[0][st]), qop[st], s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.k[1][st]), qop[st], s1, 0, 0, 0);
+        }
+        const int slot = (8 * grp) / B, tok0 = (8 * grp) % B;
+        const int nt = PPT == 1 ? tl.ntok[0] : (slot ? tl.ntok[PPT - 1] : tl.ntok[0]);
+        float x[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            x[e] = (tok0 + e < nt) ? s0[e] * scale_log2 : -INFINITY;
+            x[4 + e] = (tok0 + 4 + e < nt) ? s1[e] * scale_log2 : -INFINITY;
+        }
+        float tmax = x[0];
+#pragma unroll
+        for (int e = 1; e < 8; ++e) tmax = fmaxf(tmax, x[e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float p[8], psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(x[e] - m_new); psum += p[e]; }
+        l_run = l_run * alpha + psum;
+        bf16x8 ph, pl;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const __bf16 hi = (__bf16)p[e];
+            ph[e] = hi;
+            pl[e] = (__bf16)(p[e] - (float)hi);
+        }
+        // a partly filled tile: unused token slots of V may hold anything (NaN included); zero them
+        bool partial = tl.ntok[0] < B;
+        if (PPT > 1) partial = partial || tl.ntok[PPT - 1] < B;
+        if (partial) {
+            uint32_t keep[4];
+#pragma unroll
+            for (int wd = 0; wd < 4; ++wd)
+                keep[wd] = ((tok0 + 2 * wd < nt) ? 0x0000ffffu : 0u) | ((tok0 + 2 * wd + 1 < nt) ? 0xffff0000u : 0u);
+#pragma unroll
+            for (int blk = 0; blk < 8; ++blk) {
+                tl.v[blk].x &= keep[0]; tl.v[blk].y &= keep[1]; tl.v[blk].z &= keep[2]; tl.v[blk].w &= keep[3];
+            }
+        }
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) {
+            f32x4 acc = o[blk] * alpha;
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.v[blk]), ph, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(tl.v[blk]), pl, acc, 0, 0, 0);
+            o[blk] = acc;
+        }
+    }
+};
+
+// This wave's tiles t0, t0 + stride, ... < n_tiles of the list `ids` (nullptr: every page), whose first two
+// tiles' page numbers the caller has fetched already.
+// The next tile is always requested before the current one is computed, in the same straight-line block, so
+// the compiler waits only for the older loads (a load under its own branch would force a wait for everything
+// outstanding).  After the last tile the "next" request repeats the current tile: it hits in cache and is dropped.
+template <int B>
+__device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
+                                          int (&raw_cur)[32 / B], int (&raw_nxt)[32 / B], const int32_t* ids, int max_sel,
+                                          const int32_t* bt_row, const int32_t* phys_list, const uint16_t* k_pool,
+                                          const uint16_t* v_pool, int H, int h, int L, int P, float scale_log2, int m16,
+                                          int grp)
+{
+    constexpr int PPT = 32 / B;
+    if (t < n_tiles) {
+        Tile<B> cur, nxt;
+        load_tile<B>(cur, t, n_pages, raw_cur, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
+        for (; t < n_tiles; t += stride) {
+            const bool more = t + stride < n_tiles;
+            int raw_use[PPT];
+#pragma unroll
+            for (int s = 0; s < PPT; ++s) raw_use[s] = more ? raw_nxt[s] : raw_cur[s];
+            load_tile<B>(nxt, more ? t + stride : t, n_pages, raw_use, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
+            fetch_ids<B>(raw_nxt, t + 2 * stride, ids, max_sel);
+            acc.process(cur, scale_log2, grp);
+            cur = nxt;
+#pragma unroll
+            for (int s = 0; s < PPT; ++s) raw_cur[s] = raw_use[s];
+        }
+    }
+    acc.l_run += __shfl_xor(acc.l_run, 16);
+    acc.l_run += __shfl_xor(acc.l_run, 32);
+}
+
+// LDS the combine / merge below needs, in floats: [NW][16][128] accumulators, [NW][16] maxima, [NW][16] sums.
+template <int NW>
+struct DecodeLds {
+    static constexpr int kFloats = NW * kMaxGroup * kHeadDim + 2 * NW * kMaxGroup;
+    float* o;   // [NW][kMaxGroup][kHeadDim]
+    float* m;   // [NW][kMaxGroup]
+    float* l;   // [NW][kMaxGroup]
+    __device__ __forceinline__ explicit DecodeLds(float* base)
+        : o(base), m(base + NW * kMaxGroup * kHeadDim), l(base + NW * kMaxGroup * kHeadDim + NW * kMaxGroup) {}
+};
+
+// Merge the NW waves of this workgroup through LDS.  n_splits == 1: write `out` rows and return false.
+// Otherwise publish the workgroup's partial as split `split` and return true.
+template <int NW>
+__device__ __forceinline__ bool combine_waves(const f32x4 (&o)[8], float m_run, float l_run, DecodeLds<NW>& lds, int G,
+                                              int n_splits, int split, size_t row, float* __restrict__ out_rows,
+                                              float* __restrict__ ws_acc, float* __restrict__ ws_ml)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m16 = lane & 15, grp = lane >> 4;
+    // lane holds O^T[d = 16*blk + 4*grp + r][head m16]
+#pragma unroll
+    for (int blk = 0; blk < 8; ++blk)
+        *reinterpret_cast<f32x4*>(&lds.o[(wave * kMaxGroup + m16) * kHeadDim + 16 * blk + 4 * grp]) = o[blk];
+    if (grp == 0) { lds.m[wave * kMaxGroup + m16] = m_run; lds.l[wave * kMaxGroup + m16] = l_run; }
+    __syncthreads();
+
+    // combine this workgroup's waves; one thread per pair of adjacent d
+    uint64_t* acc_g = reinterpret_cast<uint64_t*>(ws_acc);           // partial rows as pairs of floats
+    uint64_t* ml_g = reinterpret_cast<uint64_t*>(ws_ml);             // (m, l) per partial row
+    for (int idx = threadIdx.x; idx < G * (kHeadDim / 2); idx += 64 * NW) {
+        const int head = idx / (kHeadDim / 2), d = 2 * (idx % (kHeadDim / 2));
+        float M = lds.m[head];
+#pragma unroll
+        for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, lds.m[wv * kMaxGroup + head]);
+        float a0 = 0.f, a1 = 0.f, l = 0.f;
+#pragma unroll
+        for (int wv = 0; wv < NW; ++wv) {
+            const float sc = __builtin_amdgcn_exp2f(lds.m[wv * kMaxGroup + head] - M);
+            a0 += lds.o[(wv * kMaxGroup + head) * kHeadDim + d] * sc;
+            a1 += lds.o[(wv * kMaxGroup + head) * kHeadDim + d + 1] * sc;
+            l += lds.l[wv * kMaxGroup + head] * sc;
+        }
+        if (n_splits == 1) {
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            *reinterpret_cast<float2*>(out_rows + (size_t)head * kHeadDim + d) = make_float2(a0 * inv, a1 * inv);
+        } else {
+            const size_t pr = (row * n_splits + split) * G + head;
+            publish_u64(acc_g + pr * (kHeadDim / 2) + d / 2, __builtin_bit_cast(uint64_t, make_float2(a0, a1)));
+            if (d == 0) publish_u64(ml_g + pr, __builtin_bit_cast(uint64_t, make_float2(M, l)));
+        }
+    }
+    return n_splits != 1;
+}
+
+// What the last split of a (sequence, KV head) to finish does: merge all splits' partials,
+// out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), always in split order, so the result does not
+// depend on which workgroup happens to be last.  `ml_buf`: LDS for n_splits * G float pairs.
+template <int NW>
+__device__ __forceinline__ void merge_splits(float2* ml_buf, int G, int n_splits, size_t row, float* __restrict__ out_rows,
+                                             const float* __restrict__ ws_acc, const float* __restrict__ ws_ml)
+{
+    const uint64_t* acc_g = reinterpret_cast<const uint64_t*>(ws_acc);
+    const uint64_t* ml_g = reinterpret_cast<const uint64_t*>(ws_ml);
+    constexpr int kChunk = 8;                          // partial rows in flight per output pair
+    const int n_items = G * (kHeadDim / 2);
+    // the first rows of this thread's first output pair are requested together with the (m, l) pairs,
+    // so the merge costs one round trip to memory, not two
+    uint64_t first[kChunk];
+    {
+        const int idx = min((int)threadIdx.x, n_items - 1);
+        const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
+#pragma unroll
+        for (int x = 0; x < kChunk; ++x)
+            first[x] = observe_u64(acc_g + ((row * n_splits + min(x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
+    }
+    for (int idx = threadIdx.x; idx < n_splits * G; idx += 64 * NW) {
+        const int sidx = idx / G, head = idx % G;
+        ml_buf[idx] = __builtin_bit_cast(float2, observe_u64(ml_g + (row * n_splits + sidx) * G + head));
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < G) {
+        const int head = threadIdx.x;
+        float M = kNegBig, l = 0.f;
+        for (int sidx = 0; sidx < n_splits; ++sidx) M = fmaxf(M, ml_buf[sidx * G + head].x);
+        for (int sidx = 0; sidx < n_splits; ++sidx) l += ml_buf[sidx * G + head].y * __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M);
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        for (int sidx = 0; sidx < n_splits; ++sidx)
+            ml_buf[sidx * G + head].x = __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M) * inv;   // weight of split sidx
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < n_items; idx += 64 * NW) {
+        const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
+        float a0 = 0.f, a1 = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += kChunk) {
+            uint64_t v[kChunk];
+#pragma unroll
+            for (int x = 0; x < kChunk; ++x) {
+                if (s0 == 0 && idx == (int)threadIdx.x) v[x] = first[x];
+                else v[x] = observe_u64(acc_g + ((row * n_splits + min(s0 + x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
+            }
+#pragma unroll
+            for (int x = 0; x < kChunk; ++x) {
+                if (s0 + x < n_splits) {
+                    const float2 f = __builtin_bit_cast(float2, v[x]);
+                    const float wt = ml_buf[(s0 + x) * G + head].x;
+                    a0 += f.x * wt;
+                    a1 += f.y * wt;
+                }
+            }
+        }
+        *reinterpret_cast<float2*>(out_rows + (size_t)head * kHeadDim + 2 * d2) = make_float2(a0, a1);
+    }
+}
+
+}  // namespace chess

@@ -49,7 +49,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
 
     uint64_t* pub1 = ws.keys + row * ws.key_stride;
     CascadeResult res;
-    const bool ok = cascade<kSolo>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
+    const bool ok = cascade<kSolo, false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
                                    grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pub1, m, C, m == 0, keys,
                                    kept_grids, kept_chunks, sel_pages, sh, &res, prof);
     if (!ok) {

@@ -27,6 +27,8 @@
 // and the workgroup leaves (the workspace then needs chess_workspace_init again).
 #pragma once
 
+#include <type_traits>
+
 #include "chess_internal.h"
 
 namespace chess {
@@ -661,12 +663,17 @@ struct CascadeResult {
 // zero and sh.n_mem zero on entry.  Returns false if a wait was given up.
 // The levels run through one copy of the code (a loop, not three inlined bodies): the kernel executes every
 // instruction about once, so its time is sensitive to how much code it has to fetch.
-template <bool kSolo>
+// kPhys: the caller goes on to read the kept pages, so the block-table entries of all page-level candidates are
+// requested ahead of the page-level scores (by every member, for all slots) and parked in phys_by_slot (LDS,
+// one word per slot); sel_phys[i] then receives the physical page of sel_pages[i].
+template <bool kSolo, bool kPhys>
 __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, const float* __restrict__ chunks_row,
                                         const float* __restrict__ grids_row, const double (&pr)[8], int P, const Geom& g,
                                         const SelectParams& sp, uint64_t* pub1, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
-                                        Shared& sh, CascadeResult* res, Prof& prof)
+                                        Shared& sh, CascadeResult* res, Prof& prof,
+                                        const int32_t* __restrict__ bt_row = nullptr, int32_t* phys_by_slot = nullptr,
+                                        int32_t* sel_phys = nullptr)
 {
     const int s = sp.sink, w = sp.window;
     const int nc = ceil_div_i(P, g.n_c), ng = ceil_div_i(nc, g.n_g);
@@ -699,7 +706,34 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         // this member's share of the level's slots: whole 16-slot rows
         const int per = ceil_div_i(ceil_div_i(n_slots, C), 16) * 16;
         const int lo = min(n_slots, m * per), hi = min(n_slots, lo + per);
-        score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
+        if (kPhys && level == 2) {
+            // block-table entries of every slot's page: in flight together with this member's vectors, parked in
+            // LDS once those have arrived (loads return in order, so this costs no wait of its own)
+            auto with_entries = [&](auto regs) {
+                constexpr int R = decltype(regs)::value;
+                int32_t e[R];
+#pragma unroll
+                for (int x = 0; x < R; ++x) {
+                    const int i = x * kSelThreads + (int)threadIdx.x;
+                    e[x] = 0;
+                    if (x * kSelThreads < n_slots) e[x] = bt_row[max(i < n_slots ? unit_of(i) : -1, 0)];
+                }
+                score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
+#pragma unroll
+                for (int x = 0; x < R; ++x) {
+                    const int i = x * kSelThreads + (int)threadIdx.x;
+                    if (i < n_slots) phys_by_slot[i] = e[x];
+                }
+            };
+            if (n_slots <= kRegsSmall * kSelThreads) with_entries(std::integral_constant<int, kRegsSmall>{});
+            else if (n_slots <= kRegsLarge * kSelThreads) with_entries(std::integral_constant<int, kRegsLarge>{});
+            else {
+                score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
+                for (int i = threadIdx.x; i < n_slots; i += kSelThreads) phys_by_slot[i] = bt_row[max(unit_of(i), 0)];
+            }
+        } else {
+            score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
+        }
         prof.mark();
         if (level == 2 && !want_l3) return true;
 
@@ -718,8 +752,10 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
             }
             return min(k, cap);
         };
-        const int n_kept = finish_level<kSolo>(pub, n_slots, general, keys, k_of,
-                                               [&](int pos, int slot) { out[pos] = unit_of(slot); }, sh, prof);
+        const int n_kept = finish_level<kSolo>(pub, n_slots, general, keys, k_of, [&](int pos, int slot) {
+            out[pos] = unit_of(slot);
+            if (kPhys && level == 2) sel_phys[pos] = phys_by_slot[slot];
+        }, sh, prof);
         if (n_kept < 0) return false;
         prof.mark();
         parents = out;

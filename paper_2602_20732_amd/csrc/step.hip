@@ -1,0 +1,196 @@
+// The whole decode step of one layer in one launch: coarse-to-fine page selection (Sec. 3.2, Alg. 1 stage 2)
+// followed at once by block-sparse attention over the selected pages, read in place (Sec. 4.3, App. B).
+//
+// A cluster of C workgroups per (sequence, KV head) runs the three selection levels (select_device.h); every
+// member ends up with the same page list in its LDS, so the list never travels through memory: member m
+// goes straight on to decode tiles m, m + C, ... of it (decode_device.h) as split m of C, and the last
+// member to finish merges the C partials.  Compared with chess_select + chess_sparse_decode this saves a
+// kernel boundary, the round trip of the list through HBM and the second kernel's start-up loads.
+// Member 0 also writes the list to page_ids / n_selected when the caller wants it.
+#include "decode_device.h"
+#include "select_device.h"
+
+namespace chess {
+
+static_assert(kSelThreads == 256, "the fused step decodes with four waves per workgroup");
+constexpr int kStepWaves = kSelThreads / kWave;
+
+struct StepArgs {
+    const uint16_t* q;
+    const float* pages;
+    const float* chunks;
+    const float* grids;
+    const uint16_t* k_pool;
+    const uint16_t* v_pool;
+    const int32_t* block_table;
+    const int32_t* seq_lens;
+    int32_t* page_ids;       // may be null
+    int32_t* n_selected;     // may be null
+    float* out;
+    float* ws_acc;
+    float* ws_ml;
+    int32_t* arrivals;
+    float scale_log2;
+    int32_t union_off;       // byte offset of the LDS region selection and decode share (after the page list)
+};
+
+// grid = (C, H_kv, batch)
+template <int B, bool kSolo>
+__global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, SelectParams sp, SelectWs ws)
+{
+    constexpr int PPT = 32 / B;
+    extern __shared__ unsigned long long lds_raw[];
+    int32_t* ids_l = reinterpret_cast<int32_t*>(lds_raw);                                  // [max_sel] the page list
+    int32_t* phys_l = ids_l + g.max_sel;                                                   // [max_sel] their physical pages
+    char* un = reinterpret_cast<char*>(lds_raw) + a.union_off;
+    uint64_t* keys = reinterpret_cast<uint64_t*>(un);                                      // selection's view
+    int32_t* kept_grids = reinterpret_cast<int32_t*>(keys + sp.cap_keys);
+    int32_t* kept_chunks = kept_grids + sp.cap_kg;
+    int32_t* phys_by_slot = kept_chunks + sp.cap_kc;                                       // [cap3]
+    DecodeLds<kStepWaves> dl(reinterpret_cast<float*>(un));                                // decode's view
+    __shared__ Shared sh;
+
+    const int m = blockIdx.x, C = gridDim.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, m16 = lane & 15, grp = lane >> 4;
+    const int G = g.group, H = g.n_kv_heads;
+    Prof prof;
+    prof.mark();
+    const size_t row = (size_t)b * H + h;
+    const uint16_t* q_rows = a.q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
+    float* out_rows = a.out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
+    const int L_raw = a.seq_lens[b];
+    double pr[8];
+    load_probe(q_rows, G, pr);                                        // requested before anything waits on the length
+    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
+    if (tid == 0) sh.n_mem = 0;
+    const int L = min(max(L_raw, 0), g.max_pages * B);
+    const int P = (L + B - 1) / B;
+    const int s = sp.sink, w = sp.window;
+    const int32_t* bt_row = a.block_table + (size_t)b * g.max_pages;
+    if (P == 0) {                                                     // empty sequence: no pages, zero output
+        if (m == 0) {
+            if (a.page_ids) for (int i = tid; i < g.max_sel; i += kSelThreads) a.page_ids[row * g.max_sel + i] = -1;
+            if (a.n_selected && tid == 0) a.n_selected[row] = 0;
+            for (int i = tid; i < G * kHeadDim; i += kSelThreads) out_rows[i] = 0.f;
+        }
+        return;
+    }
+    __syncthreads();
+    prof.mark();                                                      // prologue done
+
+    // ---- the page list, in every member's LDS
+    uint64_t* pub1 = ws.keys + row * ws.key_stride;
+    CascadeResult res;
+    res.n_kp = 0; res.ng = 0; res.slots2 = 0; res.slots3 = 0;
+    int n_sel;
+    if (P <= s + w) {                                                 // safety pages cover the sequence
+        n_sel = min(P, g.max_sel);
+        for (int i = tid; i < n_sel; i += kSelThreads) { ids_l[i] = i; phys_l[i] = bt_row[i]; }
+    } else {
+        // the block-table entries of the safety pages are requested now and used after the selection
+        const bool safety_early = s + w <= kSelThreads;
+        const int safety_lp = tid < s ? tid : P - w + (tid - s);
+        int safety_phys = 0;
+        if (safety_early && tid < s + w) safety_phys = bt_row[safety_lp];
+        // kept pages and their physical pages go straight to their places in the list, behind the sinks
+        const bool ok = cascade<kSolo, true>(a.pages + row * g.max_pages * kHeadDim, a.chunks + row * g.max_chunks * kHeadDim,
+                                             a.grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pub1, m, C, true, keys,
+                                             kept_grids, kept_chunks, ids_l + s, sh, &res, prof, bt_row, phys_by_slot,
+                                             phys_l + s);
+        if (!ok) {
+            if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return;
+        }
+        // union with the safety pages: sinks, kept pages, window -- already ascending
+        const int n_kp = res.n_kp;
+        n_sel = s + n_kp + w;
+        if (safety_early) {
+            if (tid < s + w) {
+                const int at = tid < s ? tid : n_kp + tid;
+                ids_l[at] = safety_lp;
+                phys_l[at] = safety_phys;
+            }
+        } else {
+            for (int i = tid; i < s + w; i += kSelThreads) {
+                const int lp = i < s ? i : P - w + (i - s), at = i < s ? i : n_kp + i;
+                ids_l[at] = lp;
+                phys_l[at] = bt_row[lp];
+            }
+        }
+    }
+    __syncthreads();
+    if (m == 0) {
+        if (a.page_ids) for (int i = tid; i < g.max_sel; i += kSelThreads) a.page_ids[row * g.max_sel + i] = i < n_sel ? ids_l[i] : -1;
+        if (a.n_selected && tid == 0) a.n_selected[row] = n_sel;
+    }
+    prof.mark();                                                      // list built
+
+    // ---- attention over this member's tiles of the list: split m of C
+    const int n_tiles = (n_sel + PPT - 1) / PPT;
+    const int stride = C * kStepWaves;
+    const int t = m + C * wave;
+    int raw_cur[PPT], raw_nxt[PPT];
+    fetch_ids<B>(raw_cur, t, ids_l, max(n_sel, 1));
+    fetch_ids<B>(raw_nxt, t + stride, ids_l, max(n_sel, 1));
+    WaveAcc<B> acc;
+    acc.init(q_rows, G, m16, grp);
+    run_tiles<B>(acc, t, stride, n_tiles, n_sel, raw_cur, raw_nxt, ids_l, max(n_sel, 1), bt_row, phys_l, a.k_pool, a.v_pool, H, h, L, P,
+                 a.scale_log2, m16, grp);
+    prof.mark();                                                      // tiles done
+    if (!combine_waves<kStepWaves>(acc.o, acc.m_run, acc.l_run, dl, G, C, m, row, out_rows, a.ws_acc, a.ws_ml)) return;
+    prof.mark();                                                      // partial published
+    if (!arrive_last(a.arrivals + row, C, &sh.flag)) return;
+    prof.mark();                                                      // last to arrive
+    merge_splits<kStepWaves>(reinterpret_cast<float2*>(un), G, C, row, out_rows, a.ws_acc, a.ws_ml);
+    if (!kSolo) clear_published(pub1, g, sp, res);                    // every member is done with the key words
+#ifdef CHESS_PROF
+    prof.mark();
+    if (tid == 0)
+        for (int i = 1; i < prof.n; ++i) ws.prof[row * 48 + i] = (int)(prof.t[i] - prof.t[i - 1]);
+#endif
+}
+
+template <int B, bool kSolo>
+static void (*step_fn())(StepArgs, Geom, SelectParams, SelectWs) { return step_kernel<B, kSolo>; }
+
+static void (*step_kernel_of(int page_size, bool solo))(StepArgs, Geom, SelectParams, SelectWs)
+{
+    if (page_size == 16) return solo ? step_fn<16, true>() : step_fn<16, false>();
+    return solo ? step_fn<32, true>() : step_fn<32, false>();
+}
+
+// Dynamic LDS of the fused kernel and where its shared region starts.
+size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off)
+{
+    const size_t list = ((size_t)max_sel * 2 * 4 + 15) / 16 * 16;                 // page list and physical pages
+    const size_t sel = (size_t)sp.cap_keys * 8 + ((size_t)(sp.cap_kg + sp.cap_kc + sp.cap3) * 4 + 7) / 8 * 8;
+    const size_t dec = (size_t)DecodeLds<kStepWaves>::kFloats * sizeof(float);
+    *union_off = (int)list;
+    return list + (sel > dec ? sel : dec);
+}
+
+hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu)
+{
+    for (bool solo : {false, true}) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kernel_of(page_size, solo)),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e != hipSuccess) return e;
+    }
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, step_kernel_of(page_size, false), kSelThreads, lds_bytes);
+}
+
+hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
+                       const SelectWs& ws, size_t lds_bytes, int union_off, hipStream_t stream)
+{
+    const Geom& g = ctx->geom;
+    StepArgs a;
+    a.q = sl.q; a.pages = sl.pages; a.chunks = sl.chunks; a.grids = sl.grids; a.k_pool = sl.k_pool; a.v_pool = sl.v_pool;
+    a.block_table = sl.block_table; a.seq_lens = sl.seq_lens; a.page_ids = sl.page_ids; a.n_selected = sl.n_selected;
+    a.out = sl.out; a.ws_acc = sl.ws_acc; a.ws_ml = sl.ws_ml; a.arrivals = sl.arrivals;
+    a.scale_log2 = ctx->sm_scale * 1.4426950408889634f;
+    a.union_off = union_off;
+    const dim3 grid(cluster, g.n_kv_heads, batch), block(kSelThreads);
+    return launch(step_kernel_of(g.page_size, cluster == 1), grid, block, lds_bytes, stream, a, g, sp, ws);
+}
+
+}  // namespace chess

@@ -33,6 +33,9 @@ class GpuRun:
     nsel: np.ndarray
     out: np.ndarray
     dense: np.ndarray
+    step_ids: np.ndarray = None      # the same step through the single-launch entry point
+    step_nsel: np.ndarray = None
+    step_out: np.ndarray = None
 
 
 def to_device(wl: workload.Workload):
@@ -67,10 +70,17 @@ def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool
     lib.sparse_decode(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, ids, nsel, out, ws)
     if dense:
         lib.dense_decode(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, dn, ws)
+    # the fused entry point: selection and attention in one launch, on a workspace of its own
+    ws2 = lib.new_workspace()
+    ids2 = torch.full_like(ids, -7)
+    nsel2 = torch.full_like(nsel, -7)
+    out2 = torch.full_like(out, float("nan"))
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids2, nsel2, out2, ws2)
     torch.cuda.synchronize()
-    assert lib.workspace_error(ws) == 0, "a kernel gave up a bounded wait"
+    assert lib.workspace_error(ws) == 0 and lib.workspace_error(ws2) == 0, "a kernel gave up a bounded wait"
     pv, cv, gv = (t[:batch].cpu().numpy() for t in lib.summary_views(summ))
-    return GpuRun(pv, cv, gv, ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dn.cpu().numpy())
+    return GpuRun(pv, cv, gv, ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dn.cpu().numpy(),
+                  ids2.cpu().numpy(), nsel2.cpu().numpy(), out2.cpu().numpy())
 
 
 @dataclass

@@ -32,8 +32,13 @@ def run_case(name, sample, dense_seq=0, seed=None):
     lib.select(wl.q, summ, wl.seq_lens, gpu_plan(plan), ids, nsel, ws)
     lib.sparse_decode(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out, ws)
     lib.dense_decode(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, dense, ws)
+    # the same step through the single-launch entry point, as bench.py times it
+    ids2, nsel2, out2 = torch.full_like(ids, -7), torch.full_like(nsel, -7), torch.full_like(out, float("nan"))
+    lib.decode_step(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, gpu_plan(plan), ids2, nsel2, out2, ws)
     torch.cuda.synchronize()
     assert lib.workspace_error(ws) == 0
+    assert torch.equal(ids2, ids) and torch.equal(nsel2, nsel), (name, "fused step: page lists differ")
+    out2_h = out2.cpu().numpy()
     pv, cv, gv = (t.cpu().numpy() for t in lib.summary_views(summ))
     ids_h, nsel_h, out_h, dense_h = ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dense.cpu().numpy()
     assert np.isfinite(out_h).all() and np.isfinite(dense_h).all()
@@ -51,8 +56,9 @@ def run_case(name, sample, dense_seq=0, seed=None):
         assert np.array_equal(gv[b, :, :ng].view(np.uint32), rg[i, :, :ng].view(np.uint32)), (name, b, "grid vectors")
         assert np.array_equal(nsel_h[b], rn[i]) and np.array_equal(ids_h[b], rids[i]), (name, b, "page lists")
         err = np.abs(out_h[b] - rout[i]).max()
-        print(f"[{name}] seq {b}: page lists exact, sparse max|out - oracle| = {err:.2e}")
-        assert err <= ATOL
+        err2 = np.abs(out2_h[b] - rout[i]).max()
+        print(f"[{name}] seq {b}: page lists exact, max|out - oracle| = {err:.2e} (two calls), {err2:.2e} (fused step)")
+        assert err <= ATOL and err2 <= ATOL
     # every sequence, not only the sampled ones: list shape invariants
     for b in range(sp.batch):
         P = -(-int(wl.seq_lens[b]) // B)

@@ -36,6 +36,11 @@ def check_all(sp, wl, plan, max_sel=None, dense=True, label=""):
     err = np.abs(gpu.out - ref.out).max()
     print(f"[{label}] sparse max|out - oracle| = {err:.3e}")
     assert np.isfinite(gpu.out).all() and err <= ATOL and err <= ATOL_TIGHT
+    # the single-launch step: the same list, attention over it against the oracle
+    assert np.array_equal(gpu.step_ids, gpu.ids) and np.array_equal(gpu.step_nsel, gpu.nsel), "fused step: page lists differ"
+    serr = np.abs(gpu.step_out - ref.out).max()
+    print(f"[{label}] fused step max|out - oracle| = {serr:.3e}")
+    assert np.isfinite(gpu.step_out).all() and serr <= ATOL and serr <= ATOL_TIGHT
     if dense:
         derr = np.abs(gpu.dense - ref.dense).max()
         print(f"[{label}] dense  max|out - oracle| = {derr:.3e}")
@@ -82,7 +87,8 @@ def test_hierarchy_shapes(nc, ng):
 @pytest.mark.parametrize("cluster", [1, 2, 3, 8, 32])
 def test_cluster_sizes_give_the_same_page_lists(cluster):
     """The number of workgroups cooperating on one (sequence, head) must not change anything; twice in a row
-    on one workspace, so the barrier counters are shown to re-arm."""
+    on one workspace, alternating with the fused step, so the key words and counters are shown to be left
+    clean by both kernels."""
     sp = workload.spec("cfg2", scale=1 / 2)
     wl = workload.generate(sp, workload.default_seed("cfg2"))
     plan = plan_of(sp)
@@ -99,6 +105,14 @@ def test_cluster_sizes_give_the_same_page_lists(cluster):
         torch.cuda.synchronize()
         assert lib.workspace_error(ws) == 0
         assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+        ids2, nsel2 = torch.full_like(ids, -7), torch.full_like(nsel, -7)
+        out2 = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+        lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids2, nsel2, out2, ws)
+        torch.cuda.synchronize()
+        assert lib.workspace_error(ws) == 0
+        assert np.array_equal(ids2.cpu().numpy(), ref.ids) and np.array_equal(nsel2.cpu().numpy(), ref.nsel)
+        err = np.abs(out2.cpu().numpy() - ref.out).max()
+        assert err <= ATOL_TIGHT, err
 
 
 def test_page32_gqa7_and_equal_norm_topics():
