@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch step by step instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense full-KV comparison")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -148,6 +150,14 @@ def main():
             torch.cuda.synchronize()
             wall_ms = (time.perf_counter() - t_wall) * 1e3
         return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_step, wall_ms_step = timed(step, args.steps, args.warmup, not args.eager)
     ms_three, _ = timed(step_three_calls, args.steps, min(args.warmup, 8), not args.eager)

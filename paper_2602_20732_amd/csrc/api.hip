@@ -292,6 +292,7 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, chess::kSelMaxCluster);
 
+    sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
     const chess::SelectWs ws = select_ws(ctx, workspace);
     const char* sb = static_cast<const char*>(summaries);
     hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
@@ -336,6 +337,7 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, chess::kSelMaxCluster);
     if (pairs * cluster > 4LL * ctx->n_cu + pairs) return CHESS_ENOTSUP;   // partial rows of the workspace
+    sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
 
     const chess::SelectWs ws = select_ws(ctx, workspace);
     const char* sb = static_cast<const char*>(summaries);

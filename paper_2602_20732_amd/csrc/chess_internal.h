@@ -27,6 +27,7 @@ struct SelectParams {
     int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
     int32_t cap_keys, cap_kg, cap_kc;   // LDS capacities: keys of one level, kept grids, kept chunks
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
+    int32_t local_grids;             // every member scores all grids itself (no exchange at the grid level)
 };
 
 #ifndef CHESS_SEL_THREADS

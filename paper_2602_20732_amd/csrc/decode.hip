@@ -51,7 +51,7 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     float* out_rows = out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     if (!combine_waves<NW>(acc.o, acc.m_run, acc.l_run, lds, G, n_splits, split, row, out_rows, ws_acc, ws_ml)) return;
     if (!arrive_last(arrivals + row, n_splits, &lds_last)) return;
-    merge_splits<NW>(reinterpret_cast<float2*>(lds_f), G, n_splits, row, out_rows, ws_acc, ws_ml);
+    merge_splits<NW>(G, n_splits, row, out_rows, ws_acc, ws_ml);
 }
 
 hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,

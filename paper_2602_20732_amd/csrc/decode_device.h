@@ -256,61 +256,51 @@ __device__ __forceinline__ bool combine_waves(const f32x4 (&o)[8], float m_run, 
 
 // What the last split of a (sequence, KV head) to finish does: merge all splits' partials,
 // out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M), always in split order, so the result does not
-// depend on which workgroup happens to be last.  `ml_buf`: LDS for n_splits * G float pairs.
+// depend on which workgroup happens to be last.  A thread owns one pair of adjacent outputs of one head and
+// derives that head's M and denominator itself from the (m, l) pairs (the threads of a head read the same
+// words), so the partial rows and the (m, l) pairs are requested together: one round trip to memory, no LDS,
+// no barrier.
 template <int NW>
-__device__ __forceinline__ void merge_splits(float2* ml_buf, int G, int n_splits, size_t row, float* __restrict__ out_rows,
+__device__ __forceinline__ void merge_splits(int G, int n_splits, size_t row, float* __restrict__ out_rows,
                                              const float* __restrict__ ws_acc, const float* __restrict__ ws_ml)
 {
     const uint64_t* acc_g = reinterpret_cast<const uint64_t*>(ws_acc);
     const uint64_t* ml_g = reinterpret_cast<const uint64_t*>(ws_ml);
-    constexpr int kChunk = 8;                          // partial rows in flight per output pair
+    constexpr int kChunk = 8;                          // splits in flight per thread
     const int n_items = G * (kHeadDim / 2);
-    // the first rows of this thread's first output pair are requested together with the (m, l) pairs,
-    // so the merge costs one round trip to memory, not two
-    uint64_t first[kChunk];
-    {
-        const int idx = min((int)threadIdx.x, n_items - 1);
-        const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
-#pragma unroll
-        for (int x = 0; x < kChunk; ++x)
-            first[x] = observe_u64(acc_g + ((row * n_splits + min(x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
-    }
-    for (int idx = threadIdx.x; idx < n_splits * G; idx += 64 * NW) {
-        const int sidx = idx / G, head = idx % G;
-        ml_buf[idx] = __builtin_bit_cast(float2, observe_u64(ml_g + (row * n_splits + sidx) * G + head));
-    }
-    __syncthreads();
-    if ((int)threadIdx.x < G) {
-        const int head = threadIdx.x;
-        float M = kNegBig, l = 0.f;
-        for (int sidx = 0; sidx < n_splits; ++sidx) M = fmaxf(M, ml_buf[sidx * G + head].x);
-        for (int sidx = 0; sidx < n_splits; ++sidx) l += ml_buf[sidx * G + head].y * __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M);
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-        for (int sidx = 0; sidx < n_splits; ++sidx)
-            ml_buf[sidx * G + head].x = __builtin_amdgcn_exp2f(ml_buf[sidx * G + head].x - M) * inv;   // weight of split sidx
-    }
-    __syncthreads();
     for (int idx = threadIdx.x; idx < n_items; idx += 64 * NW) {
         const int head = idx / (kHeadDim / 2), d2 = idx % (kHeadDim / 2);
-        float a0 = 0.f, a1 = 0.f;
+        float M = kNegBig, l = 0.f, a0 = 0.f, a1 = 0.f;
         for (int s0 = 0; s0 < n_splits; s0 += kChunk) {
-            uint64_t v[kChunk];
+            uint64_t v[kChunk], ml[kChunk];
 #pragma unroll
             for (int x = 0; x < kChunk; ++x) {
-                if (s0 == 0 && idx == (int)threadIdx.x) v[x] = first[x];
-                else v[x] = observe_u64(acc_g + ((row * n_splits + min(s0 + x, n_splits - 1)) * G + head) * (kHeadDim / 2) + d2);
+                const size_t pr = (row * n_splits + min(s0 + x, n_splits - 1)) * G + head;
+                ml[x] = observe_u64(ml_g + pr);
+                v[x] = observe_u64(acc_g + pr * (kHeadDim / 2) + d2);
             }
+            // running maximum over the splits seen so far; what has been summed is rescaled to it
+            float Mc = M;
+#pragma unroll
+            for (int x = 0; x < kChunk; ++x)
+                if (s0 + x < n_splits) Mc = fmaxf(Mc, __builtin_bit_cast(float2, ml[x]).x);
+            const float keep = __builtin_amdgcn_exp2f(M - Mc);
+            l *= keep; a0 *= keep; a1 *= keep;
+            M = Mc;
 #pragma unroll
             for (int x = 0; x < kChunk; ++x) {
                 if (s0 + x < n_splits) {
+                    const float2 mlx = __builtin_bit_cast(float2, ml[x]);
                     const float2 f = __builtin_bit_cast(float2, v[x]);
-                    const float wt = ml_buf[(s0 + x) * G + head].x;
+                    const float wt = __builtin_amdgcn_exp2f(mlx.x - M);
+                    l += mlx.y * wt;
                     a0 += f.x * wt;
                     a1 += f.y * wt;
                 }
             }
         }
-        *reinterpret_cast<float2*>(out_rows + (size_t)head * kHeadDim + 2 * d2) = make_float2(a0, a1);
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        *reinterpret_cast<float2*>(out_rows + (size_t)head * kHeadDim + 2 * d2) = make_float2(a0 * inv, a1 * inv);
     }
 }
 

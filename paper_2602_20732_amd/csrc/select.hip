@@ -6,7 +6,6 @@
 namespace chess {
 
 // grid = (C, H_kv, batch)
-template <bool kSolo>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __restrict__ q,
                                                              const float* __restrict__ pages,
                                                              const float* __restrict__ chunks,
@@ -47,18 +46,18 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     __syncthreads();
     prof.mark();                                                      // 1: prologue done
 
-    uint64_t* pub1 = ws.keys + row * ws.key_stride;
+    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g, sp);
     CascadeResult res;
-    const bool ok = cascade<kSolo, false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
-                                   grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pub1, m, C, m == 0, keys,
+    const bool ok = cascade<false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
+                                   grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, m == 0, keys,
                                    kept_grids, kept_chunks, sel_pages, sh, &res, prof);
     if (!ok) {
         if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
-    if (!kSolo) {
+    if (C > 1) {
         // whoever is last to be done with the published words clears them for the next launch
-        if (arrive_last(ws.meta + row * kSelMetaStride, C, &sh.flag)) clear_published(pub1, g, sp, res);
+        if (arrive_last(ws.meta + row * kSelMetaStride, C, &sh.flag)) clear_published(pubs, res);
     }
     if (m != 0) return;
 
@@ -87,14 +86,11 @@ size_t select_lds_bytes(const SelectParams& sp, int max_sel)
 hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu)
 {
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
     }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_kernel<false>, kSelThreads, lds_bytes);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_kernel, kSelThreads, lds_bytes);
 }
 
 hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,
@@ -103,8 +99,7 @@ hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, 
                          hipStream_t stream)
 {
     const dim3 grid(cluster, ctx->geom.n_kv_heads, batch), block(kSelThreads);
-    auto kern = cluster == 1 ? select_kernel<true> : select_kernel<false>;
-    return launch(kern, grid, block, lds_bytes, stream, q, pages, chunks, grids, seq_lens, ctx->geom, sp, ws, page_ids,
+    return launch(select_kernel, grid, block, lds_bytes, stream, q, pages, chunks, grids, seq_lens, ctx->geom, sp, ws, page_ids,
                   n_selected);
 }
 

@@ -472,10 +472,13 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
 }
 
 // Scores of the slots [lo, hi), kFly units per 16-lane group requested before the first is waited for.
-// Lane ln of a group holds probe dims 4 ln .. 4 ln + 3 and 64 + 4 ln .. 64 + 4 ln + 3.
-template <int kFly, bool kSolo, class Map>
+// `unit_of(slot)` is the index of the slot's 128-float vector in `base`, or -1 when the slot has no unit.
+// Lane ln of a group holds probe dims 4 ln .. 4 ln + 3 and 64 + 4 ln .. 64 + 4 ln + 3.  The key of a slot goes
+// to lds_keys[slot] (0 for no unit) when the level is local, else it is published in pub[slot].  (Two pointers
+// of known address space: one generic pointer for both would turn every access into a flat one.)
+template <int kFly, class Map>
 __device__ __forceinline__ void score_rows(const float* __restrict__ base, int lo, int hi, Map unit_of,
-                                           const double (&pr)[8], uint64_t* dst)
+                                           const double (&pr)[8], bool local, uint64_t* lds_keys, uint64_t* pub)
 {
     const int g16 = threadIdx.x >> 4, ln = threadIdx.x & 15;
     for (int s0 = lo; s0 < hi; s0 += kSelGroups * kFly) {
@@ -493,7 +496,7 @@ __device__ __forceinline__ void score_rows(const float* __restrict__ base, int l
         }
 #pragma unroll
         for (int x = 0; x < kFly; ++x) {
-            if (s0 + kSelGroups * x >= hi) break;             // uniform over the workgroup
+            if (s0 + kSelGroups * x >= hi) break;     // uniform over the workgroup
             double d = 0.0;
             d = fma(pr[0], (double)va[x].x, d); d = fma(pr[1], (double)va[x].y, d);
             d = fma(pr[2], (double)va[x].z, d); d = fma(pr[3], (double)va[x].w, d);
@@ -501,35 +504,35 @@ __device__ __forceinline__ void score_rows(const float* __restrict__ base, int l
             d = fma(pr[6], (double)vb[x].z, d); d = fma(pr[7], (double)vb[x].w, d);
             d = row16_sum(d);
             if (ln == 15 && slot[x] < hi) {
-                if (kSolo) dst[slot[x]] = unit[x] >= 0 ? order_key(d) : 0ull;
-                else publish_u64(dst + slot[x], unit[x] >= 0 ? order_key(d) : kAbsentKey);
+                if (local) lds_keys[slot[x]] = unit[x] >= 0 ? order_key(d) : 0ull;
+                else publish_u64(pub + slot[x], unit[x] >= 0 ? order_key(d) : kAbsentKey);
             }
         }
     }
 }
 
-// Score the slots [lo, hi) of one level: slot -> unit through `unit_of` (-1: no unit), key to `dst[slot]`.
-// A share of up to kMaxFly slots per 16-lane group is requested in one go: one memory round trip.
-template <bool kSolo, class Map>
+// Score the slots [lo, hi) of one level.  A share of up to kMaxFly slots per 16-lane group is requested in one
+// go: one memory round trip.
+template <class Map>
 __device__ __forceinline__ void score_range(const float* __restrict__ base, int lo, int hi, Map unit_of,
-                                            const double (&pr)[8], uint64_t* dst)
+                                            const double (&pr)[8], bool local, uint64_t* lds_keys, uint64_t* pub)
 {
-    score_rows<kMaxFly, kSolo>(base, lo, hi, unit_of, pr, dst);
+    score_rows<kMaxFly>(base, lo, hi, unit_of, pr, local, lds_keys, pub);
 }
 
 // A level's keys into registers (thread t: slots t, t + 256, ...; 0 = empty or beyond n_slots) and into the
-// LDS copy the general path works on.  kSolo: the keys are in LDS already.  Otherwise the published words
+// LDS copy the general path works on.  local: the keys are in LDS already.  Otherwise the published words
 // are polled until every one of them is there.  Ends with a workgroup barrier; returns false (to every
 // thread) if a word did not arrive within the poll limit.
-template <int R, bool kSolo>
-__device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, uint64_t* keys, uint64_t (&key)[R])
+template <int R>
+__device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool local, uint64_t* keys, uint64_t (&key)[R])
 {
     const int tid = threadIdx.x;
     constexpr int kBatch = R < 8 ? R : 8;             // loads requested before the first is waited for
     bool ok = true;
 #pragma unroll
     for (int x = 0; x < R; ++x) key[x] = 0ull;
-    if (kSolo) {
+    if (local) {
         __syncthreads();                              // the scores of all waves are in LDS
 #pragma unroll
         for (int x = 0; x < R; ++x) {
@@ -594,14 +597,15 @@ __device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, 
 
 // What every member does once it has scored its share of a level: the level's keys, the cut, the ordered
 // list of kept slots through `emit`.  Returns the number kept, or -1 if the keys did not arrive.
-template <bool kSolo, class KFn, class Out>
-__device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bool general, uint64_t* keys, KFn k_of,
-                                            Out emit, Shared& sh, Prof& prof)
+template <class KFn, class Hook, class Out>
+__device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bool local, bool general, uint64_t* keys,
+                                            KFn k_of, Hook after_pull, Out emit, Shared& sh, Prof& prof)
 {
     int n = -1;
     if (n_slots <= kRegsSmall * kSelThreads) {
         uint64_t key[kRegsSmall];
-        if (!pull_keys<kRegsSmall, kSolo>(pub, n_slots, keys, key)) return -1;
+        if (!pull_keys<kRegsSmall>(pub, n_slots, local, keys, key)) return -1;
+        after_pull();
         if (!general) {
             uint64_t kmin, kmax;
             int n_valid;
@@ -612,17 +616,20 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
         }
     } else if (n_slots <= kRegsLarge * kSelThreads) {
         uint64_t key[kRegsLarge];
-        if (!pull_keys<kRegsLarge, kSolo>(pub, n_slots, keys, key)) return -1;
+        if (!pull_keys<kRegsLarge>(pub, n_slots, local, keys, key)) return -1;
+        after_pull();
         if (!general) {
             uint64_t kmin, kmax;
             int n_valid;
             level_stats<kRegsLarge>(key, sh, &kmin, &kmax, &n_valid);
             n = cut_in_registers<kRegsLarge>(key, n_slots, kmin, kmax, n_valid, k_of, emit, sh, prof);
         }
-    } else if (kSolo) {
+    } else if (local) {
         __syncthreads();
+        after_pull();
     } else {
         if (!pull_keys_lds(pub, n_slots, keys)) return -1;
+        after_pull();
     }
     if (n >= 0) return n;
     // general path on the LDS copy of the keys
@@ -654,8 +661,23 @@ __device__ __forceinline__ void load_probe(const uint16_t* __restrict__ q_rows, 
 
 struct CascadeResult {
     int n_kp;              // kept pages (their numbers, ascending, are in `sel_pages`)
-    int ng, slots2, slots3;   // published words of the three levels (what has to be cleared afterwards)
+    int n1, n2, n3;        // published words of the three levels (what has to be cleared afterwards)
 };
+
+// Where the three levels' published words of one (sequence, KV head) start.
+struct PubLayout {
+    uint64_t* grids;       // [max_grids]
+    uint64_t* chunks;      // chunk slots: n_g per kept grid
+    uint64_t* pages;       // page slots: n_c per kept chunk
+};
+__device__ __forceinline__ PubLayout pub_layout(uint64_t* row_words, const Geom& g, const SelectParams& sp)
+{
+    PubLayout p;
+    p.grids = row_words;
+    p.chunks = row_words + g.max_grids;
+    p.pages = p.chunks + sp.cap2;
+    return p;
+}
 
 // The three levels for one (sequence, KV head) with P > sink + window pages.  Member m of C scores the m-th
 // part of every level.  With want_l3 every member ends up with the kept page numbers in sel_pages[0 .. n_kp);
@@ -663,13 +685,14 @@ struct CascadeResult {
 // zero and sh.n_mem zero on entry.  Returns false if a wait was given up.
 // The levels run through one copy of the code (a loop, not three inlined bodies): the kernel executes every
 // instruction about once, so its time is sensitive to how much code it has to fetch.
+//
 // kPhys: the caller goes on to read the kept pages, so the block-table entries of all page-level candidates are
-// requested ahead of the page-level scores (by every member, for all slots) and parked in phys_by_slot (LDS,
+// requested behind the page-level scores (by every member, for all slots) and parked in phys_by_slot (LDS,
 // one word per slot); sel_phys[i] then receives the physical page of sel_pages[i].
-template <bool kSolo, bool kPhys>
+template <bool kPhys>
 __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, const float* __restrict__ chunks_row,
                                         const float* __restrict__ grids_row, const double (&pr)[8], int P, const Geom& g,
-                                        const SelectParams& sp, uint64_t* pub1, int m, int C, bool want_l3,
+                                        const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
                                         Shared& sh, CascadeResult* res, Prof& prof,
                                         const int32_t* __restrict__ bt_row = nullptr, int32_t* phys_by_slot = nullptr,
@@ -681,7 +704,7 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
     const int kc_target = ceil_div_i(sp.over_chunk * k_budget, g.n_c);
     const int plan = sp.plan;
     const bool general = sp.general_cut != 0;
-    res->n_kp = 0; res->ng = ng; res->slots2 = 0; res->slots3 = 0;
+    res->n_kp = 0; res->n1 = 0; res->n2 = 0; res->n3 = 0;
 
     int n_slots = ng;                                 // candidate slots of the current level
     const int32_t* parents = nullptr;                 // kept units of the level above, ascending
@@ -694,46 +717,52 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         const int u_lo = level == 2 ? s : 0;
         const int u_hi = level == 0 ? ng : level == 1 ? nc : P - w;
         int32_t* out = level == 0 ? kept_grids : level == 1 ? kept_chunks : sel_pages;
-        uint64_t* pub = level == 0 ? pub1 : level == 1 ? pub1 + g.max_grids : pub1 + g.max_grids + sp.cap2;
+        uint64_t* pub = level == 0 ? pubs.grids : level == 1 ? pubs.chunks : pubs.pages;
+        // slot / fan without a division: exact for slot < 2^24 and 2 <= fan <= 256 (the error term slot * e / 2^32
+        // with e = fan * inv_fan - 2^32 < fan stays below 1 / fan)
+        const uint32_t inv_fan = fan > 1 ? (uint32_t)((0x100000000ull + fan - 1) / fan) : 0u;
         auto unit_of = [&](int slot) {
             int u = slot;
             if (level != 0) {
-                const int pi = slot / fan;
+                const int pi = fan > 1 ? (int)__umulhi((unsigned)slot, inv_fan) : slot;
                 u = parents[pi] * fan + (slot - pi * fan);
             }
             return (u >= u_lo && u < u_hi) ? u : -1;
         };
-        // this member's share of the level's slots: whole 16-slot rows
-        const int per = ceil_div_i(ceil_div_i(n_slots, C), 16) * 16;
-        const int lo = min(n_slots, m * per), hi = min(n_slots, lo + per);
-        if (kPhys && level == 2) {
-            // block-table entries of every slot's page: in flight together with this member's vectors, parked in
-            // LDS once those have arrived (loads return in order, so this costs no wait of its own)
-            auto with_entries = [&](auto regs) {
-                constexpr int R = decltype(regs)::value;
-                int32_t e[R];
-#pragma unroll
-                for (int x = 0; x < R; ++x) {
-                    const int i = x * kSelThreads + (int)threadIdx.x;
-                    e[x] = 0;
-                    if (x * kSelThreads < n_slots) e[x] = bt_row[max(i < n_slots ? unit_of(i) : -1, 0)];
-                }
-                score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
-#pragma unroll
-                for (int x = 0; x < R; ++x) {
-                    const int i = x * kSelThreads + (int)threadIdx.x;
-                    if (i < n_slots) phys_by_slot[i] = e[x];
-                }
-            };
-            if (n_slots <= kRegsSmall * kSelThreads) with_entries(std::integral_constant<int, kRegsSmall>{});
-            else if (n_slots <= kRegsLarge * kSelThreads) with_entries(std::integral_constant<int, kRegsLarge>{});
-            else {
-                score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
-                for (int i = threadIdx.x; i < n_slots; i += kSelThreads) phys_by_slot[i] = bt_row[max(unit_of(i), 0)];
-            }
-        } else {
-            score_range<kSolo>(base, lo, hi, unit_of, pr, kSolo ? keys : pub);
+        // A level is local when nothing is exchanged for it: a cluster of one; or the grid level when all grids fit
+        // in one request, which every member then scores for itself (the same vectors, so the same keys) instead
+        // of waiting a round trip for the others' shares (the host allows it when the repeated reads are few).
+        // Otherwise this member takes its share of the level's slots: whole 16-slot rows.
+        const bool local = C == 1 || (level == 0 && sp.local_grids != 0 && n_slots <= kSelGroups * kMaxFly);
+        {
+            const int per = local ? n_slots : ceil_div_i(ceil_div_i(n_slots, C), 16) * 16;
+            const int lo = local ? 0 : min(n_slots, m * per), hi = min(n_slots, lo + per);
+            score_range(base, lo, hi, unit_of, pr, local, keys, pub);
+            if (!local) { if (level == 0) res->n1 = n_slots; else if (level == 1) res->n2 = n_slots; else res->n3 = n_slots; }
         }
+        // kPhys: the block-table entries of every slot's page are requested now, behind this member's vectors, and
+        // parked in LDS once the level's keys have been pulled (loads return in order: no wait of their own)
+        int32_t entry[kPhys ? kRegsLarge : 1];
+        if (kPhys && level == 2) {
+#pragma unroll
+            for (int x = 0; x < kRegsLarge; ++x) {
+                const int i = x * kSelThreads + (int)threadIdx.x;
+                entry[kPhys ? x : 0] = 0;
+                if (x * kSelThreads < n_slots) entry[kPhys ? x : 0] = bt_row[max(i < n_slots ? unit_of(i) : -1, 0)];
+            }
+        }
+        auto after_pull = [&]() {
+            if (kPhys && level == 2) {
+#pragma unroll
+                for (int x = 0; x < kRegsLarge; ++x) {
+                    const int i = x * kSelThreads + (int)threadIdx.x;
+                    if (i < n_slots) phys_by_slot[i] = entry[kPhys ? x : 0];
+                }
+                for (int i = kRegsLarge * kSelThreads + threadIdx.x; i < n_slots; i += kSelThreads)
+                    phys_by_slot[i] = bt_row[max(unit_of(i), 0)];
+                __syncthreads();                      // the general path reads other threads' slots
+            }
+        };
         prof.mark();
         if (level == 2 && !want_l3) return true;
 
@@ -752,28 +781,26 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
             }
             return min(k, cap);
         };
-        const int n_kept = finish_level<kSolo>(pub, n_slots, general, keys, k_of, [&](int pos, int slot) {
+        const int n_kept = finish_level(pub, n_slots, local, general, keys, k_of, after_pull, [&](int pos, int slot) {
             out[pos] = unit_of(slot);
             if (kPhys && level == 2) sel_phys[pos] = phys_by_slot[slot];
         }, sh, prof);
         if (n_kept < 0) return false;
         prof.mark();
         parents = out;
-        if (level == 0) { n_slots = n_kept * g.n_g; res->slots2 = n_slots; }
-        else if (level == 1) { n_slots = n_kept * g.n_c; res->slots3 = n_slots; }
+        if (level == 0) n_slots = n_kept * g.n_g;
+        else if (level == 1) n_slots = n_kept * g.n_c;
         else res->n_kp = n_kept;
     }
     return true;
 }
 
 // Clear the published words of one (sequence, KV head) after everybody is done with them.
-__device__ __forceinline__ void clear_published(uint64_t* pub1, const Geom& g, const SelectParams& sp, const CascadeResult& r)
+__device__ __forceinline__ void clear_published(const PubLayout& pubs, const CascadeResult& r)
 {
-    uint64_t* pub2 = pub1 + g.max_grids;
-    uint64_t* pub3 = pub2 + sp.cap2;
-    for (int i = threadIdx.x; i < r.ng; i += blockDim.x) publish_u64(pub1 + i, 0ull);
-    for (int i = threadIdx.x; i < r.slots2; i += blockDim.x) publish_u64(pub2 + i, 0ull);
-    for (int i = threadIdx.x; i < r.slots3; i += blockDim.x) publish_u64(pub3 + i, 0ull);
+    for (int i = threadIdx.x; i < r.n1; i += blockDim.x) publish_u64(pubs.grids + i, 0ull);
+    for (int i = threadIdx.x; i < r.n2; i += blockDim.x) publish_u64(pubs.chunks + i, 0ull);
+    for (int i = threadIdx.x; i < r.n3; i += blockDim.x) publish_u64(pubs.pages + i, 0ull);
 }
 
 }  // namespace chess

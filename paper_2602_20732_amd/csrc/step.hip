@@ -35,7 +35,7 @@ struct StepArgs {
 };
 
 // grid = (C, H_kv, batch)
-template <int B, bool kSolo>
+template <int B>
 __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, SelectParams sp, SelectWs ws)
 {
     constexpr int PPT = 32 / B;
@@ -79,9 +79,9 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
     prof.mark();                                                      // prologue done
 
     // ---- the page list, in every member's LDS
-    uint64_t* pub1 = ws.keys + row * ws.key_stride;
+    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g, sp);
     CascadeResult res;
-    res.n_kp = 0; res.ng = 0; res.slots2 = 0; res.slots3 = 0;
+    res.n_kp = 0; res.n1 = 0; res.n2 = 0; res.n3 = 0;
     int n_sel;
     if (P <= s + w) {                                                 // safety pages cover the sequence
         n_sel = min(P, g.max_sel);
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
         int safety_phys = 0;
         if (safety_early && tid < s + w) safety_phys = bt_row[safety_lp];
         // kept pages and their physical pages go straight to their places in the list, behind the sinks
-        const bool ok = cascade<kSolo, true>(a.pages + row * g.max_pages * kHeadDim, a.chunks + row * g.max_chunks * kHeadDim,
-                                             a.grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pub1, m, C, true, keys,
+        const bool ok = cascade<true>(a.pages + row * g.max_pages * kHeadDim, a.chunks + row * g.max_chunks * kHeadDim,
+                                             a.grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, true, keys,
                                              kept_grids, kept_chunks, ids_l + s, sh, &res, prof, bt_row, phys_by_slot,
                                              phys_l + s);
         if (!ok) {
@@ -141,8 +141,8 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
     prof.mark();                                                      // partial published
     if (!arrive_last(a.arrivals + row, C, &sh.flag)) return;
     prof.mark();                                                      // last to arrive
-    merge_splits<kStepWaves>(reinterpret_cast<float2*>(un), G, C, row, out_rows, a.ws_acc, a.ws_ml);
-    if (!kSolo) clear_published(pub1, g, sp, res);                    // every member is done with the key words
+    merge_splits<kStepWaves>(G, C, row, out_rows, a.ws_acc, a.ws_ml);
+    if (C > 1) clear_published(pubs, res);                    // every member is done with the key words
 #ifdef CHESS_PROF
     prof.mark();
     if (tid == 0)
@@ -150,13 +150,9 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
 #endif
 }
 
-template <int B, bool kSolo>
-static void (*step_fn())(StepArgs, Geom, SelectParams, SelectWs) { return step_kernel<B, kSolo>; }
-
-static void (*step_kernel_of(int page_size, bool solo))(StepArgs, Geom, SelectParams, SelectWs)
+static void (*step_kernel_of(int page_size))(StepArgs, Geom, SelectParams, SelectWs)
 {
-    if (page_size == 16) return solo ? step_fn<16, true>() : step_fn<16, false>();
-    return solo ? step_fn<32, true>() : step_fn<32, false>();
+    return page_size == 16 ? step_kernel<16> : step_kernel<32>;
 }
 
 // Dynamic LDS of the fused kernel and where its shared region starts.
@@ -171,12 +167,10 @@ size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off)
 
 hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu)
 {
-    for (bool solo : {false, true}) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kernel_of(page_size, solo)),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e != hipSuccess) return e;
-    }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, step_kernel_of(page_size, false), kSelThreads, lds_bytes);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kernel_of(page_size)),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, step_kernel_of(page_size), kSelThreads, lds_bytes);
 }
 
 hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
@@ -190,7 +184,7 @@ hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int clus
     a.scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     a.union_off = union_off;
     const dim3 grid(cluster, g.n_kv_heads, batch), block(kSelThreads);
-    return launch(step_kernel_of(g.page_size, cluster == 1), grid, block, lds_bytes, stream, a, g, sp, ws);
+    return launch(step_kernel_of(g.page_size), grid, block, lds_bytes, stream, a, g, sp, ws);
 }
 
 }  // namespace chess
