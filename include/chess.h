@@ -149,12 +149,15 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
  * the one chess_select writes, `out` is attention over exactly those pages.  The list stays on chip
  * between the two stages; it is also written to page_ids / n_selected unless those are NULL (pass them
  * to reuse the list in later steps, as the paper does between reselections, Sec. 3.3).
- * Arguments, layouts and errors as for the two calls.  The summaries must be current
- * (chess_summarize_tail first, when the tail page has grown).
+ * Arguments, layouts and errors as for the two calls.
+ * refresh_tail != 0: the launch first does what chess_summarize_tail does (Sec. 3.1, Eq. 1-2: the vectors of
+ * the tail page, its chunk and its grid are recomputed from the K pool, written to `summaries`, and are the
+ * ones the selection scores), so a decode step is this one call.  refresh_tail == 0: `summaries` is only read
+ * and must be current.
  */
 int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
-                      const int32_t* block_table, const int32_t* seq_lens, const void* summaries, int32_t batch,
-                      const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
+                      const int32_t* block_table, const int32_t* seq_lens, void* summaries, int32_t refresh_tail,
+                      int32_t batch, const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
                       void* workspace, void* stream);
 
 /* Synchronous check (copies one word back, waits for the device): *flag is non-zero if any kernel

@@ -94,7 +94,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_dense_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp, vp, vp]
-        lib.chess_decode_step.argtypes = [vp, vp, vp, vp, i32p, i32p, vp, ctypes.c_int32, vp, i32p, i32p, vp, vp, vp]
+        lib.chess_decode_step.argtypes = [vp, vp, vp, vp, i32p, i32p, vp, ctypes.c_int32, ctypes.c_int32, vp, i32p, i32p, vp, vp, vp]
         lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
         lib.chess_debug_force_cluster.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_force_general_cut.argtypes = [vp, ctypes.c_int32]
@@ -194,10 +194,11 @@ class Chess:
                                                 _ptr(seq_lens), seq_lens.shape[0], _ptr(out), _ptr(workspace), _stream()))
 
     def decode_step(self, q, k_pool, v_pool, block_table, seq_lens, summaries, plan: SelectPlan, page_ids, n_selected,
-                    out, workspace):
+                    out, workspace, refresh_tail: bool = False):
         p = plan._c()
         self._check(self.lib.chess_decode_step(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
-                                               _ptr(seq_lens), _ptr(summaries), seq_lens.shape[0], ctypes.byref(p),
+                                               _ptr(seq_lens), _ptr(summaries), int(bool(refresh_tail)),
+                                               seq_lens.shape[0], ctypes.byref(p),
                                                _ptr(page_ids), _ptr(n_selected), _ptr(out), _ptr(workspace), _stream()))
 
     def workspace_error(self, workspace) -> int:

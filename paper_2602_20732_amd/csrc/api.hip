@@ -154,7 +154,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_ml_off = align_up(part_rows * vec, 256);
     c->ws_keys_off = align_up(c->ws_ml_off + part_rows * 2 * sizeof(float), 256);
     c->key_stride = (int64_t)g.max_grids * (1 + g.n_g) + (int64_t)g.max_chunks * g.n_c;
-    c->ws_meta_off = align_up(c->ws_keys_off + rows * c->key_stride * sizeof(uint64_t), 256);
+    c->ws_tail_off = align_up(c->ws_keys_off + rows * c->key_stride * sizeof(uint64_t), 256);
+    c->ws_meta_off = align_up(c->ws_tail_off + rows * 4 * sizeof(uint64_t), 256);
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
     c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
     c->ws_prof_off = align_up(c->ws_err_off + 256, 256);            // profiling builds only: 48 words per row
@@ -233,6 +234,17 @@ int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream)
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
+// Workgroups that cooperate on one (sequence, KV head).  Measured on MI355X (batch 1 .. 32, 16K .. 256K tokens):
+// once there is a (sequence, head) per compute unit, splitting them further only adds exchanges; below that, more
+// members keep paying off until each wave has about two tiles of the list left, between 8 and 12 members.
+// All workgroups of the grid have to fit on the device at once (the members wait for each other's keys).
+static int64_t choose_cluster(const chess_ctx* ctx, int64_t pairs, int64_t capacity)
+{
+    if (pairs >= ctx->n_cu) return 1;
+    const int64_t tiles = cdiv(ctx->geom.max_sel, chess::kTileTokens / ctx->geom.page_size);
+    return std::max<int64_t>(1, std::min<int64_t>(capacity / pairs, clampi(cdiv(tiles, 8), 8, 12)));
+}
+
 // Checks a plan against the configuration and fills the kernel-side parameters.
 static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::SelectParams* out)
 {
@@ -258,6 +270,7 @@ static chess::SelectWs select_ws(const chess_ctx* ctx, void* workspace)
 {
     char* wb = static_cast<char*>(workspace);
     return chess::SelectWs{reinterpret_cast<uint64_t*>(wb + ctx->ws_keys_off), ctx->key_stride,
+                           reinterpret_cast<uint64_t*>(wb + ctx->ws_tail_off),
                            reinterpret_cast<int32_t*>(wb + ctx->ws_meta_off), reinterpret_cast<int32_t*>(wb + ctx->ws_err_off)
 #ifdef CHESS_PROF
                            , reinterpret_cast<int32_t*>(wb + ctx->ws_prof_off)
@@ -287,8 +300,7 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     }
     const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
     const int64_t capacity = (int64_t)ctx->occ_blocks * ctx->n_cu;
-    // ... and no more members than leave each a full request (8 vectors per 16-lane group) at page level
-    int64_t cluster = std::min<int64_t>(capacity / pairs, cdiv(sp.cap3, 128));
+    int64_t cluster = choose_cluster(ctx, pairs, capacity);
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, chess::kSelMaxCluster);
 
@@ -304,8 +316,8 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
 }
 
 int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
-                      const int32_t* block_table, const int32_t* seq_lens, const void* summaries, int32_t batch,
-                      const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
+                      const int32_t* block_table, const int32_t* seq_lens, void* summaries, int32_t refresh_tail,
+                      int32_t batch, const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
                       void* workspace, void* stream)
 {
     if (!ctx || !q || !k_pool || !v_pool || !block_table || !seq_lens || !summaries || !plan || !out || !workspace)
@@ -329,24 +341,21 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
     if (ctx->step_occ_blocks < 1) return CHESS_ENOTSUP;
     const int64_t pairs = (int64_t)batch * ctx->geom.n_kv_heads;
     const int64_t capacity = (int64_t)ctx->step_occ_blocks * ctx->n_cu;
-    // members: enough that a member's share of the page-level candidates is one request (8 vectors per 16-lane
-    // group) and that every wave of the cluster has at most one tile of the list to attend to, as far as all
-    // workgroups of the grid fit on the device at once
-    const int64_t tiles = cdiv(ctx->geom.max_sel, chess::kTileTokens / ctx->geom.page_size);
-    int64_t cluster = std::min<int64_t>(capacity / pairs, std::max<int64_t>(cdiv(sp.cap3, 128), cdiv(tiles, 4)));
+    int64_t cluster = choose_cluster(ctx, pairs, capacity);
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = clampi(cluster, 1, chess::kSelMaxCluster);
     if (pairs * cluster > 4LL * ctx->n_cu + pairs) return CHESS_ENOTSUP;   // partial rows of the workspace
     sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
 
     const chess::SelectWs ws = select_ws(ctx, workspace);
-    const char* sb = static_cast<const char*>(summaries);
+    char* sb = static_cast<char*>(summaries);
     char* wb = static_cast<char*>(workspace);
-    chess::StepLaunch sl{static_cast<const uint16_t*>(q), reinterpret_cast<const float*>(sb + ctx->page_off),
-                         reinterpret_cast<const float*>(sb + ctx->chunk_off), reinterpret_cast<const float*>(sb + ctx->grid_off),
+    chess::StepLaunch sl{static_cast<const uint16_t*>(q), reinterpret_cast<float*>(sb + ctx->page_off),
+                         reinterpret_cast<float*>(sb + ctx->chunk_off), reinterpret_cast<float*>(sb + ctx->grid_off),
                          static_cast<const uint16_t*>(k_pool), static_cast<const uint16_t*>(v_pool), block_table, seq_lens,
                          page_ids, n_selected, out, reinterpret_cast<float*>(wb + ctx->ws_acc_off),
-                         reinterpret_cast<float*>(wb + ctx->ws_ml_off), reinterpret_cast<int32_t*>(wb + ctx->ws_cnt_off)};
+                         reinterpret_cast<float*>(wb + ctx->ws_ml_off), reinterpret_cast<int32_t*>(wb + ctx->ws_cnt_off),
+                         refresh_tail != 0};
     hipError_t e = chess::launch_step(ctx, sl, batch, (int)cluster, sp, ws, lds, union_off, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }

@@ -41,6 +41,7 @@ constexpr int kSelMetaStride = 8;    // int32 per (sequence, KV head): [0] membe
 struct SelectWs {
     uint64_t* keys;                  // [rows][key_stride]  published candidate keys: grids | chunk slots | page slots;
     int64_t key_stride;              //   all zero between launches
+    uint64_t* tail;                  // [rows][4] keys of the refreshed tail grid / chunk / page; zero between launches
     int32_t* meta;                   // [rows][kSelMetaStride], zero between launches
     int32_t* error;                  // one word: set if a wait for published keys was given up
 #ifdef CHESS_PROF
@@ -97,7 +98,7 @@ struct chess_ctx {
     int max_splits;
     int force_splits, force_waves;                         // 0 = automatic
     size_t ws_acc_off, ws_ml_off, workspace_bytes;
-    size_t ws_keys_off, ws_meta_off, ws_cnt_off, ws_err_off, ws_prof_off;   // select scratch, decode arrival counters, error word
+    size_t ws_keys_off, ws_tail_off, ws_meta_off, ws_cnt_off, ws_err_off, ws_prof_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
     int force_general_cut;                                 // 0 = automatic
@@ -129,9 +130,9 @@ hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, 
 // Device pointers of one fused decode-step launch.
 struct StepLaunch {
     const uint16_t* q;
-    const float* pages;
-    const float* chunks;
-    const float* grids;
+    float* pages;
+    float* chunks;
+    float* grids;
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const int32_t* block_table;
@@ -142,6 +143,7 @@ struct StepLaunch {
     float* ws_acc;
     float* ws_ml;
     int32_t* arrivals;
+    int32_t refresh_tail;
 };
 hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
                        const SelectWs& ws, size_t lds_bytes, int union_off, hipStream_t stream);

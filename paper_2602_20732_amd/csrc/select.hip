@@ -33,6 +33,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);   // requested before anything waits on the length
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
+    if (tid < 3) sh.tail_key[tid] = 0ull;
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     CascadeResult res;
     const bool ok = cascade<false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
                                    grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, m == 0, keys,
-                                   kept_grids, kept_chunks, sel_pages, sh, &res, prof);
+                                   kept_grids, kept_chunks, sel_pages, sh, &res, prof, nullptr, [] {});
     if (!ok) {
         if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;

@@ -134,6 +134,7 @@ struct Shared {
     unsigned int or_lo, or_hi, and_lo, and_hi;
     unsigned st_min[kSelWaves], st_max[kSelWaves];   // upper halves of the waves' smallest / largest key of a level
     int st_cnt[kSelWaves];
+    uint64_t tail_key[3];   // keys of the refreshed tail grid / chunk / page when this workgroup computed them, else 0
 };
 
 struct Prof {
@@ -520,12 +521,32 @@ __device__ __forceinline__ void score_range(const float* __restrict__ base, int 
     score_rows<kMaxFly>(base, lo, hi, unit_of, pr, local, lds_keys, pub);
 }
 
+// One slot of a level whose key does not come from where the others' do: the unit the decode step has just
+// refreshed (the tail page, its chunk, its grid), whose key one workgroup publishes in a word of its own.
+struct SlotOverride {
+    int slot;                 // -1: none
+    const uint64_t* word;     // where the key is published
+    uint64_t have;            // non-zero: the key itself (this workgroup computed it)
+};
+
+// Wait for one published word; 0 if it did not arrive within the poll limit.
+__device__ __forceinline__ uint64_t poll_word(const uint64_t* word)
+{
+    for (int polls = 0; polls < kPollLimit; ++polls) {
+        const uint64_t v = observe_u64(word);
+        if (v != 0ull) return v;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    return 0ull;
+}
+
 // A level's keys into registers (thread t: slots t, t + 256, ...; 0 = empty or beyond n_slots) and into the
 // LDS copy the general path works on.  local: the keys are in LDS already.  Otherwise the published words
 // are polled until every one of them is there.  Ends with a workgroup barrier; returns false (to every
 // thread) if a word did not arrive within the poll limit.
 template <int R>
-__device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool local, uint64_t* keys, uint64_t (&key)[R])
+__device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool local, const SlotOverride& ov,
+                                          uint64_t* keys, uint64_t (&key)[R])
 {
     const int tid = threadIdx.x;
     constexpr int kBatch = R < 8 ? R : 8;             // loads requested before the first is waited for
@@ -538,8 +559,14 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
         for (int x = 0; x < R; ++x) {
             const int i = x * kSelThreads + tid;
             if (i < n_slots) key[x] = keys[i];
+            if (i == ov.slot) {
+                key[x] = ov.have != 0ull ? ov.have : poll_word(ov.word);
+                ok = key[x] != 0ull;
+                keys[i] = key[x];
+            }
         }
-        return true;
+        if (ov.slot < 0) return true;
+        return __syncthreads_and(ok) != 0;
     }
 #pragma unroll
     for (int x0 = 0; x0 < R; x0 += kBatch) {
@@ -549,8 +576,9 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
             bool missing = false;
 #pragma unroll
             for (int x = x0; x < x0 + kBatch && x < R; ++x) {
-                const int ic = max(min(x * kSelThreads + tid, n_slots - 1), 0);   // unconditional: all stay in flight
-                key[x] = observe_u64(pub + ic);
+                const int i = x * kSelThreads + tid;
+                const int ic = max(min(i, n_slots - 1), 0);   // unconditional: all stay in flight
+                key[x] = observe_u64(i == ov.slot ? ov.word : pub + ic);
             }
 #pragma unroll
             for (int x = x0; x < x0 + kBatch && x < R; ++x)
@@ -570,7 +598,7 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
 }
 
 // The same for a level too large for the register path: into LDS only.
-__device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, uint64_t* keys)
+__device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, const SlotOverride& ov, uint64_t* keys)
 {
     bool ok = true;
     for (int i0 = 0; i0 < n_slots; i0 += 4 * kSelThreads) {
@@ -579,7 +607,10 @@ __device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, 
         while (true) {
             bool missing = false;
 #pragma unroll
-            for (int x = 0; x < 4; ++x) v[x] = observe_u64(pub + min(i0 + x * kSelThreads + (int)threadIdx.x, n_slots - 1));
+            for (int x = 0; x < 4; ++x) {
+                const int i = i0 + x * kSelThreads + (int)threadIdx.x;
+                v[x] = observe_u64(i == ov.slot ? ov.word : pub + min(i, n_slots - 1));
+            }
 #pragma unroll
             for (int x = 0; x < 4; ++x) missing = missing || v[x] == 0ull;
             if (__ballot(missing) == 0ull) break;
@@ -598,13 +629,14 @@ __device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, 
 // What every member does once it has scored its share of a level: the level's keys, the cut, the ordered
 // list of kept slots through `emit`.  Returns the number kept, or -1 if the keys did not arrive.
 template <class KFn, class Hook, class Out>
-__device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bool local, bool general, uint64_t* keys,
-                                            KFn k_of, Hook after_pull, Out emit, Shared& sh, Prof& prof)
+__device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bool local, bool general,
+                                            const SlotOverride& ov, uint64_t* keys, KFn k_of, Hook after_pull, Out emit,
+                                            Shared& sh, Prof& prof)
 {
     int n = -1;
     if (n_slots <= kRegsSmall * kSelThreads) {
         uint64_t key[kRegsSmall];
-        if (!pull_keys<kRegsSmall>(pub, n_slots, local, keys, key)) return -1;
+        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key)) return -1;
         after_pull();
         if (!general) {
             uint64_t kmin, kmax;
@@ -616,7 +648,7 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
         }
     } else if (n_slots <= kRegsLarge * kSelThreads) {
         uint64_t key[kRegsLarge];
-        if (!pull_keys<kRegsLarge>(pub, n_slots, local, keys, key)) return -1;
+        if (!pull_keys<kRegsLarge>(pub, n_slots, local, ov, keys, key)) return -1;
         after_pull();
         if (!general) {
             uint64_t kmin, kmax;
@@ -626,9 +658,16 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
         }
     } else if (local) {
         __syncthreads();
+        bool ok = true;
+        if (ov.slot >= 0 && (int)threadIdx.x == 0) {
+            const uint64_t k = ov.have != 0ull ? ov.have : poll_word(ov.word);
+            ok = k != 0ull;
+            keys[ov.slot] = k;
+        }
+        if (ov.slot >= 0 && __syncthreads_and(ok) == 0) return -1;
         after_pull();
     } else {
-        if (!pull_keys_lds(pub, n_slots, keys)) return -1;
+        if (!pull_keys_lds(pub, n_slots, ov, keys)) return -1;
         after_pull();
     }
     if (n >= 0) return n;
@@ -689,14 +728,20 @@ __device__ __forceinline__ PubLayout pub_layout(uint64_t* row_words, const Geom&
 // kPhys: the caller goes on to read the kept pages, so the block-table entries of all page-level candidates are
 // requested behind the page-level scores (by every member, for all slots) and parked in phys_by_slot (LDS,
 // one word per slot); sel_phys[i] then receives the physical page of sel_pages[i].
-template <bool kPhys>
+//
+// tail_words non-null: the decode step refreshes the summaries of the tail page, its chunk and its grid in this
+// launch.  `refresh_tail()` is called in member 0 once its grid-level vectors are requested; it leaves the three
+// units' keys in tail_words[0..2] (grid, chunk, page) for the cluster and in sh.tail_key for itself.  Wherever one
+// of these units is a candidate, its key is taken from there instead of the slot's own word (whatever was
+// scored for that slot from the old vector is ignored).
+template <bool kPhys, class TailFn>
 __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, const float* __restrict__ chunks_row,
                                         const float* __restrict__ grids_row, const double (&pr)[8], int P, const Geom& g,
                                         const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
-                                        Shared& sh, CascadeResult* res, Prof& prof,
-                                        const int32_t* __restrict__ bt_row = nullptr, int32_t* phys_by_slot = nullptr,
-                                        int32_t* sel_phys = nullptr)
+                                        Shared& sh, CascadeResult* res, Prof& prof, const uint64_t* tail_words,
+                                        TailFn refresh_tail, const int32_t* __restrict__ bt_row = nullptr,
+                                        int32_t* phys_by_slot = nullptr, int32_t* sel_phys = nullptr)
 {
     const int s = sp.sink, w = sp.window;
     const int nc = ceil_div_i(P, g.n_c), ng = ceil_div_i(nc, g.n_g);
@@ -708,6 +753,8 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
 
     int n_slots = ng;                                 // candidate slots of the current level
     const int32_t* parents = nullptr;                 // kept units of the level above, ascending
+    int n_parents = 0;
+    const int tail_unit[3] = {ng - 1, nc - 1, P - 1};
 #pragma unroll 1
     for (int level = 0; level < 3; ++level) {
         // level 0: every grid; level 1: chunks of kept grids; level 2: pages of kept chunks that are neither
@@ -765,6 +812,18 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         };
         prof.mark();
         if (level == 2 && !want_l3) return true;
+        if (level == 0 && tail_words != nullptr && m == 0) refresh_tail();
+
+        // the slot of the refreshed tail unit, if it competes at this level: the last child of the last parent
+        SlotOverride ov{-1, nullptr, 0ull};
+        if (tail_words != nullptr) {
+            const int u = tail_unit[level];
+            if (level == 0) ov.slot = u;
+            else if (n_parents > 0 && parents[n_parents - 1] == tail_unit[level - 1] && u >= u_lo && u < u_hi)
+                ov.slot = (n_parents - 1) * fan + (u - tail_unit[level - 1] * fan);
+            ov.word = tail_words + level;
+            ov.have = sh.tail_key[level];
+        }
 
         const int cap = level == 0 ? sp.cap_kg : level == 1 ? sp.cap_kc : g.max_sel - s - w;
         auto k_of = [&](int n) {
@@ -781,13 +840,14 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
             }
             return min(k, cap);
         };
-        const int n_kept = finish_level(pub, n_slots, local, general, keys, k_of, after_pull, [&](int pos, int slot) {
+        const int n_kept = finish_level(pub, n_slots, local, general, ov, keys, k_of, after_pull, [&](int pos, int slot) {
             out[pos] = unit_of(slot);
             if (kPhys && level == 2) sel_phys[pos] = phys_by_slot[slot];
         }, sh, prof);
         if (n_kept < 0) return false;
         prof.mark();
         parents = out;
+        n_parents = n_kept;
         if (level == 0) n_slots = n_kept * g.n_g;
         else if (level == 1) n_slots = n_kept * g.n_c;
         else res->n_kp = n_kept;
@@ -796,8 +856,9 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
 }
 
 // Clear the published words of one (sequence, KV head) after everybody is done with them.
-__device__ __forceinline__ void clear_published(const PubLayout& pubs, const CascadeResult& r)
+__device__ __forceinline__ void clear_published(const PubLayout& pubs, const CascadeResult& r, uint64_t* tail_words = nullptr)
 {
+    if (tail_words != nullptr && threadIdx.x < 3) publish_u64(tail_words + threadIdx.x, 0ull);
     for (int i = threadIdx.x; i < r.n1; i += blockDim.x) publish_u64(pubs.grids + i, 0ull);
     for (int i = threadIdx.x; i < r.n2; i += blockDim.x) publish_u64(pubs.chunks + i, 0ull);
     for (int i = threadIdx.x; i < r.n3; i += blockDim.x) publish_u64(pubs.pages + i, 0ull);

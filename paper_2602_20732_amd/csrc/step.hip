@@ -17,9 +17,9 @@ constexpr int kStepWaves = kSelThreads / kWave;
 
 struct StepArgs {
     const uint16_t* q;
-    const float* pages;
-    const float* chunks;
-    const float* grids;
+    float* pages;            // summaries: read; the tail units are rewritten when refresh_tail is set
+    float* chunks;
+    float* grids;
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const int32_t* block_table;
@@ -32,16 +32,108 @@ struct StepArgs {
     int32_t* arrivals;
     float scale_log2;
     int32_t union_off;       // byte offset of the LDS region selection and decode share (after the page list)
+    int32_t refresh_tail;    // recompute the summaries of the tail page, its chunk and its grid first
 };
+
+// The per-step refresh of the summaries (Sec. 3.1, Eq. 1-2) of the tail page, its chunk and its grid, done by one
+// workgroup per (sequence, KV head) inside the step: thread c < 128 owns column c and adds in the same order as
+// the summarize kernel (tokens, then the chunk's pages, then the grid's chunks, ascending, fp64, one rounding to
+// fp32 per vector), so the vectors are the ones chess_summarize_tail writes.  They go to the summaries and to
+// `fresh` (LDS, [3][128]: page, chunk, grid); their scores against the probe are published as keys in
+// tail_words[0..2] (grid, chunk, page) when `publish` is set (a cluster of one has nobody to tell) and kept in
+// sh.tail_key.  Every thread of the workgroup must call it.
+template <int B>
+__device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ k_pool, int64_t phys, float* pages_row,
+                                                   float* chunks_row, float* grids_row, int h, int H, int L, int P,
+                                                   const Geom& g, const double (&pr)[8], float* fresh,
+                                                   uint64_t* tail_words, bool publish, Shared& sh)
+{
+    const int tid = threadIdx.x;
+    const int tp = P - 1, tc = tp / g.n_c, tg = tc / g.n_g;
+    const int n_tok = L - tp * B;
+    if (tid < kHeadDim) {
+        const int c = tid;
+        // the page's key rows, all requested at once (rows past the last token repeat it and are not added)
+        const uint16_t* rows = k_pool + ((phys * H + h) * B) * kHeadDim + c;
+        uint16_t kr[B];
+#pragma unroll
+        for (int t = 0; t < B; ++t) kr[t] = rows[(size_t)min(t, n_tok - 1) * kHeadDim];
+        // the other pages of the chunk and the other chunks of the grid (the tail unit is the last child of each),
+        // eight at a time and the first eight of each together with the key rows: one round trip for the usual
+        // hierarchy of 8 x 8
+        constexpr int kSib = 8;
+        const int p_lo = tc * g.n_c, c_lo = tg * g.n_g;
+        float sp[kSib], sc[kSib];
+#pragma unroll
+        for (int x = 0; x < kSib; ++x) {
+            sp[x] = pages_row[(size_t)min(p_lo + x, tp) * kHeadDim + c];
+            sc[x] = chunks_row[(size_t)min(c_lo + x, tc) * kHeadDim + c];
+        }
+        double acc_c = 0.0, acc_g = 0.0;
+#pragma unroll
+        for (int x = 0; x < kSib; ++x) {
+            if (p_lo + x < tp) acc_c += (double)sp[x];
+            if (c_lo + x < tc) acc_g += (double)sc[x];
+        }
+        for (int j0 = p_lo + kSib; j0 < tp; j0 += kSib) {
+#pragma unroll
+            for (int x = 0; x < kSib; ++x) sp[x] = pages_row[(size_t)min(j0 + x, tp) * kHeadDim + c];
+#pragma unroll
+            for (int x = 0; x < kSib; ++x)
+                if (j0 + x < tp) acc_c += (double)sp[x];
+        }
+        for (int j0 = c_lo + kSib; j0 < tc; j0 += kSib) {
+#pragma unroll
+            for (int x = 0; x < kSib; ++x) sc[x] = chunks_row[(size_t)min(j0 + x, tc) * kHeadDim + c];
+#pragma unroll
+            for (int x = 0; x < kSib; ++x)
+                if (j0 + x < tc) acc_g += (double)sc[x];
+        }
+        double acc_p = 0.0;
+#pragma unroll
+        for (int t = 0; t < B; ++t)
+            if (t < n_tok) acc_p += (double)__uint_as_float((uint32_t)kr[t] << 16);
+        const float vp = (float)(acc_p / (double)n_tok);
+        const float vc = (float)((acc_c + (double)vp) / (double)(tp - tc * g.n_c + 1));
+        const float vg = (float)((acc_g + (double)vc) / (double)(tc - tg * g.n_g + 1));
+        pages_row[(size_t)tp * kHeadDim + c] = vp;
+        chunks_row[(size_t)tc * kHeadDim + c] = vc;
+        grids_row[(size_t)tg * kHeadDim + c] = vg;
+        fresh[c] = vp;
+        fresh[kHeadDim + c] = vc;
+        fresh[2 * kHeadDim + c] = vg;
+    }
+    __syncthreads();
+    // scores of the three vectors, one 16-lane group each, with the arithmetic of score_rows
+    const int g16 = tid >> 4, ln = tid & 15;
+    if (g16 < 3) {
+        const float4* v = reinterpret_cast<const float4*>(fresh + g16 * kHeadDim);
+        const float4 va = v[ln], vb = v[16 + ln];
+        double d = 0.0;
+        d = fma(pr[0], (double)va.x, d); d = fma(pr[1], (double)va.y, d);
+        d = fma(pr[2], (double)va.z, d); d = fma(pr[3], (double)va.w, d);
+        d = fma(pr[4], (double)vb.x, d); d = fma(pr[5], (double)vb.y, d);
+        d = fma(pr[6], (double)vb.z, d); d = fma(pr[7], (double)vb.w, d);
+        d = row16_sum(d);
+        if (ln == 15) {
+            const uint64_t key = order_key(d);
+            const int level = 2 - g16;                            // fresh[0] is the page, fresh[2] the grid
+            if (publish) publish_u64(tail_words + level, key);
+            sh.tail_key[level] = key;
+        }
+    }
+    __syncthreads();
+}
 
 // grid = (C, H_kv, batch)
 template <int B>
-__global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, SelectParams sp, SelectWs ws)
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))) void step_kernel(StepArgs a, Geom g, SelectParams sp, SelectWs ws)
 {
     constexpr int PPT = 32 / B;
     extern __shared__ unsigned long long lds_raw[];
     int32_t* ids_l = reinterpret_cast<int32_t*>(lds_raw);                                  // [max_sel] the page list
     int32_t* phys_l = ids_l + g.max_sel;                                                   // [max_sel] their physical pages
+    float* fresh = reinterpret_cast<float*>(reinterpret_cast<char*>(lds_raw) + a.union_off) - 3 * kHeadDim;   // [3][128]
     char* un = reinterpret_cast<char*>(lds_raw) + a.union_off;
     uint64_t* keys = reinterpret_cast<uint64_t*>(un);                                      // selection's view
     int32_t* kept_grids = reinterpret_cast<int32_t*>(keys + sp.cap_keys);
@@ -63,6 +155,7 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
     load_probe(q_rows, G, pr);                                        // requested before anything waits on the length
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
+    if (tid < 3) sh.tail_key[tid] = 0ull;
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
@@ -75,6 +168,17 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
         }
         return;
     }
+    // member 0 refreshes the tail units: its block-table entry is requested now
+    const bool tail_on = a.refresh_tail != 0;
+    uint64_t* tail_words = tail_on ? ws.tail + row * 4 : nullptr;
+    float* pages_row = a.pages + row * g.max_pages * kHeadDim;
+    float* chunks_row = a.chunks + row * g.max_chunks * kHeadDim;
+    float* grids_row = a.grids + row * g.max_grids * kHeadDim;
+    int tail_phys = 0;
+    if (tail_on && m == 0) tail_phys = bt_row[P - 1];
+    auto refresh_tail = [&]() {
+        refresh_tail_units<B>(a.k_pool, tail_phys, pages_row, chunks_row, grids_row, h, H, L, P, g, pr, fresh, tail_words, C > 1, sh);
+    };
     __syncthreads();
     prof.mark();                                                      // prologue done
 
@@ -86,6 +190,7 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
     if (P <= s + w) {                                                 // safety pages cover the sequence
         n_sel = min(P, g.max_sel);
         for (int i = tid; i < n_sel; i += kSelThreads) { ids_l[i] = i; phys_l[i] = bt_row[i]; }
+        if (tail_on && m == 0) refresh_tail();                        // nobody reads the keys; the summaries are kept current
     } else {
         // the block-table entries of the safety pages are requested now and used after the selection
         const bool safety_early = s + w <= kSelThreads;
@@ -93,10 +198,9 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
         int safety_phys = 0;
         if (safety_early && tid < s + w) safety_phys = bt_row[safety_lp];
         // kept pages and their physical pages go straight to their places in the list, behind the sinks
-        const bool ok = cascade<true>(a.pages + row * g.max_pages * kHeadDim, a.chunks + row * g.max_chunks * kHeadDim,
-                                             a.grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, true, keys,
-                                             kept_grids, kept_chunks, ids_l + s, sh, &res, prof, bt_row, phys_by_slot,
-                                             phys_l + s);
+        const bool ok = cascade<true>(pages_row, chunks_row, grids_row, pr, P, g, sp, pubs, m, C, true, keys, kept_grids,
+                                      kept_chunks, ids_l + s, sh, &res, prof, tail_words, refresh_tail, bt_row,
+                                      phys_by_slot, phys_l + s);
         if (!ok) {
             if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
@@ -142,7 +246,7 @@ __global__ __launch_bounds__(kSelThreads) void step_kernel(StepArgs a, Geom g, S
     if (!arrive_last(a.arrivals + row, C, &sh.flag)) return;
     prof.mark();                                                      // last to arrive
     merge_splits<kStepWaves>(G, C, row, out_rows, a.ws_acc, a.ws_ml);
-    if (C > 1) clear_published(pubs, res);                    // every member is done with the key words
+    if (C > 1) clear_published(pubs, res, tail_words);                    // every member is done with the key words
 #ifdef CHESS_PROF
     prof.mark();
     if (tid == 0)
@@ -158,7 +262,7 @@ static void (*step_kernel_of(int page_size))(StepArgs, Geom, SelectParams, Selec
 // Dynamic LDS of the fused kernel and where its shared region starts.
 size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off)
 {
-    const size_t list = ((size_t)max_sel * 2 * 4 + 15) / 16 * 16;                 // page list and physical pages
+    const size_t list = ((size_t)max_sel * 2 * 4 + 15) / 16 * 16 + 3 * kHeadDim * sizeof(float);   // page list, physical pages, refreshed tail vectors
     const size_t sel = (size_t)sp.cap_keys * 8 + ((size_t)(sp.cap_kg + sp.cap_kc + sp.cap3) * 4 + 7) / 8 * 8;
     const size_t dec = (size_t)DecodeLds<kStepWaves>::kFloats * sizeof(float);
     *union_off = (int)list;
@@ -183,6 +287,7 @@ hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int clus
     a.out = sl.out; a.ws_acc = sl.ws_acc; a.ws_ml = sl.ws_ml; a.arrivals = sl.arrivals;
     a.scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     a.union_off = union_off;
+    a.refresh_tail = sl.refresh_tail;
     const dim3 grid(cluster, g.n_kv_heads, batch), block(kSelThreads);
     return launch(step_kernel_of(g.page_size), grid, block, lds_bytes, stream, a, g, sp, ws);
 }

@@ -115,6 +115,47 @@ def test_cluster_sizes_give_the_same_page_lists(cluster):
         assert err <= ATOL_TIGHT, err
 
 
+@pytest.mark.parametrize("cluster", [1, 3])
+def test_fused_step_refreshes_the_tail_summaries(cluster):
+    """chess_decode_step with refresh_tail: the vectors of the tail page, its chunk and its grid are stale
+    (overwritten with junk here); the step must recompute them bit-exactly, score the fresh ones and leave them
+    in the summaries buffer.  Ragged lengths incl. a tail page that starts a new chunk and a new grid; window 0
+    in the second plan, so that the tail page itself competes."""
+    sp = RAGGED
+    lens = [3000, 1237, 641, 16 * 16 + 1, 16]        # 16*16+1: the tail page opens a chunk and a grid (N_c = N_g = 4)
+    wl = workload.generate(sp, 78, seq_lens=lens)
+    for plan in (plan_of(sp), plan_of(sp, window_pages=0, sink_pages=0)):
+        lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+        ref = run_oracle(wl, plan, sp.max_pages, dense=False)
+        d = to_device(wl)
+        summ, ws = lib.new_summaries(), lib.new_workspace()
+        lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+        pv, cv, gv = lib.summary_views(summ)
+        B, Nc, Ng = sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+        for b, L in enumerate(lens):
+            tp = -(-L // B) - 1
+            pv[b, :, tp] = 1e9; cv[b, :, tp // Nc] = -1e9; gv[b, :, tp // Nc // Ng] = float("nan")
+        lib.debug_force_cluster(cluster)
+        for _ in range(2):                               # the second call starts from refreshed summaries: same result
+            ids = torch.full((len(lens), sp.n_kv_heads, sp.max_pages), -7, dtype=torch.int32, device="cuda")
+            nsel = torch.full((len(lens), sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+            out = torch.full((len(lens), sp.n_q_heads, 128), float("nan"), device="cuda")
+            lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws,
+                            refresh_tail=True)
+            torch.cuda.synchronize()
+            assert lib.workspace_error(ws) == 0
+            got = GpuRunLike(*(t[:len(lens)].cpu().numpy() for t in lib.summary_views(summ)))
+            assert_summaries_equal(got, ref, sp, lens)
+            assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+            assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
+        lib.close()
+
+
+class GpuRunLike:
+    def __init__(self, pages, chunks, grids):
+        self.pages, self.chunks, self.grids = pages, chunks, grids
+
+
 def test_page32_gqa7_and_equal_norm_topics():
     """The stress shape scaled down (page 32, 28 / 4 heads), plus its equal-norm variant (near-tied scores)."""
     for name in ("cfg5", "cfg5adv"):
