@@ -4,7 +4,7 @@
 
 namespace chess {
 
-template <int B, int NW>
+template <int B, int NW, bool kList>
 __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ k_pool,
                                                          const uint16_t* __restrict__ v_pool,
@@ -27,7 +27,7 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     const int m16 = lane & 15, grp = lane >> 4;
     const int G = g.group, H = g.n_kv_heads;
     const size_t row = (size_t)b * H + h;
-    const int32_t* ids = page_ids ? page_ids + row * g.max_sel : nullptr;
+    const int32_t* ids = kList ? page_ids + row * g.max_sel : nullptr;
     const int32_t* bt_row = block_table + (size_t)b * g.max_pages;
     // tiles are dealt round-robin: tile = split + n_splits * (wave + NW * i), so the first tile of a wave
     // is known before the list length is, and its page numbers can be fetched alongside the lengths
@@ -35,17 +35,17 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     const int t = split + n_splits * wave;
     int raw_cur[PPT], raw_nxt[PPT];
     const int L_raw = seq_lens[b];
-    const int n_raw = page_ids ? n_selected[row] : 0;
-    fetch_ids<B>(raw_cur, t, ids, g.max_sel);
-    fetch_ids<B>(raw_nxt, t + stride, ids, g.max_sel);
+    const int n_raw = kList ? n_selected[row] : 0;
+    fetch_ids<B, kList>(raw_cur, t, ids, g.max_sel);
+    fetch_ids<B, kList>(raw_nxt, t + stride, ids, g.max_sel);
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
-    const int n_pages = P == 0 ? 0 : (page_ids ? min(max(n_raw, 0), g.max_sel) : P);
+    const int n_pages = P == 0 ? 0 : (kList ? min(max(n_raw, 0), g.max_sel) : P);
     const int n_tiles = (n_pages + PPT - 1) / PPT;
 
     WaveAcc<B> acc;
     acc.init(q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim, G, m16, grp);
-    run_tiles<B>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool, v_pool, H, h, L, P,
+    run_tiles<B, kList, false>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool, v_pool, H, h, L, P,
                  scale_log2, m16, grp);
 
     float* out_rows = out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
@@ -62,23 +62,25 @@ hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_po
     const Geom& g = ctx->geom;
     const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     const dim3 grid(n_splits, g.n_kv_heads, batch), block(64 * waves);
-    void (*kern)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
-                 const int32_t*, Geom, float, int, float*, float*, float*, int32_t*
-                 );
-    if (g.page_size == 16) kern = waves == 4 ? decode_kernel<16, 4> : decode_kernel<16, 1>;
-    else                   kern = waves == 4 ? decode_kernel<32, 4> : decode_kernel<32, 1>;
+    using Kern = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
+                          const int32_t*, Geom, float, int, float*, float*, float*, int32_t*);
+    // [page size 16 / 32][waves 4 / 1][list / every page]
+    static const Kern table[2][2][2] = {
+        {{decode_kernel<16, 4, true>, decode_kernel<16, 4, false>}, {decode_kernel<16, 1, true>, decode_kernel<16, 1, false>}},
+        {{decode_kernel<32, 4, true>, decode_kernel<32, 4, false>}, {decode_kernel<32, 1, true>, decode_kernel<32, 1, false>}}};
+    const Kern kern = table[g.page_size == 16 ? 0 : 1][waves == 4 ? 0 : 1][page_ids ? 0 : 1];
     return launch(kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
-                        page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals
-                        );
+                  page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
 }
 
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu)
 {
+    // (the list variant: it is the one whose split count depends on what fits)
     if (page_size == 16)
-        return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 4>, 256, 0)
-                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 1>, 64, 0);
-    return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 4>, 256, 0)
-                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1>, 64, 0);
+        return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 4, true>, 256, 0)
+                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 1, true>, 64, 0);
+    return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 4, true>, 256, 0)
+                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1, true>, 64, 0);
 }
 
 __global__ void zero_kernel(int32_t* p, size_t n)

@@ -39,17 +39,22 @@ struct Tile {
 
 // The logical page numbers of tile t as stored in the list (speculative: the index is clamped into the
 // row, validity is decided later), so that this load does not wait for the list length.
-template <int B>
+// kList: there is a list (compile-time, so that the list's address space stays known to the compiler: a run-time
+// choice between a list entry and a computed number becomes a choice between addresses, and the access a flat one).
+template <int B, bool kList>
 __device__ __forceinline__ void fetch_ids(int (&raw)[32 / B], int t, const int32_t* ids, int max_sel)
 {
     constexpr int PPT = 32 / B;
 #pragma unroll
-    for (int s = 0; s < PPT; ++s) raw[s] = ids ? ids[min(t * PPT + s, max_sel - 1)] : t * PPT + s;
+    for (int s = 0; s < PPT; ++s) {
+        if (kList) raw[s] = ids[min(t * PPT + s, max_sel - 1)];
+        else raw[s] = t * PPT + s;
+    }
 }
 
 // Request the K and V operands of tile t.  The physical page of a listed page comes from the block table, or,
 // when the caller has them at hand, from `phys_list` (physical pages in list order, n_pages >= 1 entries).
-template <int B>
+template <int B, bool kPhysList>
 __device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const int (&raw)[32 / B], const int32_t* bt_row,
                                           const int32_t* phys_list, const uint16_t* k_pool, const uint16_t* v_pool, int H,
                                           int h, int L, int P, int m16, int grp)
@@ -61,7 +66,9 @@ __device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const
         const bool ok = t * PPT + s < n_pages;
         int lp = ok ? raw[s] : raw[0];                            // unused slot: alias the tile's first page
         lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
-        const int pp = phys_list ? phys_list[min(ok ? t * PPT + s : t * PPT, n_pages - 1)] : bt_row[lp];
+        int pp;
+        if (kPhysList) pp = phys_list[min(ok ? t * PPT + s : t * PPT, n_pages - 1)];
+        else pp = bt_row[lp];
         phys[s] = __builtin_amdgcn_readfirstlane(pp);
         tl.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
     }
@@ -96,10 +103,14 @@ struct WaveAcc {
 
     __device__ __forceinline__ void init(const uint16_t* __restrict__ q_rows, int G, int m16, int grp)
     {
-        const uint4 z = make_uint4(0, 0, 0, 0);
         const uint4* src = reinterpret_cast<const uint4*>(q_rows + (size_t)(m16 < G ? m16 : 0) * kHeadDim) + grp;
-#pragma unroll
-        for (int st = 0; st < 4; ++st) qop[st] = as_bf16x8(m16 < G ? src[st * 4] : z);
+        const uint32_t keep = m16 < G ? 0xffffffffu : 0u;     // (a select between the load and a zero vector made
+#pragma unroll                                                //  the compiler select between two addresses instead)
+        for (int st = 0; st < 4; ++st) {
+            uint4 v = src[st * 4];
+            v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
+            qop[st] = as_bf16x8(v);
+        }
         m_run = kNegBig;
         l_run = 0.f;
 #pragma unroll
@@ -171,7 +182,7 @@ struct WaveAcc {
 // The next tile is always requested before the current one is computed, in the same straight-line block, so
 // the compiler waits only for the older loads (a load under its own branch would force a wait for everything
 // outstanding).  After the last tile the "next" request repeats the current tile: it hits in cache and is dropped.
-template <int B>
+template <int B, bool kList, bool kPhysList>
 __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
                                           int (&raw_cur)[32 / B], int (&raw_nxt)[32 / B], const int32_t* ids, int max_sel,
                                           const int32_t* bt_row, const int32_t* phys_list, const uint16_t* k_pool,
@@ -181,14 +192,14 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
     constexpr int PPT = 32 / B;
     if (t < n_tiles) {
         Tile<B> cur, nxt;
-        load_tile<B>(cur, t, n_pages, raw_cur, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
+        load_tile<B, kPhysList>(cur, t, n_pages, raw_cur, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
         for (; t < n_tiles; t += stride) {
             const bool more = t + stride < n_tiles;
             int raw_use[PPT];
 #pragma unroll
             for (int s = 0; s < PPT; ++s) raw_use[s] = more ? raw_nxt[s] : raw_cur[s];
-            load_tile<B>(nxt, more ? t + stride : t, n_pages, raw_use, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
-            fetch_ids<B>(raw_nxt, t + 2 * stride, ids, max_sel);
+            load_tile<B, kPhysList>(nxt, more ? t + stride : t, n_pages, raw_use, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
+            fetch_ids<B, kList>(raw_nxt, t + 2 * stride, ids, max_sel);
             acc.process(cur, scale_log2, grp);
             cur = nxt;
 #pragma unroll

@@ -754,7 +754,7 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
     int n_slots = ng;                                 // candidate slots of the current level
     const int32_t* parents = nullptr;                 // kept units of the level above, ascending
     int n_parents = 0;
-    const int tail_unit[3] = {ng - 1, nc - 1, P - 1};
+    auto tail_unit = [&](int lv) { return lv == 0 ? ng - 1 : lv == 1 ? nc - 1 : P - 1; };   // (no array: a run-time index would put it in scratch memory)
 #pragma unroll 1
     for (int level = 0; level < 3; ++level) {
         // level 0: every grid; level 1: chunks of kept grids; level 2: pages of kept chunks that are neither
@@ -817,10 +817,10 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         // the slot of the refreshed tail unit, if it competes at this level: the last child of the last parent
         SlotOverride ov{-1, nullptr, 0ull};
         if (tail_words != nullptr) {
-            const int u = tail_unit[level];
+            const int u = tail_unit(level);
             if (level == 0) ov.slot = u;
-            else if (n_parents > 0 && parents[n_parents - 1] == tail_unit[level - 1] && u >= u_lo && u < u_hi)
-                ov.slot = (n_parents - 1) * fan + (u - tail_unit[level - 1] * fan);
+            else if (n_parents > 0 && parents[n_parents - 1] == tail_unit(level - 1) && u >= u_lo && u < u_hi)
+                ov.slot = (n_parents - 1) * fan + (u - tail_unit(level - 1) * fan);
             ov.word = tail_words + level;
             ov.have = sh.tail_key[level];
         }

@@ -234,11 +234,11 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     const int stride = C * kStepWaves;
     const int t = m + C * wave;
     int raw_cur[PPT], raw_nxt[PPT];
-    fetch_ids<B>(raw_cur, t, ids_l, max(n_sel, 1));
-    fetch_ids<B>(raw_nxt, t + stride, ids_l, max(n_sel, 1));
+    fetch_ids<B, true>(raw_cur, t, ids_l, max(n_sel, 1));
+    fetch_ids<B, true>(raw_nxt, t + stride, ids_l, max(n_sel, 1));
     WaveAcc<B> acc;
     acc.init(q_rows, G, m16, grp);
-    run_tiles<B>(acc, t, stride, n_tiles, n_sel, raw_cur, raw_nxt, ids_l, max(n_sel, 1), bt_row, phys_l, a.k_pool, a.v_pool, H, h, L, P,
+    run_tiles<B, true, true>(acc, t, stride, n_tiles, n_sel, raw_cur, raw_nxt, ids_l, max(n_sel, 1), bt_row, phys_l, a.k_pool, a.v_pool, H, h, L, P,
                  a.scale_log2, m16, grp);
     prof.mark();                                                      // tiles done
     if (!combine_waves<kStepWaves>(acc.o, acc.m_run, acc.l_run, dl, G, C, m, row, out_rows, a.ws_acc, a.ws_ml)) return;
