@@ -281,6 +281,48 @@ def test_split_count_invariance_and_determinism():
     assert np.abs(outs[0] - ref).max() <= ATOL_TIGHT
 
 
+def test_step_in_a_hip_graph_replays_like_eager():
+    """The whole step captured in a HIP graph (as bench.py runs it): every replay, with eager launches and
+    synchronisations between the replays and a different query each time, gives the eager result bit for bit;
+    page_ids / n_selected may be NULL."""
+    sp = workload.spec("cfg2", scale=1 / 4)
+    wl = to_device(workload.generate(sp, workload.default_seed("cfg2")))
+    lib = pk.Chess(config_of(sp))
+    plan = gpu_plan(plan_of(sp))
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, summ)
+    qs = [wl.q] + [workload.extra_queries(wl, v) for v in range(1, 4)]
+    eager = []
+    for q in qs:
+        out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+        lib.decode_step(q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, plan, None, None, out, ws, refresh_tail=True)
+        torch.cuda.synchronize()
+        eager.append(out.clone())
+    q_in = torch.empty_like(wl.q)
+    out_g = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        q_in.copy_(qs[0])
+        lib.decode_step(q_in, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, plan, None, None, out_g, ws, refresh_tail=True)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            lib.decode_step(q_in, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, plan, None, None, out_g, ws,
+                            refresh_tail=True)
+        for rep in range(6):
+            i = rep % len(qs)
+            q_in.copy_(qs[i])
+            out_g.fill_(float("nan"))
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(out_g, eager[i]), f"replay {rep}"
+            scratch = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")     # eager work between replays
+            lib.dense_decode(qs[i], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, scratch, ws)
+            stream.synchronize()
+    assert lib.workspace_error(ws) == 0
+    lib.close()
+
+
 def test_zero_copy_pools_untouched_and_placement_invariance():
     sp = RAGGED
     wl = workload.generate(sp, 78, seq_lens=RAGGED_LENS)
@@ -314,6 +356,12 @@ def test_error_codes():
     with pytest.raises(pk.ChessError):       # batch beyond max_batch
         big = torch.zeros(6, dtype=torch.int32, device="cuda")
         lib.summarize(d.k_pool, d.block_table, big, summ)
+    out = torch.zeros((5, sp.n_q_heads, 128), device="cuda")
+    with pytest.raises(pk.ChessError):       # the fused step checks its plan the same way
+        lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, pk.SelectPlan(budget_pages=sp.max_selected),
+                        ids, nsel, out, ws)
+    with pytest.raises(pk.ChessError):       # ... and refuses a missing buffer
+        lib.decode_step(d.q, d.k_pool, None, d.block_table, d.seq_lens, summ, pk.SelectPlan(), ids, nsel, out, ws)
     with pytest.raises(pk.ChessError):
         pk.Chess(pk.Config(8, 3, 16, 1, 64, 8))          # 8 q heads over 3 kv heads
     with pytest.raises(pk.ChessError):
