@@ -472,6 +472,120 @@ __device__ __forceinline__ int cut_in_registers(const uint64_t (&key)[R], int n_
     return all ? n_valid : k;
 }
 
+// Cut and ordered compaction of a small level (at most kOneWaveSlots slots) by ONE wave, with no workgroup barrier
+// inside: wave 0 holds slot x * 64 + lane of the LDS copy of the keys in key[x] and does what cut_in_registers
+// does -- bounds from the upper key halves, linear-bin histogram, scan from the top, exact ranking of the bin at
+// the cut -- with ballots in place of the LDS lists (the other waves wait at the closing barrier; LDS operations of
+// one wave complete in order, so its own histogram needs no barrier).  Same contract as cut_in_registers, keys
+// from `keys` (LDS, complete: call after the pull's barrier); returns -1 (to every thread), having emitted nothing,
+// when more than kFastMembers keys share the bin at the cut.
+constexpr int kOneWaveRegs = 4;
+constexpr int kOneWaveSlots = kOneWaveRegs * kWave;
+template <class KFn, class Out>
+__device__ __forceinline__ int cut_one_wave(const uint64_t* keys, int n_slots, KFn k_of, Out emit, Shared& sh)
+{
+    constexpr int R = kOneWaveRegs;
+    const int tid = threadIdx.x, lane = tid & 63;
+    if (tid < kWave) {
+        const uint64_t below = __lanemask_lt();
+        auto f_add = [](int a, int b) { return a + b; };
+        uint64_t key[R];
+        unsigned lo_h = ~0u, hi_h = 0u;
+        int n_valid = 0;
+#pragma unroll
+        for (int x = 0; x < R; ++x) {
+            const int i = x * kWave + lane;
+            key[x] = i < n_slots ? keys[i] : 0ull;
+            const bool valid = key[x] != 0ull;
+            const unsigned h = (unsigned)(key[x] >> 32);
+            lo_h = valid ? min(lo_h, h) : lo_h;
+            hi_h = valid ? max(hi_h, h) : hi_h;
+            n_valid += __popcll(__ballot(valid));
+        }
+        const int k = k_of(n_valid);
+        int result;
+        if (k <= 0) {
+            result = 0;
+        } else {
+            const bool all = k >= n_valid;
+            int bin[R];
+            int cutbin = -1, want = 0, cnt = 0;
+            bool fits = true;
+            if (!all) {
+                lo_h = (unsigned)__builtin_amdgcn_readlane((int)wave_minmax32<true>(lo_h), 63);
+                hi_h = (unsigned)__builtin_amdgcn_readlane((int)wave_minmax32<false>(hi_h), 63);
+                const double smin = key_score((uint64_t)lo_h << 32);
+                const double scale = (double)kBins * __builtin_amdgcn_rcp(key_score(((uint64_t)hi_h << 32) | 0xffffffffull) - smin);
+#pragma unroll
+                for (int x = 0; x < R; ++x) {
+                    bin[x] = -1;
+                    if (key[x] != 0ull) {
+                        const int bx = (int)((key_score(key[x]) - smin) * scale);
+                        bin[x] = min(max(bx, 0), kBins - 1);
+                        atomicAdd(&sh.hist[hist_word(bin[x])], 1);
+                    }
+                }
+                int own = 0;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) own += sh.hist[64 * j + lane];
+                const int incl = wave_scan(own, 0, f_add);
+                const bool here = incl - own < k && k <= incl;
+                const int src = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(here)) - 1);
+                const int k_rem = k - (__builtin_amdgcn_readlane(incl, src) - __builtin_amdgcn_readlane(own, src));
+                const int c = lane < 16 ? sh.hist[64 * (15 - lane) + src] : 0;
+                int ci = c;
+                ci += __builtin_amdgcn_update_dpp(0, ci, 0x111, 0xf, 0xf, false);
+                ci += __builtin_amdgcn_update_dpp(0, ci, 0x112, 0xf, 0xf, false);
+                ci += __builtin_amdgcn_update_dpp(0, ci, 0x114, 0xf, 0xf, false);
+                ci += __builtin_amdgcn_update_dpp(0, ci, 0x118, 0xf, 0xf, false);
+                const int at = __builtin_amdgcn_readfirstlane(__ffsll((long long)__ballot(lane < 16 && ci >= k_rem)) - 1);
+                cutbin = 16 * (63 - src) + 15 - at;
+                cnt = __builtin_amdgcn_readlane(c, at);
+                want = k_rem - (__builtin_amdgcn_readlane(ci, at) - cnt);
+                fits = cnt <= kFastMembers;
+                // leave the histogram clean: this wave is its only user at this level
+#pragma unroll
+                for (int x = 0; x < R; ++x)
+                    if (bin[x] >= 0) sh.hist[hist_word(bin[x])] = 0;
+            } else {
+#pragma unroll
+                for (int x = 0; x < R; ++x) bin[x] = 0;
+            }
+            if (!fits) {
+                result = -1;
+            } else {
+                // rank the keys of the bin at the cut against each other: (key descending, slot ascending)
+                uint64_t em[R];
+                int rank[R];
+#pragma unroll
+                for (int x = 0; x < R; ++x) { em[x] = __ballot(!all && bin[x] == cutbin); rank[x] = 0; }
+#pragma unroll
+                for (int y = 0; y < R; ++y) {
+                    for (uint64_t mk = em[y]; mk != 0ull; mk &= mk - 1) {
+                        const int j = __builtin_amdgcn_readfirstlane(__ffsll((long long)mk) - 1);
+                        const uint64_t kj = lane_read64(key[y], j);
+                        const int sj = y * kWave + j;
+#pragma unroll
+                        for (int x = 0; x < R; ++x) rank[x] += kj > key[x] || (kj == key[x] && sj < x * kWave + lane);
+                    }
+                }
+                int base = 0;
+#pragma unroll
+                for (int x = 0; x < R; ++x) {
+                    const bool keep = all ? key[x] != 0ull : (bin[x] > cutbin || (bin[x] == cutbin && rank[x] < want));
+                    const uint64_t kb = __ballot(keep);
+                    if (keep) emit(base + __popcll(kb & below), x * kWave + lane);
+                    base += __popcll(kb);
+                }
+                result = base;
+            }
+        }
+        if (lane == 0) sh.cnt = result;
+    }
+    __syncthreads();
+    return sh.cnt;
+}
+
 // Scores of the slots [lo, hi), kFly units per 16-lane group requested before the first is waited for.
 // `unit_of(slot)` is the index of the slot's 128-float vector in `base`, or -1 when the slot has no unit.
 // Lane ln of a group holds probe dims 4 ln .. 4 ln + 3 and 64 + 4 ln .. 64 + 4 ln + 3.  The key of a slot goes
@@ -634,7 +748,14 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
                                             Shared& sh, Prof& prof)
 {
     int n = -1;
-    if (n_slots <= kRegsSmall * kSelThreads) {
+    if (n_slots <= kOneWaveSlots && !general) {
+        uint64_t key[kRegsSmall];
+        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key)) return -1;
+        after_pull();
+        if (local) __syncthreads();                   // the override, if any, is in the LDS copy
+        prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark();
+        n = cut_one_wave(keys, n_slots, k_of, emit, sh);
+    } else if (n_slots <= kRegsSmall * kSelThreads) {
         uint64_t key[kRegsSmall];
         if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key)) return -1;
         after_pull();
