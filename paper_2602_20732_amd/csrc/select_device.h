@@ -289,11 +289,11 @@ __device__ __forceinline__ unsigned wave_minmax32(unsigned v)
     return v;
 }
 
-// A key at or below the smallest key, a key at or above the largest key (both from the upper halves of
-// the keys: bounds are all the binning needs) and the number of non-empty keys of a level, from the
-// registers of the workgroup.  One workgroup barrier.
+// A key at or below the smallest key, a key at or above the largest key (both from the upper halves of the
+// keys: bounds are all the binning needs) and the number of non-empty keys of a level, in two steps around one
+// workgroup barrier (so that the barrier can be one the caller needs anyway): every wave leaves what it sees ...
 template <int R>
-__device__ __forceinline__ void level_stats(const uint64_t (&key)[R], Shared& sh, uint64_t* kmin, uint64_t* kmax, int* n_valid)
+__device__ __forceinline__ void wave_stats(const uint64_t (&key)[R], Shared& sh)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned a = ~0u, b = 0u;
@@ -309,8 +309,12 @@ __device__ __forceinline__ void level_stats(const uint64_t (&key)[R], Shared& sh
     a = wave_minmax32<true>(a);
     b = wave_minmax32<false>(b);
     if (lane == 63) { sh.st_min[wave] = a; sh.st_max[wave] = b; sh.st_cnt[wave] = n; }
-    __syncthreads();
-    a = ~0u; b = 0u; n = 0;
+}
+// ... and after the barrier everybody combines them.
+__device__ __forceinline__ void level_stats(const Shared& sh, uint64_t* kmin, uint64_t* kmax, int* n_valid)
+{
+    unsigned a = ~0u, b = 0u;
+    int n = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) {
         a = min(a, sh.st_min[w]);
@@ -656,11 +660,11 @@ __device__ __forceinline__ uint64_t poll_word(const uint64_t* word)
 
 // A level's keys into registers (thread t: slots t, t + 256, ...; 0 = empty or beyond n_slots) and into the
 // LDS copy the general path works on.  local: the keys are in LDS already.  Otherwise the published words
-// are polled until every one of them is there.  Ends with a workgroup barrier; returns false (to every
-// thread) if a word did not arrive within the poll limit.
+// are polled until every one of them is there.  Ends with a workgroup barrier, before which every wave has left
+// its statistics for level_stats; returns false (to every thread) if a word did not arrive within the poll limit.
 template <int R>
 __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool local, const SlotOverride& ov,
-                                          uint64_t* keys, uint64_t (&key)[R])
+                                          uint64_t* keys, uint64_t (&key)[R], Shared& sh)
 {
     const int tid = threadIdx.x;
     constexpr int kBatch = R < 8 ? R : 8;             // loads requested before the first is waited for
@@ -679,7 +683,7 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
                 keys[i] = key[x];
             }
         }
-        if (ov.slot < 0) return true;
+        wave_stats<R>(key, sh);
         return __syncthreads_and(ok) != 0;
     }
 #pragma unroll
@@ -708,6 +712,7 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
             if (i < n_slots) keys[i] = key[x];
         }
     }
+    wave_stats<R>(key, sh);
     return __syncthreads_and(ok) != 0;
 }
 
@@ -750,31 +755,30 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
     int n = -1;
     if (n_slots <= kOneWaveSlots && !general) {
         uint64_t key[kRegsSmall];
-        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key)) return -1;
+        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key, sh)) return -1;
         after_pull();
-        if (local) __syncthreads();                   // the override, if any, is in the LDS copy
         prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark();
         n = cut_one_wave(keys, n_slots, k_of, emit, sh);
     } else if (n_slots <= kRegsSmall * kSelThreads) {
         uint64_t key[kRegsSmall];
-        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key)) return -1;
+        if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key, sh)) return -1;
         after_pull();
         if (!general) {
             uint64_t kmin, kmax;
             int n_valid;
             prof.mark();
-            level_stats<kRegsSmall>(key, sh, &kmin, &kmax, &n_valid);
+            level_stats(sh, &kmin, &kmax, &n_valid);
             prof.mark();
             n = cut_in_registers<kRegsSmall>(key, n_slots, kmin, kmax, n_valid, k_of, emit, sh, prof);
         }
     } else if (n_slots <= kRegsLarge * kSelThreads) {
         uint64_t key[kRegsLarge];
-        if (!pull_keys<kRegsLarge>(pub, n_slots, local, ov, keys, key)) return -1;
+        if (!pull_keys<kRegsLarge>(pub, n_slots, local, ov, keys, key, sh)) return -1;
         after_pull();
         if (!general) {
             uint64_t kmin, kmax;
             int n_valid;
-            level_stats<kRegsLarge>(key, sh, &kmin, &kmax, &n_valid);
+            level_stats(sh, &kmin, &kmax, &n_valid);
             n = cut_in_registers<kRegsLarge>(key, n_slots, kmin, kmax, n_valid, k_of, emit, sh, prof);
         }
     } else if (local) {
