@@ -901,6 +901,37 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
             }
             return (u >= u_lo && u < u_hi) ? u : -1;
         };
+        const int cap = level == 0 ? sp.cap_kg : level == 1 ? sp.cap_kc : g.max_sel - s - w;
+        auto k_of = [&](int n) {
+            int k;
+            if (plan == CHESS_PLAN_RATIO) {
+                const int rho = level == 0 ? sp.rho_g_bp : level == 1 ? sp.rho_c_bp : sp.rho_p_bp;
+                k = n == 0 ? 0 : clamp_i(ceil_bp(n, rho), 1, n);
+            } else if (level == 2) {
+                k = min(n, k_budget);
+            } else if (plan == CHESS_PLAN_FLAT) {
+                k = n;
+            } else {
+                k = min(n, level == 0 ? ceil_div_i(sp.over_grid * kc_target, g.n_g) : kc_target);
+            }
+            return min(k, cap);
+        };
+        // A grid or chunk level that keeps every unit it has needs no scores at all: the kept list is the list of
+        // the units that exist (they are a prefix of the slots: only the last grid can lack chunks, and it is the
+        // last parent when it is kept).  Large budgets and ratios near 1 end up here.
+        if (level < 2 && !general) {
+            const int missing = (level == 1 && n_parents > 0 && parents[n_parents - 1] == ng - 1) ? ng * g.n_g - nc : 0;
+            const int n_present = n_slots - missing;
+            if (k_of(n_present) >= n_present) {
+                if (level == 0 && tail_words != nullptr && m == 0) refresh_tail();   // the summaries are still kept current
+                for (int i = threadIdx.x; i < n_present; i += kSelThreads) out[i] = unit_of(i);
+                __syncthreads();
+                parents = out;
+                n_parents = n_present;
+                n_slots = n_present * (level == 0 ? g.n_g : g.n_c);
+                continue;
+            }
+        }
         // A level is local when nothing is exchanged for it: a cluster of one; or the grid level when all grids fit
         // in one request, which every member then scores for itself (the same vectors, so the same keys) instead
         // of waiting a round trip for the others' shares (the host allows it when the repeated reads are few).
@@ -950,21 +981,6 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
             ov.have = sh.tail_key[level];
         }
 
-        const int cap = level == 0 ? sp.cap_kg : level == 1 ? sp.cap_kc : g.max_sel - s - w;
-        auto k_of = [&](int n) {
-            int k;
-            if (plan == CHESS_PLAN_RATIO) {
-                const int rho = level == 0 ? sp.rho_g_bp : level == 1 ? sp.rho_c_bp : sp.rho_p_bp;
-                k = n == 0 ? 0 : clamp_i(ceil_bp(n, rho), 1, n);
-            } else if (level == 2) {
-                k = min(n, k_budget);
-            } else if (plan == CHESS_PLAN_FLAT) {
-                k = n;
-            } else {
-                k = min(n, level == 0 ? ceil_div_i(sp.over_grid * kc_target, g.n_g) : kc_target);
-            }
-            return min(k, cap);
-        };
         const int n_kept = finish_level(pub, n_slots, local, general, ov, keys, k_of, after_pull, [&](int pos, int slot) {
             out[pos] = unit_of(slot);
             if (kPhys && level == 2) sel_phys[pos] = phys_by_slot[slot];

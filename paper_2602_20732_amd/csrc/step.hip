@@ -12,7 +12,7 @@
 
 namespace chess {
 
-static_assert(kSelThreads == 256, "the fused step decodes with four waves per workgroup");
+static_assert(kSelThreads % kWave == 0 && kSelThreads >= 256, "the fused step decodes with every wave of the workgroup");
 constexpr int kStepWaves = kSelThreads / kWave;
 
 struct StepArgs {
