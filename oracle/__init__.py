@@ -23,6 +23,7 @@ _SRC = os.path.join(_HERE, "chess_oracle.c")
 _LIB = os.path.join(_HERE, "liboracle.so")
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
+PROBE_QUERY, PROBE_ANCHOR = 0, 1         # what units are scored against: the query sum, or the Eq. 3 key anchor
 
 
 def build(force: bool = False) -> str:
@@ -42,7 +43,7 @@ class _Geom(ctypes.Structure):
 class _Plan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("plan", "sink_pages", "window_pages", "budget_pages", "budget_bp", "over_chunk", "over_grid",
-                 "rho_g_bp", "rho_c_bp", "rho_p_bp")]
+                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe")]
 
 
 @dataclass(frozen=True)
@@ -80,10 +81,11 @@ class Plan:
     rho_g_bp: int = 10000
     rho_c_bp: int = 10000
     rho_p_bp: int = 10000
+    probe: int = PROBE_QUERY
 
     def _c(self) -> _Plan:
         return _Plan(self.plan, self.sink_pages, self.window_pages, self.budget_pages, self.budget_bp,
-                     self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp)
+                     self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe)
 
 
 _lib = None
@@ -128,8 +130,9 @@ def summarize(k_pool, block_table, seq_lens, geom: Geometry):
     return pv, cv, gv
 
 
-def scores(q, page_vec, chunk_vec, grid_vec, seq_lens, geom: Geometry):
-    """Eq. 4 for every unit of every level, fp64; rows past a sequence's counts are NaN."""
+def scores(q, page_vec, chunk_vec, grid_vec, seq_lens, geom: Geometry, plan: "Plan | None" = None):
+    """Eq. 4 for every unit of every level, fp64; rows past a sequence's counts are NaN.  The probe is the
+    plan's (Eq. 3 anchor over its window, or the query sum); no plan = the query sum."""
     q, sl = _u16(q), _i32(seq_lens)
     batch = sl.shape[0]
     shp = (batch, geom.n_kv_heads)
@@ -137,9 +140,11 @@ def scores(q, page_vec, chunk_vec, grid_vec, seq_lens, geom: Geometry):
     cs = np.full(shp + (geom.max_chunks,), np.nan)
     gs = np.full(shp + (geom.max_grids,), np.nan)
     g = geom._c()
+    pl = plan._c() if plan is not None else None
     _load().oracle_scores(_p(q, ctypes.c_uint16), _p(page_vec, ctypes.c_float), _p(chunk_vec, ctypes.c_float),
                           _p(grid_vec, ctypes.c_float), _p(sl, ctypes.c_int32), ctypes.c_int32(batch),
-                          ctypes.byref(g), _p(ps, ctypes.c_double), _p(cs, ctypes.c_double), _p(gs, ctypes.c_double))
+                          ctypes.byref(g), ctypes.byref(pl) if pl is not None else None,
+                          _p(ps, ctypes.c_double), _p(cs, ctypes.c_double), _p(gs, ctypes.c_double))
     return ps, cs, gs
 
 

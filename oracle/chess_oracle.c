@@ -14,7 +14,8 @@
  * What each function follows:
  *   oracle_summarize  Sec. 3.1, Eq. 1 (page vector = mean of the page's key
  *                     rows) and Eq. 2 (chunk / grid vector = mean of children)
- *   oracle_scores     Sec. 3.2, Eq. 4 (dot product of probe and unit vector)
+ *   oracle_scores     Sec. 3.2, Eq. 4 (dot product of probe and unit vector); the probe is the group's
+ *                     query sum or the key-derived anchor of Eq. 3
  *   oracle_select     Sec. 3.2 cascade text and Alg. 1 stage 2 (grid -> chunk
  *                     -> page, a child is ranked only if its parent was kept),
  *                     then the union with sink and recent-window pages
@@ -45,6 +46,7 @@
 #include <string.h>
 
 enum { ORACLE_PLAN_BUDGET = 0, ORACLE_PLAN_RATIO = 1, ORACLE_PLAN_FLAT = 2 };
+enum { ORACLE_PROBE_QUERY = 0, ORACLE_PROBE_ANCHOR = 1 };
 
 typedef struct {
     int32_t n_q_heads;       /* H_q                                        */
@@ -66,6 +68,7 @@ typedef struct {
     int32_t over_chunk;    /* budget plan: chunk oversampling               */
     int32_t over_grid;     /* budget plan: grid oversampling                */
     int32_t rho_g_bp, rho_c_bp, rho_p_bp; /* ratio plan, basis points       */
+    int32_t probe;         /* ORACLE_PROBE_*: what the units are scored against */
 } oracle_plan;
 
 static double bf16_value(uint16_t h)
@@ -154,6 +157,33 @@ static void probe_of(const uint16_t *q, const oracle_geom *g, int b, int h, doub
     }
 }
 
+/*
+ * Sec. 3.2, Eq. 3: the query anchor, the mean of the page vectors of the recent
+ * window W (the last min(w, P) pages of the sequence), per KV head like every
+ * other vector here.  Summed in page order in fp64, divided by |W|, rounded to
+ * fp32 once like the other stored means of Eq. 1-2.
+ */
+static void anchor_of(const float *page_vec, const oracle_geom *g, int64_t row, int64_t P, int64_t w, double *probe)
+{
+    const int d = g->head_dim;
+    const int64_t W = w < P ? w : P;
+    for (int i = 0; i < d; ++i) {
+        double acc = 0.0;
+        for (int64_t j = P - W; j < P; ++j) acc += (double)page_vec[(row * g->max_pages + j) * d + i];
+        probe[i] = (double)(float)(acc / (double)W);
+    }
+}
+
+/* the probe the plan asks for (pl == NULL: the query probe) */
+static void probe_for(const oracle_plan *pl, const uint16_t *q, const float *page_vec, const oracle_geom *g,
+                      int b, int h, int64_t P, double *probe)
+{
+    if (pl && pl->probe == ORACLE_PROBE_ANCHOR)
+        anchor_of(page_vec, g, (int64_t)b * g->n_kv_heads + h, P, pl->window_pages, probe);
+    else
+        probe_of(q, g, b, h, probe);
+}
+
 static double dot_probe(const double *probe, const float *vec, int d)
 {
     double acc = 0.0;
@@ -167,7 +197,7 @@ static double dot_probe(const double *probe, const float *vec, int d)
  * Outputs fp64, same row strides as the summary arrays.
  */
 void oracle_scores(const uint16_t *q, const float *page_vec, const float *chunk_vec, const float *grid_vec,
-                   const int32_t *seq_lens, int32_t batch, const oracle_geom *g,
+                   const int32_t *seq_lens, int32_t batch, const oracle_geom *g, const oracle_plan *pl,
                    double *page_s, double *chunk_s, double *grid_s)
 {
     const int d = g->head_dim, B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
@@ -177,7 +207,8 @@ void oracle_scores(const uint16_t *q, const float *page_vec, const float *chunk_
         const int64_t P = ceil_div(seq_lens[b], B), nc = ceil_div(P, Nc), ng = ceil_div(nc, Ng);
         for (int h = 0; h < g->n_kv_heads; ++h) {
             const int64_t row = (int64_t)b * g->n_kv_heads + h;
-            probe_of(q, g, b, h, probe);
+            if (P == 0) continue;
+            probe_for(pl, q, page_vec, g, b, h, P, probe);
             for (int64_t j = 0; j < P; ++j)
                 page_s[row * g->max_pages + j] = dot_probe(probe, page_vec + (row * g->max_pages + j) * d, d);
             for (int64_t c = 0; c < nc; ++c)
@@ -249,7 +280,7 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
                 const int64_t k = pl->budget_pages > 0 ? pl->budget_pages
                                                        : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
                 const int64_t kc_target = ceil_div((int64_t)pl->over_chunk * k, Nc);
-                probe_of(q, g, b, h, probe);
+                probe_for(pl, q, page_vec, g, b, h, P, probe);
 
                 /* level 1: every grid is a candidate */
                 int64_t m = 0;

@@ -406,6 +406,60 @@ def test_planted_topic_is_recovered():
             assert want <= got
 
 
+# ------------------------------------------------------------------ Eq. 3: the key-derived query anchor
+def test_anchor_probe_is_the_mean_of_the_window_page_vectors(ragged):
+    """Scores under the anchor probe against the definition written with numpy from the raw keys:
+    anchor = mean over the last w pages of (mean of the page's key rows); S(u) = anchor . v_u.  With w = 1 the
+    anchor is the tail page's vector, so S(tail page) = |v_tail|^2; sum_{p in W} S(p) / |W| = |anchor|^2 >= 0."""
+    sp, wl, (K, V, Q, bt, sl) = ragged
+    g = geom_of(sp)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    B = sp.page_size
+    for w in (1, 2, 5):
+        plan = plan_of(sp, window_pages=w, probe=oracle.PROBE_ANCHOR)
+        ps, cs, gs = oracle.scores(Q, pv, cv, gv, sl, g, plan)
+        for b in range(sp.batch):
+            L = int(sl[b]); P = -(-L // B); W = min(w, P)
+            for h in range(sp.n_kv_heads):
+                Kl, _ = logical_kv(K, V, bt, L, b, h)
+                page_means = np.stack([Kl[j * B:min((j + 1) * B, L)].mean(0) for j in range(P)])
+                anchor = page_means[P - W:].mean(0)
+                np.testing.assert_allclose(ps[b, h, :P], page_means @ anchor, rtol=2e-6, atol=2e-6)
+                np.testing.assert_allclose(ps[b, h, P - W:P].mean(), anchor @ anchor, rtol=2e-6, atol=2e-6)
+                if w == 1:
+                    np.testing.assert_allclose(ps[b, h, P - 1], page_means[P - 1] @ page_means[P - 1], rtol=2e-6)
+                nc = -(-P // sp.pages_per_chunk)
+                np.testing.assert_allclose(cs[b, h, :nc], cv[b, h, :nc].astype(np.float64) @ anchor, rtol=2e-6, atol=2e-6)
+
+
+def test_anchor_selection_ignores_the_query_and_the_scale_of_the_keys(ragged):
+    """Eq. 3-4 use keys only: another query gives the same pages; doubling every key multiplies all scores by 4
+    and gives the same pages; and the list differs from the query probe's (so the switch is not a no-op)."""
+    sp, wl, (K, V, Q, bt, sl) = ragged
+    g = geom_of(sp)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    plan = plan_of(sp, probe=oracle.PROBE_ANCHOR)
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, g, plan, sp.max_selected)
+    Q2 = f32_to_bf16_bits(np.random.default_rng(5).standard_normal(Q.shape).astype(np.float32))
+    ids2, nsel2 = oracle.select(Q2, pv, cv, gv, sl, g, plan, sp.max_selected)
+    assert np.array_equal(ids, ids2) and np.array_equal(nsel, nsel2)
+    ids3, nsel3 = oracle.select(Q, 2 * pv, 2 * cv, 2 * gv, sl, g, plan, sp.max_selected)
+    assert np.array_equal(ids, ids3) and np.array_equal(nsel, nsel3)
+    idq, _ = oracle.select(Q, pv, cv, gv, sl, g, plan_of(sp), sp.max_selected)
+    assert not np.array_equal(ids, idq)
+    # brute force under the flat plan: stable argsort of the anchor's page scores
+    flat = plan_of(sp, plan=oracle.PLAN_FLAT, budget_pages=7, probe=oracle.PROBE_ANCHOR)
+    idf, nf = oracle.select(Q, pv, cv, gv, sl, g, flat, sp.max_pages)
+    ps, _, _ = oracle.scores(Q, pv, cv, gv, sl, g, flat)
+    for b in range(sp.batch):
+        P = -(-int(sl[b]) // sp.page_size)
+        for h in range(sp.n_kv_heads):
+            cand = np.arange(flat.sink_pages, P - flat.window_pages)
+            order = cand[np.argsort(-ps[b, h, cand], kind="stable")][:7]
+            want = sorted(set(range(flat.sink_pages)) | set(order.tolist()) | set(range(P - flat.window_pages, P)))
+            assert idf[b, h, :nf[b, h]].tolist() == want
+
+
 # ------------------------------------------------------------------ P12: degenerate hierarchy
 def test_one_token_pages_give_token_level_topk_attention():
     rng = np.random.default_rng(4)
