@@ -50,6 +50,11 @@ extern "C" {
 #define CHESS_PLAN_RATIO  1  /* the paper's retention ratios rho_g, rho_c, rho_p              */
 #define CHESS_PLAN_FLAT   2  /* keep every grid and chunk: plain top-k over pages             */
 
+/* What a unit's vector is scored against (Sec. 3.2). */
+#define CHESS_PROBE_QUERY  0 /* the sum of the KV head's G query rows (the decode query)                   */
+#define CHESS_PROBE_ANCHOR 1 /* Eq. 3: the mean of the page vectors of the recent window (the last          */
+                             /* window_pages pages), keys only; q is then not read and may be NULL          */
+
 typedef struct chess_ctx chess_ctx; /* opaque; small host-side state only */
 
 typedef struct {
@@ -76,6 +81,7 @@ typedef struct {
     int32_t rho_g_bp;           /* PLAN_RATIO: ratios in basis points; a level keeps         */
     int32_t rho_c_bp;           /*   clamp(ceil(n * rho), 1, n) of its n active units        */
     int32_t rho_p_bp;
+    int32_t probe;              /* CHESS_PROBE_*; the anchor needs window_pages >= 1         */
 } chess_select_plan;
 
 /* Create / destroy the host-side context.  `cfg` is a host pointer and is copied.  Queries the
@@ -150,6 +156,8 @@ int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const 
  * between the two stages; it is also written to page_ids / n_selected unless those are NULL (pass them
  * to reuse the list in later steps, as the paper does between reselections, Sec. 3.3).
  * Arguments, layouts and errors as for the two calls.
+ * With CHESS_PROBE_ANCHOR the attention still uses q; the selection does not.  (The anchor reads the window's
+ * page vectors before anything else, so it cannot be combined with refresh_tail: CHESS_ENOTSUP.)
  * refresh_tail != 0: the launch first does what chess_summarize_tail does (Sec. 3.1, Eq. 1-2: the vectors of
  * the tail page, its chunk and its grid are recomputed from the K pool, written to `summaries`, and are the
  * ones the selection scores), so a decode step is this one call.  refresh_tail == 0: `summaries` is only read

@@ -12,6 +12,7 @@ from dataclasses import dataclass
 import torch
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
+PROBE_QUERY, PROBE_ANCHOR = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libchess.so")
@@ -35,7 +36,7 @@ class _CConfig(ctypes.Structure):
 class _CPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("plan", "sink_pages", "window_pages", "budget_pages", "budget_bp", "over_chunk", "over_grid",
-                 "rho_g_bp", "rho_c_bp", "rho_p_bp")]
+                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe")]
 
 
 @dataclass(frozen=True)
@@ -64,10 +65,11 @@ class SelectPlan:
     rho_g_bp: int = 10000
     rho_c_bp: int = 10000
     rho_p_bp: int = 10000
+    probe: int = PROBE_QUERY
 
     def _c(self) -> _CPlan:
         return _CPlan(self.plan, self.sink_pages, self.window_pages, self.budget_pages, self.budget_bp,
-                      self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp)
+                      self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe)
 
 
 def library_path() -> str:

@@ -25,6 +25,8 @@ bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
     const chess::Geom& g = ctx->geom;
     const int64_t P = g.max_pages, nc = g.max_chunks, ng = g.max_grids;
     if (pl->sink_pages < 0 || pl->window_pages < 0) return false;
+    if (pl->probe != CHESS_PROBE_QUERY && pl->probe != CHESS_PROBE_ANCHOR) return false;
+    if (pl->probe == CHESS_PROBE_ANCHOR && pl->window_pages < 1) return false;
     const int64_t cand = std::max<int64_t>(0, P - pl->sink_pages - pl->window_pages);   // pages that may compete
     int64_t kmax = 0;
     if (pl->plan != CHESS_PLAN_RATIO) {
@@ -261,6 +263,7 @@ static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::
     sp.cap_keys = (int32_t)bd.slots;
     sp.cap_kg = (int32_t)bd.kg;
     sp.cap_kc = (int32_t)bd.kc;
+    sp.probe = plan->probe;
     sp.general_cut = ctx->force_general_cut;
     *out = sp;
     return CHESS_OK;
@@ -281,7 +284,8 @@ static chess::SelectWs select_ws(const chess_ctx* ctx, void* workspace)
 int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
                  const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace, void* stream)
 {
-    if (!ctx || !q || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
+    if (!ctx || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
+    if (!q && plan->probe != CHESS_PROBE_ANCHOR) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
     if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(workspace)) & 15)
         return CHESS_EINVAL;
@@ -328,6 +332,7 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
         return CHESS_EINVAL;
     chess::SelectParams sp;
     if (int rc = prepare_select(ctx, plan, &sp)) return rc;
+    if (sp.probe == CHESS_PROBE_ANCHOR && refresh_tail != 0) return CHESS_ENOTSUP;
     int union_off = 0;
     const size_t lds = chess::step_lds_bytes(sp, ctx->geom.max_sel, &union_off);
     if (lds + 8192 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;

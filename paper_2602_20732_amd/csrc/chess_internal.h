@@ -26,6 +26,7 @@ struct SelectParams {
     int32_t plan, sink, window, budget_pages, budget_bp, over_chunk, over_grid, rho_g_bp, rho_c_bp, rho_p_bp;
     int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
     int32_t cap_keys, cap_kg, cap_kc;   // LDS capacities: keys of one level, kept grids, kept chunks
+    int32_t probe;                   // CHESS_PROBE_*
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
     int32_t local_grids;             // every member scores all grids itself (no exchange at the grid level)
 };

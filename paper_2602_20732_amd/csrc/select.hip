@@ -30,7 +30,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     const int B = g.page_size;
     const int L_raw = seq_lens[b];
     double pr[8];
-    load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);   // requested before anything waits on the length
+    if (sp.probe == CHESS_PROBE_QUERY)                                // requested before anything waits on the length
+        load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
     if (tid < 3) sh.tail_key[tid] = 0ull;
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
         }
         return;
     }
+    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor(pages + row * g.max_pages * kHeadDim, P, w, pr);
     __syncthreads();
     prof.mark();                                                      // 1: prologue done
 

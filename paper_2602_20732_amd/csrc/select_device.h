@@ -137,6 +137,34 @@ struct Shared {
     uint64_t tail_key[3];   // keys of the refreshed tail grid / chunk / page when this workgroup computed them, else 0
 };
 
+// Eq. 3: the query anchor of a (sequence, KV head), the mean of the page vectors of the recent window (the last
+// min(w, P) pages): fp64 sum in page order, divided by the count, rounded to fp32 once like every stored mean.
+// This lane's dims as in load_probe.  The window's vectors are requested four pages at a time.
+__device__ __forceinline__ void load_anchor(const float* __restrict__ pages_row, int P, int w, double (&pr)[8])
+{
+    const int ln = threadIdx.x & 15;
+    const int W = min(w, P), first = P - W;
+    double acc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int j0 = first; j0 < P; j0 += 4) {
+        float4 va[4], vb[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const float4* p = reinterpret_cast<const float4*>(pages_row + (size_t)min(j0 + x, P - 1) * kHeadDim) + ln;
+            va[x] = p[0];
+            vb[x] = p[16];
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            if (j0 + x < P) {
+                acc[0] += (double)va[x].x; acc[1] += (double)va[x].y; acc[2] += (double)va[x].z; acc[3] += (double)va[x].w;
+                acc[4] += (double)vb[x].x; acc[5] += (double)vb[x].y; acc[6] += (double)vb[x].z; acc[7] += (double)vb[x].w;
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pr[i] = (double)(float)(acc[i] / (double)W);
+}
+
 struct Prof {
 #ifdef CHESS_PROF
     long long t[48];

@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     float* out_rows = a.out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     const int L_raw = a.seq_lens[b];
     double pr[8];
-    load_probe(q_rows, G, pr);                                        // requested before anything waits on the length
+    if (sp.probe == CHESS_PROBE_QUERY) load_probe(q_rows, G, pr);     // requested before anything waits on the length
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
     if (tid < 3) sh.tail_key[tid] = 0ull;
@@ -168,6 +168,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
         }
         return;
     }
+    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor(a.pages + row * g.max_pages * kHeadDim, P, w, pr);
     // member 0 refreshes the tail units: its block-table entry is requested now
     const bool tail_on = a.refresh_tail != 0;
     uint64_t* tail_words = tail_on ? ws.tail + row * 4 : nullptr;

@@ -123,7 +123,7 @@ def classify_selection(gpu_ids, gpu_n, ref: OracleRun, wl, plan: oracle.Plan):
     sp = wl.spec
     K, V, Q, bt, sl = ref.host
     g = geom_of(sp)
-    ps, cs, gs = oracle.scores(Q, ref.pages, ref.chunks, ref.grids, sl, g)
+    ps, cs, gs = oracle.scores(Q, ref.pages, ref.chunks, ref.grids, sl, g, plan)
     hard, near = [], []
     for b in range(gpu_ids.shape[0]):
         for h in range(gpu_ids.shape[1]):

@@ -68,6 +68,8 @@ RAGGED_LENS = [3000, 1237, 641, 16, 0]
     dict(plan=oracle.PLAN_RATIO, rho_g_bp=9000, rho_c_bp=9000, rho_p_bp=9000),
     dict(plan=oracle.PLAN_FLAT, budget_pages=16),
     dict(plan=oracle.PLAN_RATIO),                                  # ratios 1,1,1: Full-KV through the sparse path
+    dict(plan=oracle.PLAN_BUDGET, probe=oracle.PROBE_ANCHOR),      # Eq. 3: units scored against the window's key anchor
+    dict(plan=oracle.PLAN_RATIO, rho_g_bp=5000, rho_c_bp=2000, rho_p_bp=1000, probe=oracle.PROBE_ANCHOR, window_pages=3),
 ])
 def test_ragged_batch_all_plans(plan_kw):
     """GQA 4, ragged lengths incl. a partial tail page, partial chunk / grid, a one-page and an empty sequence."""
@@ -154,6 +156,32 @@ def test_fused_step_refreshes_the_tail_summaries(cluster):
 class GpuRunLike:
     def __init__(self, pages, chunks, grids):
         self.pages, self.chunks, self.grids = pages, chunks, grids
+
+
+def test_anchor_probe_at_cfg1_and_refusals():
+    """Eq. 3 probe on the 4K configuration, several members per (sequence, head); it cannot be combined with the
+    in-launch tail refresh, needs a window, and lets chess_select run without a query."""
+    sp = workload.spec("cfg1")
+    wl = workload.generate(sp, workload.default_seed("cfg1"))
+    plan = plan_of(sp, probe=oracle.PROBE_ANCHOR)
+    check_all(sp, wl, plan, dense=False, label="cfg1 anchor")
+    lib = pk.Chess(config_of(sp))
+    d = to_device(wl)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    ids = torch.zeros((1, sp.n_kv_heads, sp.max_selected), dtype=torch.int32, device="cuda")
+    nsel = torch.zeros((1, sp.n_kv_heads), dtype=torch.int32, device="cuda")
+    out = torch.zeros((1, sp.n_q_heads, 128), device="cuda")
+    lib.select(None, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)             # no query needed
+    torch.cuda.synchronize()
+    ref = run_oracle(wl, plan, sp.max_selected, dense=False)
+    assert np.array_equal(ids.cpu().numpy(), ref.ids)
+    with pytest.raises(pk.ChessError):
+        lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws,
+                        refresh_tail=True)
+    with pytest.raises(pk.ChessError):
+        lib.select(d.q, summ, d.seq_lens, gpu_plan(plan_of(sp, probe=oracle.PROBE_ANCHOR, window_pages=0)), ids, nsel, ws)
+    lib.close()
 
 
 def test_page32_gqa7_and_equal_norm_topics():
