@@ -20,7 +20,7 @@ _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
            "chess_summarize", "chess_summarize_tail", "chess_select", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
-           "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_workspace_error", "chess_strerror", "chess_version"]
+           "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
 class ChessError(RuntimeError):
@@ -100,6 +100,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
         lib.chess_debug_force_cluster.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_force_general_cut.argtypes = [vp, ctypes.c_int32]
+        lib.chess_debug_set_poll_limit.argtypes = [vp, ctypes.c_int32]
         lib.chess_workspace_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
         lib.chess_strerror.argtypes = [ctypes.c_int]
         lib.chess_strerror.restype = ctypes.c_char_p
@@ -213,6 +214,9 @@ class Chess:
 
     def debug_force_general_cut(self, on: bool):
         self._check(self.lib.chess_debug_force_general_cut(self._h, int(bool(on))))
+
+    def debug_set_poll_limit(self, polls: int):
+        self._check(self.lib.chess_debug_set_poll_limit(self._h, polls))
 
     def debug_force_splits(self, n_splits: int, waves: int = 4):
         self._check(self.lib.chess_debug_force_splits(self._h, n_splits, waves))

@@ -167,6 +167,7 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
     c->force_cluster = 0;
     c->force_general_cut = 0;
+    c->poll_limit = 0;
     c->occ_lds = -1;
     c->occ_blocks = 0;
     c->step_occ_lds = -1;
@@ -264,6 +265,7 @@ static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::
     sp.cap_kg = (int32_t)bd.kg;
     sp.cap_kc = (int32_t)bd.kc;
     sp.probe = plan->probe;
+    sp.poll_limit = ctx->poll_limit > 0 ? ctx->poll_limit : (1 << 15);
     sp.general_cut = ctx->force_general_cut;
     *out = sp;
     return CHESS_OK;
@@ -383,6 +385,13 @@ int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on)
 {
     if (!ctx || (on != 0 && on != 1)) return CHESS_EINVAL;
     ctx->force_general_cut = on;
+    return CHESS_OK;
+}
+
+int chess_debug_set_poll_limit(chess_ctx* ctx, int32_t polls)
+{
+    if (!ctx || polls < 0) return CHESS_EINVAL;
+    ctx->poll_limit = polls;
     return CHESS_OK;
 }
 

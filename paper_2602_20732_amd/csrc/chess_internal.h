@@ -27,6 +27,7 @@ struct SelectParams {
     int32_t cap2, cap3;              // most candidate slots level 2 / level 3 can have (host bound)
     int32_t cap_keys, cap_kg, cap_kc;   // LDS capacities: keys of one level, kept grids, kept chunks
     int32_t probe;                   // CHESS_PROBE_*
+    int32_t poll_limit;              // polls before a wait for published keys is given up
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
     int32_t local_grids;             // every member scores all grids itself (no exchange at the grid level)
 };
@@ -103,6 +104,7 @@ struct chess_ctx {
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
     int force_general_cut;                                 // 0 = automatic
+    int poll_limit;                                        // 0 = the default
     int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
     int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
     int step_occ_lds, step_occ_blocks;                     // ... and of the fused step kernel

@@ -34,7 +34,7 @@
 namespace chess {
 
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kPollLimit = 1 << 15;         // polls (each a memory round trip, ~1 us) before a wait is declared dead
+constexpr int kPollLimit = 1 << 15;         // polls (each a memory round trip, ~1 us) before a wait is declared dead (default)
 constexpr int kKeepAll = 0x7fffffff;
 constexpr uint64_t kAbsentKey = 1ull;       // published for a slot that has no unit; below every real key
 
@@ -134,6 +134,7 @@ struct Shared {
     unsigned int or_lo, or_hi, and_lo, and_hi;
     unsigned st_min[kSelWaves], st_max[kSelWaves];   // upper halves of the waves' smallest / largest key of a level
     int st_cnt[kSelWaves];
+    int poll_limit;         // polls before a wait is given up (kPollLimit unless a test lowered it)
     uint64_t tail_key[3];   // keys of the refreshed tail grid / chunk / page when this workgroup computed them, else 0
 };
 
@@ -676,9 +677,9 @@ struct SlotOverride {
 };
 
 // Wait for one published word; 0 if it did not arrive within the poll limit.
-__device__ __forceinline__ uint64_t poll_word(const uint64_t* word)
+__device__ __forceinline__ uint64_t poll_word(const uint64_t* word, int limit)
 {
-    for (int polls = 0; polls < kPollLimit; ++polls) {
+    for (int polls = 0; polls < limit; ++polls) {
         const uint64_t v = observe_u64(word);
         if (v != 0ull) return v;
         __builtin_amdgcn_s_sleep(1);
@@ -706,7 +707,7 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
             const int i = x * kSelThreads + tid;
             if (i < n_slots) key[x] = keys[i];
             if (i == ov.slot) {
-                key[x] = ov.have != 0ull ? ov.have : poll_word(ov.word);
+                key[x] = ov.have != 0ull ? ov.have : poll_word(ov.word, sh.poll_limit);
                 ok = key[x] != 0ull;
                 keys[i] = key[x];
             }
@@ -730,7 +731,7 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
             for (int x = x0; x < x0 + kBatch && x < R; ++x)
                 missing = missing || (x * kSelThreads + tid < n_slots && key[x] == 0ull);
             if (__ballot(missing) == 0ull) break;
-            if (++polls >= kPollLimit) { ok = false; break; }
+            if (++polls >= sh.poll_limit) { ok = false; break; }
             __builtin_amdgcn_s_sleep(1);
         }
 #pragma unroll
@@ -745,7 +746,8 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, int n_slots, bool
 }
 
 // The same for a level too large for the register path: into LDS only.
-__device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, const SlotOverride& ov, uint64_t* keys)
+__device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, const SlotOverride& ov, uint64_t* keys,
+                                              int limit)
 {
     bool ok = true;
     for (int i0 = 0; i0 < n_slots; i0 += 4 * kSelThreads) {
@@ -761,7 +763,7 @@ __device__ __forceinline__ bool pull_keys_lds(const uint64_t* pub, int n_slots, 
 #pragma unroll
             for (int x = 0; x < 4; ++x) missing = missing || v[x] == 0ull;
             if (__ballot(missing) == 0ull) break;
-            if (++polls >= kPollLimit) { ok = false; break; }
+            if (++polls >= limit) { ok = false; break; }
             __builtin_amdgcn_s_sleep(1);
         }
 #pragma unroll
@@ -813,14 +815,14 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
         __syncthreads();
         bool ok = true;
         if (ov.slot >= 0 && (int)threadIdx.x == 0) {
-            const uint64_t k = ov.have != 0ull ? ov.have : poll_word(ov.word);
+            const uint64_t k = ov.have != 0ull ? ov.have : poll_word(ov.word, sh.poll_limit);
             ok = k != 0ull;
             keys[ov.slot] = k;
         }
         if (ov.slot >= 0 && __syncthreads_and(ok) == 0) return -1;
         after_pull();
     } else {
-        if (!pull_keys_lds(pub, n_slots, ov, keys)) return -1;
+        if (!pull_keys_lds(pub, n_slots, ov, keys, sh.poll_limit)) return -1;
         after_pull();
     }
     if (n >= 0) return n;

@@ -156,6 +156,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
     if (tid == 0) sh.n_mem = 0;
     if (tid < 3) sh.tail_key[tid] = 0ull;
+    if (tid == 0) sh.poll_limit = sp.poll_limit;
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;

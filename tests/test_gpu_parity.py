@@ -351,6 +351,37 @@ def test_step_in_a_hip_graph_replays_like_eager():
     lib.close()
 
 
+def test_a_wait_that_is_given_up_raises_the_error_flag_and_every_kernel_still_ends():
+    """The members of a cluster wait for each other's keys with a bounded number of polls.  With the bound forced
+    down to one poll the waits fail: the launches must still end by themselves, the workspace's error flag must be
+    up, and after re-initialising the workspace (and restoring the bound) the results are right again."""
+    sp = workload.spec("cfg2", scale=1 / 2)
+    wl = workload.generate(sp, workload.default_seed("cfg2"))
+    plan = plan_of(sp)
+    lib = pk.Chess(config_of(sp))
+    ref = run_oracle(wl, plan, sp.max_selected, dense=False)
+    d = to_device(wl)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    ids = torch.full((1, sp.n_kv_heads, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((1, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+    lib.debug_force_cluster(4)
+    lib.debug_set_poll_limit(1)
+    lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws)
+    torch.cuda.synchronize()                              # returns: nobody is left waiting
+    assert lib.workspace_error(ws) == 1
+    lib.debug_set_poll_limit(0)
+    ws = lib.new_workspace()
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+    assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
+    lib.close()
+
+
 def test_zero_copy_pools_untouched_and_placement_invariance():
     sp = RAGGED
     wl = workload.generate(sp, 78, seq_lens=RAGGED_LENS)
