@@ -169,6 +169,31 @@ def main():
             wall_ms = (time.perf_counter() - t_wall) * 1e3
         return max(e0.elapsed_time(e1), 0.0) / steps, wall_ms / steps
 
+    def spread(fn, block=16, replays=32):
+        """p10 / median / p90 of the time per step over `replays` separately timed replays of a `block`-step graph."""
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            for i in range(block):
+                fn(i)
+            stream.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                for i in range(block):
+                    fn(i)
+            g.replay()
+            stream.synchronize()
+            ts = []
+            for _ in range(replays):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                g.replay()
+                e1.record(stream)
+                stream.synchronize()
+                ts.append(e0.elapsed_time(e1) * 1e3 / block)
+        ts.sort()
+        pick = lambda f: round(ts[min(len(ts) - 1, int(f * len(ts)))], 3)
+        return {"p10": pick(0.1), "median": pick(0.5), "p90": pick(0.9), "steps_per_sample": block, "samples": replays}
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -179,6 +204,14 @@ def main():
 
     ms_step, wall_ms_step = timed(step, args.steps, args.warmup, not args.eager)
     ms_three, _ = timed(step_three_calls, args.steps, min(args.warmup, 8), not args.eager)
+    step_spread = None if args.eager else spread(step)
+
+    # the full summarize pass (prefill time, not part of the step): a pure stream of the K pool
+    def full_summarize(i):
+        wl, _ = pools[i % n_pools]
+        lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, summs[i % n_pools])
+
+    ms_full, _ = timed(full_summarize, max(2, min(8, n_pools * 2)), 1, False)
 
     # per-phase durations: each phase alone, same rotation, replayed as its own HIP graph and timed with
     # HIP events on the launch stream (inside a graph the gaps between kernels are negligible, so the
@@ -246,6 +279,7 @@ def main():
         "step_gbs": round(ab["step"] / (ms_step * 1e-3) / 1e9, 1),
         "step_frac_of_hbm_peak": round(ab["step"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
         "wall_us_per_step": round(wall_ms_step * 1e3, 3),
+        "us_per_step_spread": step_spread,
         "algorithmic_bytes": ab,
         "kernels": kern,
         "three_calls": {"us_per_step": round(ms_three * 1e3, 3), "kernels": kern3,
@@ -256,6 +290,12 @@ def main():
         "setup_seconds": round(gen_s, 1),
     }
 
+    B_, d_ = sp.page_size, sp.head_dim
+    full_bytes = sum(-(-L // B_) for L in lens) * sp.n_kv_heads * (B_ * d_ * 2 + d_ * 4) \
+        + sum(-(-(-(-L // B_)) // sp.pages_per_chunk) for L in lens) * sp.n_kv_heads * d_ * 4
+    result["summarize_full_pass"] = {"us": round(ms_full * 1e3, 1), "bytes": full_bytes,
+                                     "gbs": round(full_bytes / (ms_full * 1e-3) / 1e9, 1),
+                                     "frac_of_hbm_peak": round(full_bytes / (ms_full * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if args.workload == "cfg3":
         result["stack_of_32_layers_us"] = round(ms_step * 1e3 * 32, 1)
 
