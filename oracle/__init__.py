@@ -96,6 +96,7 @@ def _load():
     if _lib is None:
         _lib = ctypes.CDLL(build())
         _lib.oracle_select.restype = ctypes.c_int
+        _lib.oracle_select_shared.restype = ctypes.c_int
     return _lib
 
 
@@ -168,6 +169,48 @@ def select(q, page_vec, chunk_vec, grid_vec, seq_lens, geom: Geometry, plan: Pla
     if rc != 0:
         raise ValueError("oracle_select: a row needs more than max_sel page ids")
     return (ids, nsel, kg, kc, cnt) if detail else (ids, nsel)
+
+
+def anchor(page_vec, seq_lens, geom: Geometry, window_pages: int):
+    """Eq. 3: the key anchor of every (sequence, KV head), fp32 [b, H_kv, d]."""
+    sl = _i32(seq_lens)
+    batch = sl.shape[0]
+    out = np.zeros((batch, geom.n_kv_heads, geom.head_dim), np.float32)
+    g = geom._c()
+    _load().oracle_anchor(_p(np.ascontiguousarray(page_vec), ctypes.c_float), _p(sl, ctypes.c_int32),
+                          ctypes.c_int32(batch), ctypes.byref(g), ctypes.c_int32(window_pages), _p(out, ctypes.c_float))
+    return out
+
+
+def select_shared(probes, page_vecs, chunk_vecs, grid_vecs, seq_lens, geom: Geometry, plan: Plan, max_sel: int,
+                  detail=False):
+    """The cascade under the model-wide scope of Eq. 1: lists of per-layer arrays (probes fp32 [b,H_kv,d] and the
+    three summary levels); a unit's score is the sum over layers and KV heads of the per-head dots.  Returns
+    (page_ids [b,max_sel] padded -1, n_selected [b]); with detail=True also counts [b,3] = k_g, k_c, k_p."""
+    sl = _i32(seq_lens)
+    batch, n_layers = sl.shape[0], len(probes)
+    assert len(page_vecs) == len(chunk_vecs) == len(grid_vecs) == n_layers
+
+    def table(arrs):
+        keep = [np.ascontiguousarray(a, dtype=np.float32) for a in arrs]
+        ptrs = (ctypes.POINTER(ctypes.c_float) * n_layers)(*[_p(a, ctypes.c_float) for a in keep])
+        return keep, ptrs
+
+    kp, pp = table(probes)
+    k1, p1 = table(page_vecs)
+    k2, p2 = table(chunk_vecs)
+    k3, p3 = table(grid_vecs)
+    ids = np.empty((batch, max_sel), np.int32)
+    nsel = np.zeros((batch,), np.int32)
+    cnt = np.zeros((batch, 3), np.int32)
+    g, p = geom._c(), plan._c()
+    rc = _load().oracle_select_shared(ctypes.c_int32(n_layers), pp, p1, p2, p3, _p(sl, ctypes.c_int32),
+                                      ctypes.c_int32(batch), ctypes.byref(g), ctypes.byref(p), ctypes.c_int32(max_sel),
+                                      _p(ids, ctypes.c_int32), _p(nsel, ctypes.c_int32), _p(cnt, ctypes.c_int32))
+    del kp, k1, k2, k3
+    if rc != 0:
+        raise ValueError("oracle_select_shared: a sequence needs more than max_sel page ids")
+    return (ids, nsel, cnt) if detail else (ids, nsel)
 
 
 def attend(q, k_pool, v_pool, block_table, seq_lens, geom: Geometry, page_ids=None, n_selected=None,

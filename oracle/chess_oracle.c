@@ -19,6 +19,11 @@
  *   oracle_select     Sec. 3.2 cascade text and Alg. 1 stage 2 (grid -> chunk
  *                     -> page, a child is ranked only if its parent was kept),
  *                     then the union with sink and recent-window pages
+ *   oracle_anchor     Sec. 3.2, Eq. 3 as an output of its own (the anchor of every sequence and KV head)
+ *   oracle_select_shared  the same cascade under the paper's own scope: Eq. 1 flattens the states of all
+ *                     layers and heads into one vector per unit, so one score per unit (Eq. 4 on the
+ *                     flattened vectors = the sum of the per-layer, per-head dots) and one page set per
+ *                     sequence, shared by every layer and head
  *   oracle_attend     softmax attention restricted to the listed pages: the
  *                     textbook definition, the paper's "Full-KV" when every
  *                     page is listed (Sec. 5.1 Baselines)
@@ -326,6 +331,119 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
         }
     }
     free(probe); free(cand); free(kg); free(kc); free(kp);
+    return rc;
+}
+
+/*
+ * Sec. 3.2, Eq. 3 for every (sequence, KV head): anchor [batch][H_kv][d] fp32, the mean of the page
+ * vectors of the last min(w, P) pages (zero for an empty sequence).
+ */
+void oracle_anchor(const float *page_vec, const int32_t *seq_lens, int32_t batch, const oracle_geom *g,
+                   int32_t window_pages, float *anchor)
+{
+    const int d = g->head_dim;
+    double *probe = (double *)malloc(sizeof(double) * d);
+    for (int b = 0; b < batch; ++b) {
+        const int64_t P = ceil_div(seq_lens[b], g->page_size);
+        for (int h = 0; h < g->n_kv_heads; ++h) {
+            const int64_t row = (int64_t)b * g->n_kv_heads + h;
+            if (P > 0) anchor_of(page_vec, g, row, P, window_pages, probe);
+            for (int i = 0; i < d; ++i) anchor[row * d + i] = P > 0 ? (float)probe[i] : 0.0f;
+        }
+    }
+    free(probe);
+}
+
+/*
+ * Eq. 4 on the flattened vectors of Eq. 1: the unit vector of the model is the concatenation, over layers
+ * l and KV heads h, of the per-(l, h) unit vectors, and the probe is flattened the same way, so
+ * S(u) = sum_l sum_h sum_i probe[l][b][h][i] * vec[l][b][h][u][i]   (one fp64 sum, in that order).
+ * vecs[l] has `stride` units per (sequence, head) row; probes[l] is fp32 [batch][H_kv][d].
+ */
+static double shared_score(int32_t n_layers, const float *const *probes, const float *const *vecs,
+                           const oracle_geom *g, int b, int64_t stride, int64_t u)
+{
+    const int d = g->head_dim;
+    double acc = 0.0;
+    for (int l = 0; l < n_layers; ++l)
+        for (int h = 0; h < g->n_kv_heads; ++h) {
+            const int64_t row = (int64_t)b * g->n_kv_heads + h;
+            const float *pr = probes[l] + row * d, *v = vecs[l] + (row * stride + u) * d;
+            for (int i = 0; i < d; ++i) acc += (double)pr[i] * (double)v[i];
+        }
+    return acc;
+}
+
+/*
+ * The cascade of Sec. 3.2 under the model-wide scope of Eq. 1: the three levels, their keep-counts, the
+ * rank order and the union with the safety pages are those of oracle_select; only the score differs
+ * (shared_score), and there is one list per sequence: page_ids [batch][max_sel], n_selected [batch],
+ * counts [batch][3] (may be NULL).  Returns 0, or -1 if a sequence would need more than max_sel ids.
+ */
+int oracle_select_shared(int32_t n_layers, const float *const *probes, const float *const *page_vec,
+                         const float *const *chunk_vec, const float *const *grid_vec, const int32_t *seq_lens,
+                         int32_t batch, const oracle_geom *g, const oracle_plan *pl, int32_t max_sel,
+                         int32_t *page_ids, int32_t *n_selected, int32_t *counts)
+{
+    const int B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
+    const int64_t cs = chunk_stride(g), gs = grid_stride(g);
+    const int64_t s = pl->sink_pages, w = pl->window_pages;
+    ranked *cand = (ranked *)malloc(sizeof(ranked) * (size_t)(g->max_pages + 1));
+    uint8_t *kg = (uint8_t *)malloc((size_t)gs + 1), *kc = (uint8_t *)malloc((size_t)cs + 1);
+    uint8_t *kp = (uint8_t *)malloc((size_t)g->max_pages + 1);
+    int rc = 0;
+
+    for (int b = 0; b < batch && rc == 0; ++b) {
+        const int64_t P = ceil_div(seq_lens[b], B), nc = ceil_div(P, Nc), ng = ceil_div(nc, Ng);
+        int32_t *ids = page_ids + (int64_t)b * max_sel;
+        for (int i = 0; i < max_sel; ++i) ids[i] = -1;
+        memset(kg, 0, (size_t)gs + 1); memset(kc, 0, (size_t)cs + 1); memset(kp, 0, (size_t)g->max_pages + 1);
+        int64_t k_g = 0, k_c = 0, k_p = 0, n = 0;
+
+        if (P <= s + w) {                           /* safety pages cover the sequence */
+            if (P > max_sel) { rc = -1; break; }
+            for (int64_t j = 0; j < P; ++j) ids[n++] = (int32_t)j;
+        } else {
+            const int64_t k = pl->budget_pages > 0 ? pl->budget_pages : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
+            const int64_t kc_target = ceil_div((int64_t)pl->over_chunk * k, Nc);
+
+            int64_t m = 0;                          /* level 1: every grid */
+            for (int64_t u = 0; u < ng; ++u) {
+                cand[m].score = shared_score(n_layers, probes, grid_vec, g, b, gs, u);
+                cand[m++].index = u;
+            }
+            if (pl->plan == ORACLE_PLAN_RATIO) k_g = clamp_i(ceil_bp(m, pl->rho_g_bp), 1, m);
+            else if (pl->plan == ORACLE_PLAN_FLAT) k_g = m;
+            else k_g = clamp_i(ceil_div((int64_t)pl->over_grid * kc_target, Ng), 0, m);
+            keep_top(cand, m, k_g, kg);
+
+            m = 0;                                  /* level 2: chunks of kept grids */
+            for (int64_t u = 0; u < nc; ++u) if (kg[u / Ng]) {
+                cand[m].score = shared_score(n_layers, probes, chunk_vec, g, b, cs, u);
+                cand[m++].index = u;
+            }
+            if (pl->plan == ORACLE_PLAN_RATIO) k_c = clamp_i(ceil_bp(m, pl->rho_c_bp), 1, m);
+            else if (pl->plan == ORACLE_PLAN_FLAT) k_c = m;
+            else k_c = clamp_i(kc_target, 0, m);
+            keep_top(cand, m, k_c, kc);
+
+            m = 0;                                  /* level 3: pages of kept chunks, safety pages excluded */
+            for (int64_t u = s; u < P - w; ++u) if (kc[u / Nc]) {
+                cand[m].score = shared_score(n_layers, probes, page_vec, g, b, g->max_pages, u);
+                cand[m++].index = u;
+            }
+            if (pl->plan == ORACLE_PLAN_RATIO) k_p = m == 0 ? 0 : clamp_i(ceil_bp(m, pl->rho_p_bp), 1, m);
+            else k_p = clamp_i(k, 0, m);
+            keep_top(cand, m, k_p, kp);
+
+            if (s + k_p + w > max_sel) { rc = -1; break; }
+            for (int64_t j = 0; j < P; ++j)
+                if (j < s || j >= P - w || kp[j]) ids[n++] = (int32_t)j;
+        }
+        n_selected[b] = (int32_t)n;
+        if (counts) { counts[b * 3] = (int32_t)k_g; counts[b * 3 + 1] = (int32_t)k_c; counts[b * 3 + 2] = (int32_t)k_p; }
+    }
+    free(cand); free(kg); free(kc); free(kp);
     return rc;
 }
 

@@ -460,6 +460,121 @@ def test_anchor_selection_ignores_the_query_and_the_scale_of_the_keys(ragged):
             assert idf[b, h, :nf[b, h]].tolist() == want
 
 
+# ------------------------------------------------------------------ Eq. 1 Flatten: one page set for all layers and heads
+@pytest.fixture(scope="module")
+def layers():
+    """Three 'layers' of the ragged workload: same lengths, independent keys and block tables."""
+    sp = workload.WorkloadSpec("ragged", 3, (64, 3000), 8, 2, 16, ("fixed", 128), (2, 2), 1, 2, budget_bp=300,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    out = []
+    for seed in (77, 78, 79):
+        wl = workload.generate(sp, seed, seq_lens=[3000, 1237, 641])
+        out.append(host_arrays(wl))
+    return sp, out
+
+
+def test_anchor_output_is_the_mean_of_the_window_page_means(layers):
+    """oracle.anchor against Eq. 3 written with numpy from the raw keys."""
+    sp, ls = layers
+    g = geom_of(sp)
+    K, V, Q, bt, sl = ls[0]
+    pv, _, _ = oracle.summarize(K, bt, sl, g)
+    B = sp.page_size
+    for w in (1, 3, 400):
+        a = oracle.anchor(pv, sl, g, w)
+        for b in range(sp.batch):
+            L = int(sl[b]); P = -(-L // B); W = min(w, P)
+            for h in range(sp.n_kv_heads):
+                Kl, _ = logical_kv(K, V, bt, L, b, h)
+                means = np.stack([Kl[j * B:min((j + 1) * B, L)].mean(0) for j in range(P - W, P)])
+                np.testing.assert_allclose(a[b, h], means.mean(0), rtol=3e-6, atol=3e-6)
+
+
+def test_shared_scope_scores_the_flattened_vectors(layers):
+    """Eq. 1 concatenates the per-layer, per-head page means into one vector per page, Eq. 3 averages those over
+    the window and Eq. 4 is their dot product.  Built here with numpy from the raw keys (one long vector per page),
+    stable argsort, first k: the flat plan of the shared scope must return exactly these pages."""
+    sp, ls = layers
+    g = geom_of(sp)
+    B, s, w, k = sp.page_size, sp.sink_pages, sp.window_pages, 9
+    summ = [oracle.summarize(K, bt, sl, g) for (K, V, Q, bt, sl) in ls]
+    sl = ls[0][4]
+    probes = [oracle.anchor(pv, sl, g, w) for (pv, cv, gv) in summ]
+    plan = plan_of(sp, plan=oracle.PLAN_FLAT, budget_pages=k)
+    ids, nsel = oracle.select_shared(probes, [x[0] for x in summ], [x[1] for x in summ], [x[2] for x in summ], sl, g,
+                                     plan, s + w + k)
+    for b in range(sp.batch):
+        L = int(sl[b]); P = -(-L // B)
+        flat = []
+        for (K, V, Q, bt, _) in ls:
+            for h in range(sp.n_kv_heads):
+                Kl, _ = logical_kv(K, V, bt, L, b, h)
+                flat.append(np.stack([Kl[j * B:min((j + 1) * B, L)].mean(0) for j in range(P)]))
+        flat = np.concatenate(flat, axis=1)                   # [P, layers * heads * d]
+        assert flat.shape == (P, 3 * sp.n_kv_heads * sp.head_dim)
+        score = flat @ flat[P - w:].mean(0)
+        cand = np.arange(s, P - w)
+        order = cand[np.argsort(-score[cand], kind="stable")]
+        gap = score[order[k - 1]] - score[order[k]]
+        assert gap > 1e-4, "seed gives a near-tie at the cut; pick another"
+        want = sorted(list(range(s)) + order[:k].tolist() + list(range(P - w, P)))
+        assert nsel[b] == s + k + w and ids[b, :nsel[b]].tolist() == want
+    # and it is not what any single layer would pick
+    one, _ = oracle.select_shared(probes[:1], [summ[0][0]], [summ[0][1]], [summ[0][2]], sl, g, plan, s + w + k)
+    assert not np.array_equal(one, ids)
+
+
+def test_shared_scope_of_one_layer_and_one_head_is_the_per_head_cascade():
+    """With a single layer and a single KV head the flattened vector is that head's vector: the shared cascade
+    (all three levels, budget and ratio plans) must return the per-head cascade's list."""
+    sp = workload.WorkloadSpec("onehead", 2, (64, 4000), 4, 1, 16, ("fixed", 128), (2, 2), 1, 3, budget_bp=200,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    wl = workload.generate(sp, 5, seq_lens=[4000, 1733])
+    K, V, Q, bt, sl = host_arrays(wl)
+    g = geom_of(sp)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    for kw in (dict(), dict(plan=oracle.PLAN_RATIO, rho_g_bp=5000, rho_c_bp=4000, rho_p_bp=3000)):
+        plan = plan_of(sp, probe=oracle.PROBE_ANCHOR, **kw)
+        ids, nsel, _, _, cnt = oracle.select(Q, pv, cv, gv, sl, g, plan, sp.max_pages, detail=True)
+        probe = oracle.anchor(pv, sl, g, plan.window_pages)
+        ids_s, nsel_s, cnt_s = oracle.select_shared([probe], [pv], [cv], [gv], sl, g, plan, sp.max_pages, detail=True)
+        assert np.array_equal(ids[:, 0], ids_s) and np.array_equal(nsel[:, 0], nsel_s)
+        assert np.array_equal(cnt[:, 0], cnt_s)
+        if kw:
+            assert (cnt_s[:, 0] < -(-(-(-sl // 16) // 4) // 4)).all(), "the grid level must actually prune"
+
+
+def test_shared_scope_is_linear_in_the_layers(layers):
+    """The score is a sum over layers: listing every layer twice doubles all scores (same pages), a layer whose
+    probe is zero changes nothing, and the order of the layers does not matter beyond rounding."""
+    sp, ls = layers
+    g = geom_of(sp)
+    summ = [oracle.summarize(K, bt, sl, g) for (K, V, Q, bt, sl) in ls]
+    sl = ls[0][4]
+    plan = plan_of(sp)
+    probes = [oracle.anchor(x[0], sl, g, plan.window_pages) for x in summ]
+    cols = lambda idx: ([probes[i] for i in idx], [summ[i][0] for i in idx], [summ[i][1] for i in idx], [summ[i][2] for i in idx])
+    base = oracle.select_shared(*cols([0, 1, 2]), sl, g, plan, sp.max_selected, detail=True)
+    twice = oracle.select_shared(*cols([0, 1, 2, 0, 1, 2]), sl, g, plan, sp.max_selected, detail=True)
+    swapped = oracle.select_shared(*cols([2, 0, 1]), sl, g, plan, sp.max_selected, detail=True)
+    for other in (twice, swapped):
+        assert all(np.array_equal(a, b) for a, b in zip(base, other))
+    pr, pg, ch, gr = cols([0, 1, 2])
+    muted = oracle.select_shared(pr[:2] + [np.zeros_like(pr[2])], pg, ch, gr, sl, g, plan, sp.max_selected, detail=True)
+    two = oracle.select_shared(*cols([0, 1]), sl, g, plan, sp.max_selected, detail=True)
+    assert all(np.array_equal(a, b) for a, b in zip(muted, two))
+    assert not np.array_equal(two[0], base[0])
+    # list invariants: safety pages present, ascending, counts as the plan's integer formulas say
+    ids, nsel, cnt = base
+    for b in range(sp.batch):
+        P = -(-int(sl[b]) // sp.page_size)
+        row = ids[b, :nsel[b]].tolist()
+        assert row == sorted(set(row)) and set(range(plan.sink_pages)) <= set(row)
+        assert set(range(P - plan.window_pages, P)) <= set(row) and (ids[b, nsel[b]:] == -1).all()
+        k = max(1, -(-P * plan.budget_bp // 10000))
+        assert nsel[b] == plan.sink_pages + plan.window_pages + min(k, cnt[b, 2]) and cnt[b, 2] <= k
+
+
 # ------------------------------------------------------------------ P12: degenerate hierarchy
 def test_one_token_pages_give_token_level_topk_attention():
     rng = np.random.default_rng(4)
