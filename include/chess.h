@@ -55,6 +55,8 @@ extern "C" {
 #define CHESS_PROBE_ANCHOR 1 /* Eq. 3: the mean of the page vectors of the recent window (the last          */
                              /* window_pages pages), keys only; q is then not read and may be NULL          */
 
+#define CHESS_MAX_LAYERS 64   /* most layers one chess_select_shared call can take */
+
 typedef struct chess_ctx chess_ctx; /* opaque; small host-side state only */
 
 typedef struct {
@@ -133,6 +135,34 @@ int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* bloc
 int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int32_t* seq_lens, int32_t batch,
                  const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, void* workspace,
                  void* stream);
+
+/*
+ * The query anchor of Sec. 3.2, Eq. 3 for every (sequence, KV head) of one layer: the mean of the page
+ * vectors of the last min(window_pages, P) pages (fp64 sum in page order, rounded to fp32 once; zero for an
+ * empty sequence).  anchor: device, fp32 [batch][H_kv][128], 16-byte aligned, written.  Asynchronous on `stream`.
+ * CHESS_EINVAL on null / misaligned pointers, batch outside [1, max_batch], window_pages < 1.
+ */
+int chess_anchor(chess_ctx* ctx, const void* summaries, const int32_t* seq_lens, int32_t batch, int32_t window_pages,
+                 float* anchor, void* stream);
+
+/*
+ * The selection under the paper's own scope (Sec. 3.1, Eq. 1 flattens the key means of all layers and heads
+ * into one vector per unit; Sec. 3.2, Eq. 3-4): a unit's score is the sum, over the n_layers layers and the H_kv
+ * heads, of probe[l][b][h] . unit vector[l][b][h] (fp64), and the cascade of chess_select runs once per
+ * sequence on those scores: one page list per sequence, for every layer and head of the model.
+ * probes, summaries: HOST arrays of n_layers DEVICE pointers (read during the call only): probes[l] fp32
+ * [batch][H_kv][128] (what chess_anchor writes for layer l, or any other probe), summaries[l] a summary buffer
+ * of this context's geometry; 16-byte aligned.  All layers share seq_lens.
+ * page_ids / n_selected: the layout chess_sparse_decode reads, [batch][H_kv][max_selected_pages] and
+ * [batch][H_kv]; the sequence's list is written for each of its KV heads, so the decode calls of every layer
+ * take them as they are.  plan->probe is ignored (the probes are given).
+ * CHESS_EINVAL as for chess_select, or n_layers outside [1, CHESS_MAX_LAYERS], or a null / misaligned table
+ * entry; CHESS_ENOTSUP as for chess_select, or batch above the number of compute units.
+ * Uses the workspace like chess_select (rows of the first KV head of each sequence).
+ */
+int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* const* summaries, int32_t n_layers,
+                        const int32_t* seq_lens, int32_t batch, const chess_select_plan* plan, int32_t* page_ids,
+                        int32_t* n_selected, void* workspace, void* stream);
 
 /*
  * Block-sparse decode attention over the listed pages, read in place (Sec. 4.3 takes a paged

@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
-           "chess_summarize", "chess_summarize_tail", "chess_select", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
+           "chess_summarize", "chess_summarize_tail", "chess_select", "chess_anchor", "chess_select_shared", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
            "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
@@ -94,6 +94,9 @@ def load_library() -> ctypes.CDLL:
         lib.chess_summarize_tail.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, vp, vp]
         lib.chess_workspace_init.argtypes = [vp, vp, vp]
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
+        lib.chess_anchor.argtypes = [vp, vp, i32p, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        lib.chess_select_shared.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32,
+                                            ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_dense_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_decode_step.argtypes = [vp, vp, vp, vp, i32p, i32p, vp, ctypes.c_int32, ctypes.c_int32, vp, i32p, i32p, vp, vp, vp]
@@ -186,6 +189,20 @@ class Chess:
         p = plan._c()
         self._check(self.lib.chess_select(self._h, _ptr(q), _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0],
                                           ctypes.byref(p), _ptr(page_ids), _ptr(n_selected), _ptr(workspace), _stream()))
+
+    def anchor(self, summaries, seq_lens, window_pages: int, anchor):
+        self._check(self.lib.chess_anchor(self._h, _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0], window_pages,
+                                          _ptr(anchor), _stream()))
+
+    def select_shared(self, probes, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected, workspace):
+        """probes / summaries: sequences of per-layer device tensors."""
+        n = len(probes)
+        assert len(summaries) == n
+        pt = (ctypes.c_void_p * n)(*[t.data_ptr() for t in probes])
+        st = (ctypes.c_void_p * n)(*[t.data_ptr() for t in summaries])
+        p = plan._c()
+        self._check(self.lib.chess_select_shared(self._h, pt, st, n, _ptr(seq_lens), seq_lens.shape[0], ctypes.byref(p),
+                                                 _ptr(page_ids), _ptr(n_selected), _ptr(workspace), _stream()))
 
     def sparse_decode(self, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, out, workspace):
         self._check(self.lib.chess_sparse_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),

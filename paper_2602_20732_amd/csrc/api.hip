@@ -170,6 +170,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->poll_limit = 0;
     c->occ_lds = -1;
     c->occ_blocks = 0;
+    c->shared_occ_lds = -1;
+    c->shared_occ_blocks = 0;
     c->step_occ_lds = -1;
     c->step_occ_blocks = 0;
     c->ws_zero_off = c->ws_keys_off;
@@ -318,6 +320,59 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
                                         reinterpret_cast<const float*>(sb + ctx->chunk_off),
                                         reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, (int)cluster,
                                         sp, ws, lds, page_ids, n_selected, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_anchor(chess_ctx* ctx, const void* summaries, const int32_t* seq_lens, int32_t batch, int32_t window_pages,
+                 float* anchor, void* stream)
+{
+    if (!ctx || !summaries || !seq_lens || !anchor) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch || window_pages < 1) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(anchor)) & 15) return CHESS_EINVAL;
+    const char* sb = static_cast<const char*>(summaries);
+    hipError_t e = chess::launch_anchor(ctx, reinterpret_cast<const float*>(sb + ctx->page_off), seq_lens, batch,
+                                        window_pages, anchor, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* const* summaries, int32_t n_layers,
+                        const int32_t* seq_lens, int32_t batch, const chess_select_plan* plan, int32_t* page_ids,
+                        int32_t* n_selected, void* workspace, void* stream)
+{
+    if (!ctx || !probes || !summaries || !seq_lens || !plan || !page_ids || !n_selected || !workspace) return CHESS_EINVAL;
+    if (n_layers < 1 || n_layers > CHESS_MAX_LAYERS) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return CHESS_EINVAL;
+    chess::SharedTable tab{};
+    for (int l = 0; l < n_layers; ++l) {
+        if (!probes[l] || !summaries[l]) return CHESS_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(probes[l]) | reinterpret_cast<uintptr_t>(summaries[l])) & 15) return CHESS_EINVAL;
+        tab.probes[l] = probes[l];
+        tab.summaries[l] = static_cast<const char*>(summaries[l]);
+    }
+    tab.page_off = ctx->page_off; tab.chunk_off = ctx->chunk_off; tab.grid_off = ctx->grid_off;
+    tab.n_layers = n_layers;
+    chess::SelectParams sp;
+    if (int rc = prepare_select(ctx, plan, &sp)) return rc;
+    const size_t lds = chess::select_lds_bytes(sp, ctx->geom.max_sel);
+    if (lds + 10240 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;  // the kernel's static LDS is below 10 KB
+    if (ctx->shared_occ_lds != (int)lds) {
+        int blocks = 0;
+        if (chess::select_shared_occupancy((int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        ctx->shared_occ_lds = (int)lds;
+        ctx->shared_occ_blocks = blocks;
+    }
+    // a unit's vector is n_layers * H_kv rows, so the more members the better, as long as all fit at once:
+    // one workgroup per compute unit keeps every member's loads at full speed
+    const int64_t capacity = (int64_t)std::min(ctx->shared_occ_blocks, 1) * ctx->n_cu;
+    if (capacity < batch) return CHESS_ENOTSUP;
+    int64_t cluster = capacity / batch;
+    if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, cluster);
+    cluster = clampi(cluster, 1, chess::kSharedMaxCluster);
+    sp.local_grids = 0;
+    const chess::SelectWs ws = select_ws(ctx, workspace);
+    hipError_t e = chess::launch_select_shared(ctx, tab, seq_lens, batch, (int)cluster, sp, ws, lds, page_ids, n_selected,
+                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

@@ -108,6 +108,7 @@ struct chess_ctx {
     int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
     int occ_lds, occ_blocks;                               // cached occupancy query of the select kernel
     int step_occ_lds, step_occ_blocks;                     // ... and of the fused step kernel
+    int shared_occ_lds, shared_occ_blocks;                 // ... and of the model-wide select kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
 };
 
@@ -153,6 +154,22 @@ hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int clus
 size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off);
 hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu);
 hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
+
+// The model-wide scope: per-layer probes (fp32 [batch][H_kv][128]) and summary buffers, passed by value.
+constexpr int kMaxLayers = CHESS_MAX_LAYERS;
+constexpr int kSharedMaxCluster = 128;
+struct SharedTable {
+    const float* probes[kMaxLayers];
+    const char* summaries[kMaxLayers];
+    size_t page_off, chunk_off, grid_off;            // bytes into a summary buffer
+    int n_layers;
+};
+hipError_t launch_anchor(chess_ctx* ctx, const float* pages, const int32_t* seq_lens, int batch, int window,
+                         float* anchor, hipStream_t stream);
+hipError_t select_shared_occupancy(int lds_bytes, int* blocks_per_cu);
+hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const int32_t* seq_lens, int batch, int cluster,
+                                const SelectParams& sp, const SelectWs& ws, size_t lds_bytes, int32_t* page_ids,
+                                int32_t* n_selected, hipStream_t stream);
 size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);

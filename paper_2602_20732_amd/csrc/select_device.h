@@ -889,9 +889,12 @@ __device__ __forceinline__ PubLayout pub_layout(uint64_t* row_words, const Geom&
 // units' keys in tail_words[0..2] (grid, chunk, page) for the cluster and in sh.tail_key for itself.  Wherever one
 // of these units is a candidate, its key is taken from there instead of the slot's own word (whatever was
 // scored for that slot from the old vector is ignored).
-template <bool kPhys, class TailFn>
-__device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, const float* __restrict__ chunks_row,
-                                        const float* __restrict__ grids_row, const double (&pr)[8], int P, const Geom& g,
+//
+// How a level's slots are scored is the Scorer's business: scorer(level, lo, hi, unit_of, local, keys, pub) leaves
+// the keys of the slots [lo, hi) in keys[] (local) or publishes them in pub[]; a member's share of a level is a
+// multiple of Scorer::kShareRound slots.
+template <bool kPhys, class Scorer, class TailFn>
+__device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const Geom& g,
                                         const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
                                         Shared& sh, CascadeResult* res, Prof& prof, const uint64_t* tail_words,
@@ -914,7 +917,6 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
     for (int level = 0; level < 3; ++level) {
         // level 0: every grid; level 1: chunks of kept grids; level 2: pages of kept chunks that are neither
         // sink nor window pages
-        const float* base = level == 0 ? grids_row : level == 1 ? chunks_row : pages_row;
         const int fan = level == 0 ? 1 : level == 1 ? g.n_g : g.n_c;
         const int u_lo = level == 2 ? s : 0;
         const int u_hi = level == 0 ? ng : level == 1 ? nc : P - w;
@@ -968,9 +970,9 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         // Otherwise this member takes its share of the level's slots: whole 16-slot rows.
         const bool local = C == 1 || (level == 0 && sp.local_grids != 0 && n_slots <= kSelGroups * kMaxFly);
         {
-            const int per = local ? n_slots : ceil_div_i(ceil_div_i(n_slots, C), 16) * 16;
+            const int per = local ? n_slots : ceil_div_i(ceil_div_i(n_slots, C), Scorer::kShareRound) * Scorer::kShareRound;
             const int lo = local ? 0 : min(n_slots, m * per), hi = min(n_slots, lo + per);
-            score_range(base, lo, hi, unit_of, pr, local, keys, pub);
+            scorer(level, lo, hi, unit_of, local, keys, pub);
             if (!local) { if (level == 0) res->n1 = n_slots; else if (level == 1) res->n2 = n_slots; else res->n3 = n_slots; }
         }
         // kPhys: the block-table entries of every slot's page are requested now, behind this member's vectors, and
@@ -1024,6 +1026,36 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
         else res->n_kp = n_kept;
     }
     return true;
+}
+
+// The scorer of one (sequence, KV head): a level's vectors are rows of one array, the probe is in registers.
+struct HeadScorer {
+    static constexpr int kShareRound = 16;           // whole rows of 16-lane groups
+    const float* pages_row;
+    const float* chunks_row;
+    const float* grids_row;
+    const double (&pr)[8];
+    template <class Map>
+    __device__ __forceinline__ void operator()(int level, int lo, int hi, Map unit_of, bool local, uint64_t* keys,
+                                               uint64_t* pub) const
+    {
+        const float* base = level == 0 ? grids_row : level == 1 ? chunks_row : pages_row;
+        score_range(base, lo, hi, unit_of, pr, local, keys, pub);
+    }
+};
+
+template <bool kPhys, class TailFn>
+__device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, const float* __restrict__ chunks_row,
+                                        const float* __restrict__ grids_row, const double (&pr)[8], int P, const Geom& g,
+                                        const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
+                                        uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
+                                        Shared& sh, CascadeResult* res, Prof& prof, const uint64_t* tail_words,
+                                        TailFn refresh_tail, const int32_t* __restrict__ bt_row = nullptr,
+                                        int32_t* phys_by_slot = nullptr, int32_t* sel_phys = nullptr)
+{
+    const HeadScorer scorer{pages_row, chunks_row, grids_row, pr};
+    return cascade_with<kPhys>(scorer, P, g, sp, pubs, m, C, want_l3, keys, kept_grids, kept_chunks, sel_pages, sh, res,
+                               prof, tail_words, refresh_tail, bt_row, phys_by_slot, sel_phys);
 }
 
 // Clear the published words of one (sequence, KV head) after everybody is done with them.
