@@ -137,13 +137,15 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
                  void* stream);
 
 /*
- * The query anchor of Sec. 3.2, Eq. 3 for every (sequence, KV head) of one layer: the mean of the page
- * vectors of the last min(window_pages, P) pages (fp64 sum in page order, rounded to fp32 once; zero for an
- * empty sequence).  anchor: device, fp32 [batch][H_kv][128], 16-byte aligned, written.  Asynchronous on `stream`.
- * CHESS_EINVAL on null / misaligned pointers, batch outside [1, max_batch], window_pages < 1.
+ * The query anchor of Sec. 3.2, Eq. 3 for every (sequence, KV head) of n_layers layers, one launch: the mean of
+ * the page vectors of the last min(window_pages, P) pages (fp64 sum in page order, rounded to fp32 once; zero
+ * for an empty sequence).  summaries, anchors: HOST arrays of n_layers DEVICE pointers (read during the call
+ * only); anchors[l]: fp32 [batch][H_kv][128], 16-byte aligned, written.  Asynchronous on `stream`.
+ * CHESS_EINVAL on null / misaligned pointers, n_layers outside [1, CHESS_MAX_LAYERS], batch outside
+ * [1, max_batch], window_pages < 1.
  */
-int chess_anchor(chess_ctx* ctx, const void* summaries, const int32_t* seq_lens, int32_t batch, int32_t window_pages,
-                 float* anchor, void* stream);
+int chess_anchor(chess_ctx* ctx, const void* const* summaries, int32_t n_layers, const int32_t* seq_lens, int32_t batch,
+                 int32_t window_pages, float* const* anchors, void* stream);
 
 /*
  * The selection under the paper's own scope (Sec. 3.1, Eq. 1 flattens the key means of all layers and heads

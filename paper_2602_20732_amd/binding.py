@@ -94,7 +94,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_summarize_tail.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, vp, vp]
         lib.chess_workspace_init.argtypes = [vp, vp, vp]
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
-        lib.chess_anchor.argtypes = [vp, vp, i32p, ctypes.c_int32, ctypes.c_int32, vp, vp]
+        lib.chess_anchor.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(vp), vp]
         lib.chess_select_shared.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32,
                                             ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
@@ -190,9 +190,15 @@ class Chess:
         self._check(self.lib.chess_select(self._h, _ptr(q), _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0],
                                           ctypes.byref(p), _ptr(page_ids), _ptr(n_selected), _ptr(workspace), _stream()))
 
-    def anchor(self, summaries, seq_lens, window_pages: int, anchor):
-        self._check(self.lib.chess_anchor(self._h, _ptr(summaries), _ptr(seq_lens), seq_lens.shape[0], window_pages,
-                                          _ptr(anchor), _stream()))
+    def anchor(self, summaries, seq_lens, window_pages: int, anchors):
+        """summaries / anchors: one device tensor each, or sequences of per-layer tensors (one launch)."""
+        if isinstance(summaries, torch.Tensor):
+            summaries, anchors = [summaries], [anchors]
+        n = len(summaries)
+        assert len(anchors) == n
+        st = (ctypes.c_void_p * n)(*[t.data_ptr() for t in summaries])
+        at = (ctypes.c_void_p * n)(*[t.data_ptr() for t in anchors])
+        self._check(self.lib.chess_anchor(self._h, st, n, _ptr(seq_lens), seq_lens.shape[0], window_pages, at, _stream()))
 
     def select_shared(self, probes, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected, workspace):
         """probes / summaries: sequences of per-layer device tensors."""

@@ -323,15 +323,21 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
-int chess_anchor(chess_ctx* ctx, const void* summaries, const int32_t* seq_lens, int32_t batch, int32_t window_pages,
-                 float* anchor, void* stream)
+int chess_anchor(chess_ctx* ctx, const void* const* summaries, int32_t n_layers, const int32_t* seq_lens, int32_t batch,
+                 int32_t window_pages, float* const* anchors, void* stream)
 {
-    if (!ctx || !summaries || !seq_lens || !anchor) return CHESS_EINVAL;
+    if (!ctx || !summaries || !seq_lens || !anchors) return CHESS_EINVAL;
+    if (n_layers < 1 || n_layers > CHESS_MAX_LAYERS) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch || window_pages < 1) return CHESS_EINVAL;
-    if ((reinterpret_cast<uintptr_t>(summaries) | reinterpret_cast<uintptr_t>(anchor)) & 15) return CHESS_EINVAL;
-    const char* sb = static_cast<const char*>(summaries);
-    hipError_t e = chess::launch_anchor(ctx, reinterpret_cast<const float*>(sb + ctx->page_off), seq_lens, batch,
-                                        window_pages, anchor, static_cast<hipStream_t>(stream));
+    chess::AnchorTable tab{};
+    for (int l = 0; l < n_layers; ++l) {
+        if (!summaries[l] || !anchors[l]) return CHESS_EINVAL;
+        if ((reinterpret_cast<uintptr_t>(summaries[l]) | reinterpret_cast<uintptr_t>(anchors[l])) & 15) return CHESS_EINVAL;
+        tab.summaries[l] = static_cast<const char*>(summaries[l]);
+        tab.anchors[l] = anchors[l];
+    }
+    tab.page_off = ctx->page_off;
+    hipError_t e = chess::launch_anchor(ctx, tab, n_layers, seq_lens, batch, window_pages, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

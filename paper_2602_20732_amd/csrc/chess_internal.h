@@ -164,8 +164,13 @@ struct SharedTable {
     size_t page_off, chunk_off, grid_off;            // bytes into a summary buffer
     int n_layers;
 };
-hipError_t launch_anchor(chess_ctx* ctx, const float* pages, const int32_t* seq_lens, int batch, int window,
-                         float* anchor, hipStream_t stream);
+struct AnchorTable {
+    const char* summaries[kMaxLayers];
+    float* anchors[kMaxLayers];
+    size_t page_off;
+};
+hipError_t launch_anchor(chess_ctx* ctx, const AnchorTable& tab, int n_layers, const int32_t* seq_lens, int batch,
+                         int window, hipStream_t stream);
 hipError_t select_shared_occupancy(int lds_bytes, int* blocks_per_cu);
 hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const int32_t* seq_lens, int batch, int cluster,
                                 const SelectParams& sp, const SelectWs& ws, size_t lds_bytes, int32_t* page_ids,

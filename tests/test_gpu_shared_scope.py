@@ -32,10 +32,9 @@ def run_both(sp, wls, plan, cluster=0, window=None, max_sel=None):
     for d in ds:
         s = lib.new_summaries()
         lib.summarize(d.k_pool, d.block_table, d.seq_lens, s)
-        a = torch.full((batch, sp.n_kv_heads, 128), float("nan"), device="cuda")
-        lib.anchor(s, d.seq_lens, window, a)
         summs.append(s)
-        probes.append(a)
+        probes.append(torch.full((batch, sp.n_kv_heads, 128), float("nan"), device="cuda"))
+    lib.anchor(summs, ds[0].seq_lens, window, probes)                  # all layers in one launch
     ws = lib.new_workspace()
     ids = torch.full((batch, sp.n_kv_heads, max_sel), -7, dtype=torch.int32, device="cuda")
     nsel = torch.full((batch, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
@@ -131,4 +130,45 @@ def test_shared_scope_refusals():
         lib.select_shared([a] * 65, [s] * 65, wl.seq_lens, gpu_plan(plan_of(sp)), ids, nsel, ws)   # too many layers
     with pytest.raises(pk.ChessError):
         lib.select_shared([a[:, :, 1:]], [s], wl.seq_lens, gpu_plan(plan_of(sp)), ids, nsel, ws)   # misaligned probe
+    lib.close()
+
+
+@pytest.mark.parametrize("batch,lo,hi,n_layers,sample", [(32, 16384, 32768, 32, (0, 21)), (8, 131072, 131072, 8, (5,))])
+def test_shared_scope_at_benchmark_shapes(batch, lo, hi, n_layers, sample):
+    """The launch shapes of the benchmark (32 KV-head rows x layers per unit, automatic cluster) on summary buffers
+    filled with seeded normal vectors (the selection reads nothing else); whole sampled sequences against the oracle."""
+    sp = workload.WorkloadSpec("shape", batch, (lo, hi), 32, 8, 16, ("fixed", 128), (3, 3), 1, 4, budget_bp=100)
+    g = geom_of(sp)
+    plan = plan_of(sp)
+    lib = pk.Chess(config_of(sp))
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    lens = torch.randint(lo, hi + 1, (batch,), generator=torch.Generator().manual_seed(7)).to(torch.int32)
+    sl = lens.cuda()
+    summs, probes = [], []
+    for _ in range(n_layers):
+        s = lib.new_summaries()
+        s.view(torch.float32).normal_(generator=gen)
+        summs.append(s)
+        probes.append(torch.empty((batch, sp.n_kv_heads, 128), device="cuda"))
+    lib.anchor(summs, sl, plan.window_pages, probes)
+    ws = lib.new_workspace()
+    ids = torch.full((batch, sp.n_kv_heads, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((batch, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    lib.select_shared(probes, summs, sl, gpu_plan(plan), ids, nsel, ws)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    ids_h, nsel_h = ids.cpu().numpy(), nsel.cpu().numpy()
+    assert (ids_h == ids_h[:, :1]).all() and (nsel_h == nsel_h[:, :1]).all()
+    for b in sample:
+        pv, cv, gv = [], [], []
+        for s in summs:
+            p, c, gr = lib.summary_views(s)
+            pv.append(p[b:b + 1].cpu().numpy()); cv.append(c[b:b + 1].cpu().numpy()); gv.append(gr[b:b + 1].cpu().numpy())
+        one = lens[b:b + 1].numpy()
+        oanc = [oracle.anchor(p, one, g, plan.window_pages) for p in pv]
+        for a, o in zip(probes, oanc):
+            assert np.array_equal(a[b:b + 1].cpu().numpy().view(np.uint32), o.view(np.uint32))
+        oids, on = oracle.select_shared(oanc, pv, cv, gv, one, g, plan, sp.max_selected)
+        assert nsel_h[b, 0] == on[0] and np.array_equal(ids_h[b, 0], oids[0]), (b, "page list")
+        print(f"[shared {batch}x{n_layers}] seq {b} ({int(lens[b])} tokens): page list exact, {on[0]} pages")
     lib.close()
