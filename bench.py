@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="launch step by step instead of replaying a HIP graph")
     ap.add_argument("--no-cpu", action="store_true", help="skip the oracle timing")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense full-KV comparison")
+    ap.add_argument("--shared-layers", type=int, default=32,
+                    help="layers of the model-wide selection timed beside the step (0 = skip)")
     ap.add_argument("--cluster", type=int, default=0,
                     help="tuning aid: force the workgroups per (sequence, KV head) of select / decode_step (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -59,6 +61,52 @@ def algorithmic_bytes(sp, seq_lens, nsel, counts):
     attn = int(nsel.sum()) * B * d * 2 * 2
     summ = len(seq_lens) * sp.n_kv_heads * (B * d * 2 + (Nc + Ng + 3) * d * 4)
     return {"select": sel, "attention": attn, "summarize": summ, "step": sel + attn + summ}
+
+
+def shared_scope(lib, sp, seq_lens, lens, plan, n_layers, timed):
+    """The paper's own scope (Sec. 3.1 Eq. 1, Sec. 3.2 Eq. 3): anchors of n_layers layers + one selection per sequence
+    for the whole model, on this workload's lengths.  The summary buffers hold seeded normal vectors (the
+    selection reads nothing else; n_layers KV pools of this size would not add information)."""
+    import torch
+    gen = torch.Generator(device="cuda").manual_seed(20732)
+    summs, probes = [], []
+    for _ in range(n_layers):
+        s = lib.new_summaries()
+        s.view(torch.float32).normal_(generator=gen)
+        summs.append(s)
+        probes.append(torch.empty((sp.batch, sp.n_kv_heads, sp.head_dim), device="cuda"))
+    ws = lib.new_workspace()
+    ids = torch.empty((sp.batch, sp.n_kv_heads, sp.max_selected), dtype=torch.int32, device="cuda")
+    nsel = torch.empty((sp.batch, sp.n_kv_heads), dtype=torch.int32, device="cuda")
+
+    torch.cuda.synchronize()        # the fills ran on another stream; a cluster needs the device to itself
+
+    def both(i):
+        lib.anchor(summs, seq_lens, plan.window_pages, probes)
+        lib.select_shared(probes, summs, seq_lens, plan, ids, nsel, ws)
+
+    def anchors(i):
+        lib.anchor(summs, seq_lens, plan.window_pages, probes)
+
+    ms, _ = timed(both, 8, 2, True)
+    ms_a, _ = timed(anchors, 8, 2, True)
+    if lib.workspace_error(ws) != 0:
+        raise RuntimeError("the model-wide selection gave up a bounded wait")
+    d, B, Nc, Ng = sp.head_dim, sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    units = 0
+    for L in lens:
+        P = -(-L // B); nc = -(-P // Nc); ng = -(-nc // Ng)
+        k = sp.budget_for(P)
+        kct = -(-plan.over_chunk * k // Nc)
+        kg = min(ng, -(-plan.over_grid * kct // Ng))
+        kc = min(kct, kg * Ng, nc)
+        units += (ng if kg < ng else 0) + (kg * Ng if kc < min(kg * Ng, nc) else 0) + kc * Nc + plan.window_pages
+    byts = units * n_layers * sp.n_kv_heads * d * 4
+    sel_ms = ms - ms_a
+    return {"layers": n_layers, "us_per_selection": round(ms * 1e3, 1), "anchors_us": round(ms_a * 1e3, 1),
+            "us_per_layer": round(ms * 1e3 / n_layers, 2), "algorithmic_bytes": byts,
+            "gbs": round(byts / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "data": "seeded normal summary vectors", "selection_alone_us": round(sel_ms * 1e3, 1)}
 
 
 def measured_traffic(workload_name):
@@ -296,6 +344,8 @@ def main():
     result["summarize_full_pass"] = {"us": round(ms_full * 1e3, 1), "bytes": full_bytes,
                                      "gbs": round(full_bytes / (ms_full * 1e-3) / 1e9, 1),
                                      "frac_of_hbm_peak": round(full_bytes / (ms_full * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    if args.shared_layers > 0:
+        result["shared_scope"] = shared_scope(lib, sp, pools[0][0].seq_lens, lens, plan, args.shared_layers, timed)
     if args.workload == "cfg3":
         result["stack_of_32_layers_us"] = round(ms_step * 1e3 * 32, 1)
 
