@@ -116,6 +116,18 @@ int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream);
 int chess_summarize(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
                     int32_t batch, const int32_t* from_page, void* summaries, void* stream);
 
+/*
+ * The append of a decode step (the paper's decode loop grows the paged cache by one token per step, Sec. 4.3;
+ * the layouts are this library's): writes the new token's key and value rows, bf16 [batch][H_kv][128], at
+ * position seq_lens[b] of sequence b -- K row-major in its page, V token-minor -- through the block table, which
+ * must already map that page.  seq_lens holds the lengths BEFORE the append and is not changed (the caller adds
+ * one); a sequence with no room left (seq_lens[b] >= max_pages_per_seq * page_size) or a negative length is
+ * skipped.  The only call that writes the pools.  Follow it with chess_summarize_tail (or chess_decode_step
+ * with refresh_tail) on the new lengths to bring the summaries up to date.
+ */
+int chess_append_kv(chess_ctx* ctx, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, void* stream);
+
 /* The per-decode-step refresh: chess_summarize with from_page[b] = (pages of sequence b) - 1,
  * i.e. the tail page and its chunk and grid, launched on batch * H workgroups only. */
 int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,

@@ -323,6 +323,17 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
+int chess_append_kv(chess_ctx* ctx, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, void* stream)
+{
+    if (!ctx || !k_new || !v_new || !k_pool || !v_pool || !block_table || !seq_lens) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    hipError_t e = chess::launch_append(ctx, static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                                        static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool), block_table,
+                                        seq_lens, batch, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
 int chess_anchor(chess_ctx* ctx, const void* const* summaries, int32_t n_layers, const int32_t* seq_lens, int32_t batch,
                  int32_t window_pages, float* const* anchors, void* stream)
 {

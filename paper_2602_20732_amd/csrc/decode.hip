@@ -83,6 +83,30 @@ hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu)
                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1, true>, 64, 0);
 }
 
+// One new token per sequence into the paged pools: K row-major [phys][H][B][128], V token-minor [phys][H][128][B].
+// grid = batch * H_kv workgroups of 128 threads, thread = dim.
+__global__ __launch_bounds__(kHeadDim) void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+                                                          uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool,
+                                                          const int32_t* __restrict__ block_table,
+                                                          const int32_t* __restrict__ seq_lens, Geom g)
+{
+    const int row = blockIdx.x, b = row / g.n_kv_heads, h = row - b * g.n_kv_heads, dim = threadIdx.x;
+    const int L = seq_lens[b], B = g.page_size;
+    if (L < 0 || L >= g.max_pages * B) return;        // no room: the sequence is left as it is
+    const int64_t phys = block_table[(size_t)b * g.max_pages + L / B];
+    const int t = L % B;
+    const size_t blk = ((size_t)phys * g.n_kv_heads + h) * B * kHeadDim;
+    k_pool[blk + (size_t)t * kHeadDim + dim] = k_new[(size_t)row * kHeadDim + dim];
+    v_pool[blk + (size_t)dim * B + t] = v_new[(size_t)row * kHeadDim + dim];
+}
+
+hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
+                         const int32_t* block_table, const int32_t* seq_lens, int batch, hipStream_t stream)
+{
+    return launch(append_kernel, dim3(batch * ctx->geom.n_kv_heads), dim3(kHeadDim), 0, stream, k_new, v_new, k_pool, v_pool,
+                  block_table, seq_lens, ctx->geom);
+}
+
 __global__ void zero_kernel(int32_t* p, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
