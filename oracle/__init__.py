@@ -238,3 +238,23 @@ def attend(q, k_pool, v_pool, block_table, seq_lens, geom: Geometry, page_ids=No
                           _p(out, ctypes.c_float), _p(wts, ctypes.c_double),
                           ctypes.c_int32(0 if weights_head is None else weights_head))
     return out if weights_head is None else (out, wts)
+
+
+def entropy(logits_bits, vocab=None):
+    """Sec. 3.3: entropy (nats) of softmax(logits) per row; logits as bf16 bit patterns [batch, stride]."""
+    z = _u16(logits_bits)
+    batch, stride = z.shape
+    vocab = stride if vocab is None else vocab
+    out = np.zeros((batch,), np.float64)
+    _load().oracle_entropy(_p(z, ctypes.c_uint16), ctypes.c_int32(batch), ctypes.c_int32(vocab), ctypes.c_int64(stride),
+                           _p(out, ctypes.c_double))
+    return out
+
+
+def page_trigger(H, tau_h: float, tau_v: float):
+    """Sec. 3.3 over the steps of one generated page: (mean entropy, variance of the entropy, fire)."""
+    h = np.ascontiguousarray(H, dtype=np.float32)
+    mean, var, fire = ctypes.c_double(), ctypes.c_double(), ctypes.c_int32()
+    _load().oracle_page_trigger(_p(h, ctypes.c_float), ctypes.c_int32(h.shape[0]), ctypes.c_double(tau_h), ctypes.c_double(tau_v),
+                                ctypes.byref(mean), ctypes.byref(var), ctypes.byref(fire))
+    return mean.value, var.value, bool(fire.value)

@@ -24,6 +24,9 @@
  *                     layers and heads into one vector per unit, so one score per unit (Eq. 4 on the
  *                     flattened vectors = the sum of the per-layer, per-head dots) and one page set per
  *                     sequence, shared by every layer and head
+ *   oracle_entropy    Sec. 3.3: the entropy of a step's output distribution (softmax of the logits)
+ *   oracle_page_trigger  Sec. 3.3: average entropy and variance of the entropy over the steps of one
+ *                     generated page, and the decision to reselect when either exceeds its threshold
  *   oracle_attend     softmax attention restricted to the listed pages: the
  *                     textbook definition, the paper's "Full-KV" when every
  *                     page is listed (Sec. 5.1 Baselines)
@@ -40,6 +43,10 @@
  *     ascending; an inactive unit is never ranked (no zero fill);
  *   - sink and window pages are not candidates at page level, the budget is
  *     on top of them.
+ *   - Sec. 3.3 names its two metrics "average Entropy" H_p and "Varentropy" Var(H)_p of a page p and says the
+ *     second captures temporal instability: read here as the mean and the population variance, over the
+ *     steps that generated page p, of the per-step entropy; reselection fires when either is above its
+ *     threshold (the thresholds are inputs: the paper calibrates them on data this build does not have);
  * Parity unpinned (our reading only, the paper cannot arbitrate): N_c / N_g
  * defaults, ceil vs interpolated quantile count, group-sum probe, exclusion
  * of safety pages from the candidates, partial-unit means, the oversampling
@@ -504,4 +511,39 @@ void oracle_attend(const uint16_t *q, const uint16_t *k_pool, const uint16_t *v_
         }
     }
     free(z); free(acc);
+}
+
+/*
+ * Sec. 3.3: entropy (nats) of the output distribution of one decode step, per sequence:
+ * p = softmax(logits), H = -sum_v p_v log p_v, with the terms of p_v = 0 taken as 0.
+ * logits bf16 [batch][row_stride], the first `vocab` of each row used.
+ */
+void oracle_entropy(const uint16_t *logits, int32_t batch, int32_t vocab, int64_t row_stride, double *H)
+{
+    for (int b = 0; b < batch; ++b) {
+        const uint16_t *z = logits + (int64_t)b * row_stride;
+        double m = -INFINITY, Z = 0.0, acc = 0.0;
+        for (int v = 0; v < vocab; ++v) { const double x = bf16_value(z[v]); if (x > m) m = x; }
+        for (int v = 0; v < vocab; ++v) Z += exp(bf16_value(z[v]) - m);
+        for (int v = 0; v < vocab; ++v) {
+            const double p = exp(bf16_value(z[v]) - m) / Z;
+            if (p > 0.0) acc -= p * log(p);
+        }
+        H[b] = acc;
+    }
+}
+
+/*
+ * Sec. 3.3 over one generated page: H[0..n) are the entropies of its steps (fp32, as the step stores them).
+ * mean = (1/n) sum H, var = (1/n) sum (H - mean)^2 (both fp64, index order); fire = mean > tau_h || var > tau_v.
+ */
+void oracle_page_trigger(const float *H, int32_t n, double tau_h, double tau_v, double *mean, double *var, int32_t *fire)
+{
+    double s = 0.0, q = 0.0;
+    for (int i = 0; i < n; ++i) s += (double)H[i];
+    const double mu = s / (double)n;
+    for (int i = 0; i < n; ++i) { const double d = (double)H[i] - mu; q += d * d; }
+    *mean = mu;
+    *var = q / (double)n;
+    *fire = (*mean > tau_h || *var > tau_v) ? 1 : 0;
 }

@@ -575,6 +575,53 @@ def test_shared_scope_is_linear_in_the_layers(layers):
         assert nsel[b] == plan.sink_pages + plan.window_pages + min(k, cnt[b, 2]) and cnt[b, 2] <= k
 
 
+# ------------------------------------------------------------------ Sec. 3.3: entropy / variance of the entropy per page
+def test_entropy_closed_forms_and_library_routine():
+    """Uniform logits: log V.  One logit far above the rest: ~0.  Two levels: the closed form
+    H = log Z - (a e^a n_a + b e^b n_b) / Z.  Random rows: scipy's entropy of scipy's softmax.  Adding a constant to a
+    row changes nothing; 0 <= H <= log V."""
+    from scipy.special import softmax
+    from scipy.stats import entropy as sp_entropy
+    V = 1000
+    rows = np.zeros((5, V), np.float32)
+    rows[1, 7] = 100.0
+    rows[2, :250] = 2.0                                   # two levels: 250 logits at 2, 750 at 0
+    rng = np.random.default_rng(0)
+    rows[3] = rng.standard_normal(V) * 3
+    rows[4] = -rows[3]
+    bits = f32_to_bf16_bits(rows)
+    H = oracle.entropy(bits)
+    z = bf16_to_f64(bits)
+    assert abs(H[0] - np.log(V)) < 1e-12
+    assert 0 <= H[1] < 1e-38
+    Z = 250 * np.exp(2.0) + 750
+    assert abs(H[2] - (np.log(Z) - 2.0 * 250 * np.exp(2.0) / Z)) < 1e-12
+    for r in (3, 4):
+        assert abs(H[r] - sp_entropy(softmax(z[r]))) < 1e-10
+    half = np.round(rng.uniform(-4, 4, V) * 2) / 2          # half-integers: they and their shift by 8 are exact in bf16
+    pair = f32_to_bf16_bits(np.stack([half, half + 8.0]).astype(np.float32))
+    assert np.array_equal(bf16_to_f64(pair[1]) - 8.0, bf16_to_f64(pair[0]))
+    Hs = oracle.entropy(pair)
+    assert abs(Hs[0] - Hs[1]) < 1e-12, "softmax is shift invariant"
+    assert (H >= 0).all() and (H <= np.log(V) + 1e-12).all()
+    # only the first `vocab` entries of a row count
+    wide = np.concatenate([bits[3:4], f32_to_bf16_bits(np.full((1, 24), 50.0, np.float32))], axis=1)
+    assert abs(oracle.entropy(wide, vocab=V)[0] - H[3]) == 0
+
+
+def test_page_trigger_is_mean_and_population_variance_with_an_or_rule():
+    rng = np.random.default_rng(1)
+    H = rng.uniform(0.5, 3.0, 16).astype(np.float32)
+    mean, var, fire = oracle.page_trigger(H, 10.0, 10.0)
+    assert abs(mean - H.astype(np.float64).mean()) < 1e-12 and abs(var - H.astype(np.float64).var()) < 1e-12 and not fire
+    assert oracle.page_trigger(H, mean - 1e-6, 10.0)[2] and oracle.page_trigger(H, 10.0, var - 1e-6)[2]
+    assert not oracle.page_trigger(H, mean + 1e-6, var + 1e-6)[2]
+    const = np.full(16, 2.5, np.float32)
+    assert oracle.page_trigger(const, 2.4, 0.0)[:2] == (2.5, 0.0)
+    assert not oracle.page_trigger(const, 2.5, 0.0)[2], "strictly above, not at, the threshold"
+    assert oracle.page_trigger(np.array([1.0, 3.0], np.float32), 5.0, 0.5)[:2] == (2.0, 1.0)
+
+
 # ------------------------------------------------------------------ P12: degenerate hierarchy
 def test_one_token_pages_give_token_level_topk_attention():
     rng = np.random.default_rng(4)
