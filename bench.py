@@ -109,6 +109,27 @@ def shared_scope(lib, sp, seq_lens, lens, plan, n_layers, timed):
             "data": "seeded normal summary vectors", "selection_alone_us": round(sel_ms * 1e3, 1)}
 
 
+def trigger_monitor(lib, sp, timed, vocab=151936):
+    """Sec. 3.3 monitor per decode step: entropy of the batch's logits rows (bf16, a 152K vocabulary) + page statistics."""
+    import torch
+    logits = [torch.randn((sp.batch, vocab), device="cuda").mul_(3).to(torch.bfloat16) for _ in range(4)]
+    H = torch.empty((sp.batch,), device="cuda")
+    ws = lib.new_workspace()
+    hist = torch.zeros((sp.batch, sp.page_size), device="cuda")
+    count = torch.zeros((sp.batch,), dtype=torch.int32, device="cuda")
+    fire = torch.zeros((sp.batch,), dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+
+    def monitor(i):
+        lib.entropy(logits[i % 4], H, ws)
+        lib.trigger_update(H, sp.page_size, 1e9, 1e9, hist, count, fire)
+
+    ms, _ = timed(monitor, 64, 4, True)
+    byts = sp.batch * vocab * 2
+    return {"us_per_step": round(ms * 1e3, 2), "logit_bytes": byts, "gbs": round(byts / (ms * 1e-3) / 1e9, 1),
+            "vocab": vocab, "kernel_launches_per_step": 2}
+
+
 def measured_traffic(workload_name):
     """HBM bytes per launch of the step kernel from the committed rocprofv3 counter summary, or None."""
     path = os.path.join(ROOT, "profiles", "step_kernel_hbm_traffic.txt")
@@ -346,6 +367,7 @@ def main():
                                      "frac_of_hbm_peak": round(full_bytes / (ms_full * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if args.shared_layers > 0:
         result["shared_scope"] = shared_scope(lib, sp, pools[0][0].seq_lens, lens, plan, args.shared_layers, timed)
+    result["trigger"] = trigger_monitor(lib, sp, timed)
     if args.workload == "cfg3":
         result["stack_of_32_layers_us"] = round(ms_step * 1e3 * 32, 1)
 

@@ -179,6 +179,30 @@ int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* 
                         int32_t* n_selected, void* workspace, void* stream);
 
 /*
+ * The quality monitor of Sec. 3.3, first half: the entropy (nats) of the output distribution of one decode step,
+ * H[b] = -sum_v p_v log p_v with p = softmax(logits[b]).  logits: device, bf16 [batch][row_stride], the first
+ * `vocab` entries of a row are used (-inf entries count as probability 0); 16-byte aligned, row_stride a multiple
+ * of 8.  entropy: device fp32 [batch], written.  fp32 arithmetic (absolute error around 1e-5).  Uses the workspace.
+ * CHESS_EINVAL on null / misaligned pointers, batch outside [1, max_batch], vocab < 1, row_stride < vocab or not
+ * a multiple of 8.
+ */
+int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
+                  void* workspace, void* stream);
+
+/*
+ * Sec. 3.3, second half: one call per decode step.  Appends entropy[b] to the history of the page sequence b is
+ * generating; when that makes page_steps entries, takes their mean and population variance (fp64, in step order),
+ * sets fire[b] = (mean > tau_entropy || variance > tau_variance), writes stats[b] = {mean, variance} (if stats is
+ * not NULL) and starts a new page; otherwise fire[b] = 0.  The thresholds are inputs (the paper takes the 99th
+ * percentiles of a calibration run).  history: device fp32 [batch][page_steps]; count: device int32 [batch], zero
+ * before a sequence's first step; fire: device int32 [batch]; stats: device fp64 [batch][2] or NULL.  A caller
+ * reselects (chess_select / chess_decode_step) for the sequences whose flag is set and reuses the page list for
+ * the others.  CHESS_EINVAL on null pointers, batch outside [1, max_batch], page_steps < 1.
+ */
+int chess_trigger_update(chess_ctx* ctx, const float* entropy, int32_t batch, int32_t page_steps, double tau_entropy,
+                         double tau_variance, float* history, int32_t* count, int32_t* fire, double* stats, void* stream);
+
+/*
  * Block-sparse decode attention over the listed pages, read in place (Sec. 4.3 takes a paged
  * decode kernel over page indices; App. B).  Per q head: softmax(sm_scale * q . K_t) weighted sum
  * of V_t over the valid tokens of the listed pages.  bf16 inputs, fp32 accumulation, fp32 out.

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libchess.so")
-SOURCES = ["api.hip", "summarize.hip", "select.hip", "decode.hip", "step.hip", "shared.hip"]
+SOURCES = ["api.hip", "summarize.hip", "select.hip", "decode.hip", "step.hip", "shared.hip", "trigger.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument"]
 

@@ -161,7 +161,9 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
     c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
     c->ws_prof_off = align_up(c->ws_err_off + 256, 256);            // profiling builds only: 48 words per row
-    c->workspace_bytes = align_up(c->ws_prof_off + rows * 48 * sizeof(int32_t), 256);
+    c->ws_ent_off = align_up(c->ws_prof_off + rows * 48 * sizeof(int32_t), 256);
+    c->ws_entcnt_off = align_up(c->ws_ent_off + (size_t)cfg->max_batch * chess::kEntMaxSplits * 4 * sizeof(float), 256);
+    c->workspace_bytes = align_up(c->ws_entcnt_off + (size_t)cfg->max_batch * sizeof(int32_t), 256);
     c->dec_blocks4 = c->dec_blocks1 = 2;
     if (chess::decode_occupancy(g.page_size, 4, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
     if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
@@ -320,6 +322,32 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
                                         reinterpret_cast<const float*>(sb + ctx->chunk_off),
                                         reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, (int)cluster,
                                         sp, ws, lds, page_ids, n_selected, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
+                  void* workspace, void* stream)
+{
+    if (!ctx || !logits || !entropy || !workspace) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch || vocab < 1 || row_stride < vocab || (row_stride & 7)) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(logits) | reinterpret_cast<uintptr_t>(workspace)) & 15) return CHESS_EINVAL;
+    // enough workgroups to fill the device, each with at least 4096 logits
+    const int64_t by_size = std::max<int64_t>(1, vocab / 4096);
+    const int splits = (int)clampi(std::min<int64_t>(by_size, cdiv(2 * ctx->n_cu, batch)), 1, chess::kEntMaxSplits);
+    char* wb = static_cast<char*>(workspace);
+    hipError_t e = chess::launch_entropy(ctx, static_cast<const uint16_t*>(logits), batch, vocab, row_stride, splits, entropy,
+                                         reinterpret_cast<float*>(wb + ctx->ws_ent_off),
+                                         reinterpret_cast<int32_t*>(wb + ctx->ws_entcnt_off), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_trigger_update(chess_ctx* ctx, const float* entropy, int32_t batch, int32_t page_steps, double tau_entropy,
+                         double tau_variance, float* history, int32_t* count, int32_t* fire, double* stats, void* stream)
+{
+    if (!ctx || !entropy || !history || !count || !fire) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch || page_steps < 1) return CHESS_EINVAL;
+    hipError_t e = chess::launch_trigger(entropy, batch, page_steps, tau_entropy, tau_variance, history, count, fire, stats,
+                                         static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

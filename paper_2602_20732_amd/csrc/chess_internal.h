@@ -100,6 +100,7 @@ struct chess_ctx {
     int max_splits;
     int force_splits, force_waves;                         // 0 = automatic
     size_t ws_acc_off, ws_ml_off, workspace_bytes;
+    size_t ws_ent_off, ws_entcnt_off;                      // entropy partials, their arrival counters
     size_t ws_keys_off, ws_tail_off, ws_meta_off, ws_cnt_off, ws_err_off, ws_prof_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
@@ -179,6 +180,11 @@ size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);
 hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, int batch, hipStream_t stream);
+constexpr int kEntMaxSplits = 32;
+hipError_t launch_entropy(chess_ctx* ctx, const uint16_t* logits, int batch, int vocab, int64_t row_stride, int splits,
+                          float* H, float* partials, int32_t* arrivals, hipStream_t stream);
+hipError_t launch_trigger(const float* H, int batch, int page_steps, double tau_h, double tau_v, float* history,
+                          int32_t* count, int32_t* fire, double* stats, hipStream_t stream);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);
 
 // page_ids == nullptr: every page of the sequence.  n_splits >= 1; the last split of a (sequence,
