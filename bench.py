@@ -109,6 +109,53 @@ def shared_scope(lib, sp, seq_lens, lens, plan, n_layers, timed):
             "data": "seeded normal summary vectors", "selection_alone_us": round(sel_ms * 1e3, 1)}
 
 
+def steady_state(lib, sp, plan, pools, summs, n_pools, n_q, out, ws, timed, steps, pages_between=10):
+    """The paper's operating point (Sec. 3.3, App. on reconstruction: a reselection about every 10 generated pages).
+    Two step types, each timed cache-cold over the same rotation as the main step:
+    reuse step = append one token + extend the window + sparse attention over the kept list;
+    reselect step = summaries of the pages generated since the last selection + the fused step.
+    `us_per_step_at_interval` combines them for a reselection every pages_between * page_size steps."""
+    import torch
+    H, d = sp.n_kv_heads, sp.head_dim
+    lists = {}
+    for pi in range(n_pools):
+        wl, qs = pools[pi]
+        for qi in range(n_q):
+            ids = torch.empty((sp.batch, H, sp.max_selected), dtype=torch.int32, device="cuda")
+            nsel = torch.empty((sp.batch, H), dtype=torch.int32, device="cuda")
+            lib.decode_step(qs[qi], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summs[pi], plan, ids, nsel, out, ws)
+            lists[(pi, qi)] = (ids, nsel)
+    rows_k = torch.randn((sp.batch, H, d), device="cuda").to(torch.bfloat16)
+    rows_v = torch.randn((sp.batch, H, d), device="cuda").to(torch.bfloat16)
+    before = [(pools[pi][0].seq_lens - 1).clamp_(min=0) for pi in range(n_pools)]        # the append rewrites the last token
+    since = [((-(-pools[pi][0].seq_lens // sp.page_size)) - pages_between).clamp_(min=0).to(torch.int32) for pi in range(n_pools)]
+    torch.cuda.synchronize()
+
+    def reuse(i):
+        pi, qi = i % n_pools, (i // n_pools) % n_q
+        wl, qs = pools[pi]
+        ids, nsel = lists[(pi, qi)]
+        lib.append_kv(rows_k, rows_v, wl.k_pool, wl.v_pool, wl.block_table, before[pi])
+        lib.extend_window(wl.seq_lens, ids, nsel)
+        lib.sparse_decode(qs[qi], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out, ws)
+
+    def reselect(i):
+        pi, qi = i % n_pools, (i // n_pools) % n_q
+        wl, qs = pools[pi]
+        ids, nsel = lists[(pi, qi)]
+        lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, summs[pi], from_page=since[pi])
+        lib.decode_step(qs[qi], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summs[pi], plan, ids, nsel, out, ws,
+                        refresh_tail=True)
+
+    ms_reuse, _ = timed(reuse, steps, 8, True)
+    ms_resel, _ = timed(reselect, min(steps, 64), 4, True)
+    interval = pages_between * sp.page_size
+    avg = ((interval - 1) * ms_reuse + ms_resel) / interval
+    return {"reuse_step_us": round(ms_reuse * 1e3, 2), "reselect_step_us": round(ms_resel * 1e3, 2),
+            "reselect_every_steps": interval, "us_per_step_at_interval": round(avg * 1e3, 2),
+            "kernel_launches": {"reuse_step": 3, "reselect_step": 2}}
+
+
 def trigger_monitor(lib, sp, timed, vocab=151936):
     """Sec. 3.3 monitor per decode step: entropy of the batch's logits rows (bf16, a 152K vocabulary) + page statistics."""
     import torch
@@ -368,6 +415,7 @@ def main():
     if args.shared_layers > 0:
         result["shared_scope"] = shared_scope(lib, sp, pools[0][0].seq_lens, lens, plan, args.shared_layers, timed)
     result["trigger"] = trigger_monitor(lib, sp, timed)
+    result["steady_state"] = steady_state(lib, sp, plan, pools, summs, n_pools, n_q, out, ws, timed, args.steps)
     if args.workload == "cfg3":
         result["stack_of_32_layers_us"] = round(ms_step * 1e3 * 32, 1)
 

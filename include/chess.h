@@ -179,6 +179,17 @@ int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* 
                         int32_t* n_selected, void* workspace, void* stream);
 
 /*
+ * Between reselections (Sec. 3.3) a page list is reused while the sequence grows; the recent window of Sec. 3.2
+ * is relative to the current position, so the pages generated since the selection belong to the list.  This call
+ * appends to every list the pages after its last entry up to the sequence's current last page (seq_lens: the
+ * current lengths); an empty list starts at page 0.  A row stops growing when it holds max_selected_pages ids:
+ * size the configuration for the longest stretch between reselections.  page_ids / n_selected: as written by
+ * chess_select / chess_decode_step / chess_select_shared, updated in place.
+ */
+int chess_extend_window(chess_ctx* ctx, const int32_t* seq_lens, int32_t batch, int32_t* page_ids, int32_t* n_selected,
+                        void* stream);
+
+/*
  * The quality monitor of Sec. 3.3, first half: the entropy (nats) of the output distribution of one decode step,
  * H[b] = -sum_v p_v log p_v with p = softmax(logits[b]).  logits: device, bf16 [batch][row_stride], the first
  * `vocab` entries of a row are used (-inf entries count as probability 0); 16-byte aligned, row_stride a multiple

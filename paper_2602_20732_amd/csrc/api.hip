@@ -325,6 +325,15 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
+int chess_extend_window(chess_ctx* ctx, const int32_t* seq_lens, int32_t batch, int32_t* page_ids, int32_t* n_selected,
+                        void* stream)
+{
+    if (!ctx || !seq_lens || !page_ids || !n_selected) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    hipError_t e = chess::launch_extend(ctx, seq_lens, batch, page_ids, n_selected, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
 int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
                   void* workspace, void* stream)
 {

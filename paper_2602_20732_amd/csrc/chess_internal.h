@@ -180,6 +180,8 @@ size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu);
 hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, int batch, hipStream_t stream);
+hipError_t launch_extend(chess_ctx* ctx, const int32_t* seq_lens, int batch, int32_t* page_ids, int32_t* n_selected,
+                         hipStream_t stream);
 constexpr int kEntMaxSplits = 32;
 hipError_t launch_entropy(chess_ctx* ctx, const uint16_t* logits, int batch, int vocab, int64_t row_stride, int splits,
                           float* H, float* partials, int32_t* arrivals, hipStream_t stream);

@@ -107,6 +107,29 @@ hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* 
                   block_table, seq_lens, ctx->geom);
 }
 
+// Between reselections the recent window follows the tail: every list is extended by the pages after its last
+// entry, up to the sequence's current last page (as far as the row has room).  One thread per (sequence, KV head).
+__global__ void extend_kernel(const int32_t* __restrict__ seq_lens, int rows, Geom g, int32_t* __restrict__ page_ids,
+                              int32_t* __restrict__ n_selected)
+{
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    const int L = min(max(seq_lens[row / g.n_kv_heads], 0), g.max_pages * g.page_size);
+    const int P = (L + g.page_size - 1) / g.page_size;
+    int32_t* ids = page_ids + (size_t)row * g.max_sel;
+    int n = min(max(n_selected[row], 0), g.max_sel);
+    int last = n > 0 ? ids[n - 1] : -1;
+    while (last < P - 1 && n < g.max_sel) ids[n++] = ++last;
+    n_selected[row] = n;
+}
+
+hipError_t launch_extend(chess_ctx* ctx, const int32_t* seq_lens, int batch, int32_t* page_ids, int32_t* n_selected,
+                         hipStream_t stream)
+{
+    const int rows = batch * ctx->geom.n_kv_heads;
+    return launch(extend_kernel, dim3((rows + 63) / 64), dim3(64), 0, stream, seq_lens, rows, ctx->geom, page_ids, n_selected);
+}
+
 __global__ void zero_kernel(int32_t* p, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;

@@ -82,3 +82,64 @@ def test_append_grows_the_cache_and_the_step_follows_it():
     torch.cuda.synchronize()
     assert torch.equal(before.view(torch.int16), k_pool.view(torch.int16))
     lib.close()
+
+
+def test_list_reuse_between_reselections_follows_the_tail():
+    """The paper's operating point (Sec. 3.3): select once, then decode for several pages with the same list while the
+    cache grows.  chess_extend_window keeps the recent pages in the list; each step's attention equals the oracle's
+    attention over (list at selection time) + (every page generated since)."""
+    sp = workload.WorkloadSpec("reuse", 2, (0, 1400), 8, 2, 16, ("fixed", 128), (2, 2), 1, 2, budget_pages=5,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    start, steps = [1200, 700], 50
+    full = workload.generate(sp, 21, seq_lens=[n + steps for n in start])
+    d = to_device(full)
+    K, V, Q = workload.bf16_bits(full.k_pool), workload.bf16_bits(full.v_pool), workload.bf16_bits(full.q)
+    bt = full.block_table.numpy()
+    g = geom_of(sp)
+    B = sp.page_size
+    room = 1 + 5 + 2 + -(-steps // B) + 1
+    lib = pk.Chess(config_of(sp, max_selected=room))
+    plan = plan_of(sp)
+    lens = torch.tensor(start, dtype=torch.int32, device="cuda")
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, lens, summ)
+    ids = torch.empty((2, sp.n_kv_heads, room), dtype=torch.int32, device="cuda")
+    nsel = torch.empty((2, sp.n_kv_heads), dtype=torch.int32, device="cuda")
+    out = torch.empty((2, sp.n_q_heads, 128), device="cuda")
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, lens, summ, gpu_plan(plan), ids, nsel, out, ws)
+    torch.cuda.synchronize()
+    ids0, n0 = ids.cpu().numpy().copy(), nsel.cpu().numpy().copy()
+    rp, rc, rg = oracle.summarize(K, bt, np.array(start, np.int32), g)
+    rids, rn = oracle.select(Q, rp, rc, rg, np.array(start, np.int32), g, plan, room)
+    assert np.array_equal(ids0, rids) and np.array_equal(n0, rn)
+    for step in range(1, steps + 1):
+        lens += 1                                          # the pools already hold the rows (appends are tested above)
+        lib.extend_window(lens, ids, nsel)
+        lib.sparse_decode(d.q, d.k_pool, d.v_pool, d.block_table, lens, ids, nsel, out, ws)
+        if step in (1, 15, 16, 17, 33, steps):
+            sl = lens.cpu().numpy()
+            want_ids = np.full_like(rids, -1)
+            want_n = np.zeros_like(rn)
+            for b in range(2):
+                P = -(-int(sl[b]) // B)
+                for h in range(sp.n_kv_heads):
+                    row = rids[b, h, :rn[b, h]].tolist()
+                    row += list(range(row[-1] + 1, P))
+                    want_ids[b, h, :len(row)] = row
+                    want_n[b, h] = len(row)
+            got_ids, got_n = ids.cpu().numpy(), nsel.cpu().numpy()
+            assert np.array_equal(got_n, want_n), step
+            for b in range(2):
+                for h in range(sp.n_kv_heads):
+                    assert np.array_equal(got_ids[b, h, :got_n[b, h]], want_ids[b, h, :want_n[b, h]]), (step, b, h)
+            ref = oracle.attend(Q, K, V, bt, sl, g, want_ids, want_n)
+            assert np.abs(out.cpu().numpy() - ref).max() <= 2e-3, step
+    # a row that is full stops growing and stays valid
+    small = pk.Chess(config_of(sp, max_selected=9))
+    ids9 = torch.as_tensor(np.ascontiguousarray(rids[:, :, :9])).cuda()
+    n9 = torch.as_tensor(np.minimum(rn, 9)).cuda()
+    small.extend_window(lens, ids9, n9)
+    torch.cuda.synchronize()
+    assert int(n9.max()) == 9 and int(ids9.max()) < -(-int(lens.max()) // B)
+    small.close()
+    lib.close()
