@@ -65,9 +65,14 @@ bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
 
 struct SplitShape { int n_splits, waves; };
 
-// Split-K shape: enough workgroups to cover the chip a few times over, never more splits than
-// there are tiles; small problems drop to one wave per workgroup so that tiles spread over more CUs.
-SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages)
+// Split-K shape.  Every workgroup has four waves; tiles are dealt round-robin over splits and waves.
+// Dense (every page): enough workgroups to cover the chip a few times over; the workgroup that finishes last merges
+// ns partial rows per output, tile time falls as 1/ns and merge time grows as G*ns/32 (in units of one memory
+// round trip), so the best split count is about sqrt(8*tiles/G), within what is resident at once.
+// A page list (tens to hundreds of pages): the fixed latencies dominate, and the measured optimum (sweeps at batch
+// 1 .. 32, 21 .. 415 pages, G = 1 .. 7) is: no split once there is a (sequence, head) per compute unit; otherwise one
+// workgroup per compute unit, at least two tiles per workgroup, and at most 1.6 x the merge-balanced count.
+SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages, bool listed)
 {
     const chess::Geom& g = ctx->geom;
     const int ppt = chess::kTileTokens / g.page_size;
@@ -78,12 +83,18 @@ SplitShape choose_splits(const chess_ctx* ctx, int batch, int64_t max_list_pages
     const int waves = 4;
     // all workgroups resident at once: a second round of workgroups would double a short kernel
     const int64_t resident = (int64_t)ctx->dec_blocks4 * ctx->n_cu;
-    // the workgroup that finishes last merges ns partial rows per output; tile time falls as 1/ns and merge
-    // time grows as G*ns/32 (in units of one memory round trip), so the best split count is about sqrt(8*tiles/G)
-    int64_t ns = (int64_t)std::llround(std::sqrt(8.0 * (double)tiles / g.group));
-    ns = std::min<int64_t>(ns, std::max<int64_t>(1, resident / pairs));
-    ns = clampi(ns, 1, cdiv(tiles, waves));
-    ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 1024 / g.group));   // the merge keeps (m, l) of every split in LDS
+    const double balanced = std::sqrt(8.0 * (double)tiles / g.group);
+    int64_t ns;
+    if (listed) {
+        ns = std::min<int64_t>(ctx->n_cu / pairs, cdiv(tiles, 2));
+        ns = std::min<int64_t>(ns, (int64_t)std::llround(1.6 * balanced));
+        ns = std::max<int64_t>(ns, 1);
+    } else {
+        ns = (int64_t)std::llround(balanced);
+        ns = std::min<int64_t>(ns, std::max<int64_t>(1, resident / pairs));
+        ns = clampi(ns, 1, cdiv(tiles, waves));
+    }
+    ns = std::min<int64_t>(ns, std::min<int64_t>(ctx->max_splits, 1024 / g.group));
     while (ns > 1 && pairs * ns > target + pairs) --ns;            // stay inside the workspace
     return {(int)ns, waves};
 }
@@ -96,7 +107,7 @@ int decode_common(chess_ctx* ctx, const void* q, const void* k_pool, const void*
     if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(q) |
          reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace)) & 15) return CHESS_EINVAL;
-    const SplitShape sh = choose_splits(ctx, batch, page_ids ? ctx->geom.max_sel : ctx->geom.max_pages);
+    const SplitShape sh = choose_splits(ctx, batch, page_ids ? ctx->geom.max_sel : ctx->geom.max_pages, page_ids != nullptr);
     float* ws_acc = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_acc_off);
     float* ws_ml = reinterpret_cast<float*>(static_cast<char*>(workspace) + ctx->ws_ml_off);
     int32_t* arrivals = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + ctx->ws_cnt_off);
@@ -165,8 +176,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_entcnt_off = align_up(c->ws_ent_off + (size_t)cfg->max_batch * chess::kEntMaxSplits * 4 * sizeof(float), 256);
     c->workspace_bytes = align_up(c->ws_entcnt_off + (size_t)cfg->max_batch * sizeof(int32_t), 256);
     c->dec_blocks4 = c->dec_blocks1 = 2;
-    if (chess::decode_occupancy(g.page_size, 4, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
-    if (chess::decode_occupancy(g.page_size, 1, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
+    if (chess::decode_occupancy(g.page_size, 4, g.group, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
+    if (chess::decode_occupancy(g.page_size, 1, g.group, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
     c->force_cluster = 0;
     c->force_general_cut = 0;
     c->poll_limit = 0;

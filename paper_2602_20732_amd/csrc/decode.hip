@@ -18,9 +18,9 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
                                                          )
 {
     constexpr int PPT = 32 / B;
-    __shared__ float lds_f[DecodeLds<NW>::kFloats];
+    extern __shared__ float lds_f[];                  // DecodeLds<NW>::floats(G)
     __shared__ int lds_last;
-    DecodeLds<NW> lds(lds_f);
+    DecodeLds<NW> lds(lds_f, g.group);
 
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -62,6 +62,7 @@ hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_po
     const Geom& g = ctx->geom;
     const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     const dim3 grid(n_splits, g.n_kv_heads, batch), block(64 * waves);
+    const size_t lds = (size_t)(waves * g.group * kHeadDim + 2 * waves * g.group) * sizeof(float);
     using Kern = void (*)(const uint16_t*, const uint16_t*, const uint16_t*, const int32_t*, const int32_t*, const int32_t*,
                           const int32_t*, Geom, float, int, float*, float*, float*, int32_t*);
     // [page size 16 / 32][waves 4 / 1][list / every page]
@@ -69,18 +70,23 @@ hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_po
         {{decode_kernel<16, 4, true>, decode_kernel<16, 4, false>}, {decode_kernel<16, 1, true>, decode_kernel<16, 1, false>}},
         {{decode_kernel<32, 4, true>, decode_kernel<32, 4, false>}, {decode_kernel<32, 1, true>, decode_kernel<32, 1, false>}}};
     const Kern kern = table[g.page_size == 16 ? 0 : 1][waves == 4 ? 0 : 1][page_ids ? 0 : 1];
-    return launch(kern, grid, block, 0, stream, q, k_pool, v_pool, block_table, seq_lens,
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    return launch(kern, grid, block, lds, stream, q, k_pool, v_pool, block_table, seq_lens,
                   page_ids, n_selected, g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
 }
 
-hipError_t decode_occupancy(int page_size, int waves, int* blocks_per_cu)
+hipError_t decode_occupancy(int page_size, int waves, int group, int* blocks_per_cu)
 {
     // (the list variant: it is the one whose split count depends on what fits)
+    const size_t lds = (size_t)(waves * group * kHeadDim + 2 * waves * group) * sizeof(float);
     if (page_size == 16)
-        return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 4, true>, 256, 0)
-                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 1, true>, 64, 0);
-    return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 4, true>, 256, 0)
-                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1, true>, 64, 0);
+        return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 4, true>, 256, lds)
+                          : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<16, 1, true>, 64, lds);
+    return waves == 4 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 4, true>, 256, lds)
+                      : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_kernel<32, 1, true>, 64, lds);
 }
 
 // One new token per sequence into the paged pools: K row-major [phys][H][B][128], V token-minor [phys][H][128][B].

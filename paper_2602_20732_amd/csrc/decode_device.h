@@ -210,15 +210,19 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
     acc.l_run += __shfl_xor(acc.l_run, 32);
 }
 
-// LDS the combine / merge below needs, in floats: [NW][16][128] accumulators, [NW][16] maxima, [NW][16] sums.
+// LDS the combine below needs, in floats: [NW][hs][128] accumulators, [NW][hs] maxima, [NW][hs] sums, where the
+// head stride hs is 16 (one MFMA N-tile: nothing to guard) or the group size G (what a large workgroup can afford).
 template <int NW>
 struct DecodeLds {
     static constexpr int kFloats = NW * kMaxGroup * kHeadDim + 2 * NW * kMaxGroup;
-    float* o;   // [NW][kMaxGroup][kHeadDim]
-    float* m;   // [NW][kMaxGroup]
-    float* l;   // [NW][kMaxGroup]
-    __device__ __forceinline__ explicit DecodeLds(float* base)
-        : o(base), m(base + NW * kMaxGroup * kHeadDim), l(base + NW * kMaxGroup * kHeadDim + NW * kMaxGroup) {}
+    static constexpr int floats(int hs) { return NW * hs * kHeadDim + 2 * NW * hs; }
+    float* o;   // [NW][hs][kHeadDim]
+    float* m;   // [NW][hs]
+    float* l;   // [NW][hs]
+    int hs;
+    __device__ __forceinline__ explicit DecodeLds(float* base, int head_stride = kMaxGroup)
+        : o(base), m(base + NW * head_stride * kHeadDim), l(base + NW * head_stride * kHeadDim + NW * head_stride),
+          hs(head_stride) {}
 };
 
 // Merge the NW waves of this workgroup through LDS.  n_splits == 1: write `out` rows and return false.
@@ -231,10 +235,13 @@ __device__ __forceinline__ bool combine_waves(const f32x4 (&o)[8], float m_run, 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m16 = lane & 15, grp = lane >> 4;
     // lane holds O^T[d = 16*blk + 4*grp + r][head m16]
+    const int hs = lds.hs;
+    if (m16 < hs) {                                     // (heads beyond the group are zero columns)
 #pragma unroll
-    for (int blk = 0; blk < 8; ++blk)
-        *reinterpret_cast<f32x4*>(&lds.o[(wave * kMaxGroup + m16) * kHeadDim + 16 * blk + 4 * grp]) = o[blk];
-    if (grp == 0) { lds.m[wave * kMaxGroup + m16] = m_run; lds.l[wave * kMaxGroup + m16] = l_run; }
+        for (int blk = 0; blk < 8; ++blk)
+            *reinterpret_cast<f32x4*>(&lds.o[(wave * hs + m16) * kHeadDim + 16 * blk + 4 * grp]) = o[blk];
+        if (grp == 0) { lds.m[wave * hs + m16] = m_run; lds.l[wave * hs + m16] = l_run; }
+    }
     __syncthreads();
 
     // combine this workgroup's waves; one thread per pair of adjacent d
@@ -244,14 +251,14 @@ __device__ __forceinline__ bool combine_waves(const f32x4 (&o)[8], float m_run, 
         const int head = idx / (kHeadDim / 2), d = 2 * (idx % (kHeadDim / 2));
         float M = lds.m[head];
 #pragma unroll
-        for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, lds.m[wv * kMaxGroup + head]);
+        for (int wv = 1; wv < NW; ++wv) M = fmaxf(M, lds.m[wv * hs + head]);
         float a0 = 0.f, a1 = 0.f, l = 0.f;
 #pragma unroll
         for (int wv = 0; wv < NW; ++wv) {
-            const float sc = __builtin_amdgcn_exp2f(lds.m[wv * kMaxGroup + head] - M);
-            a0 += lds.o[(wv * kMaxGroup + head) * kHeadDim + d] * sc;
-            a1 += lds.o[(wv * kMaxGroup + head) * kHeadDim + d + 1] * sc;
-            l += lds.l[wv * kMaxGroup + head] * sc;
+            const float sc = __builtin_amdgcn_exp2f(lds.m[wv * hs + head] - M);
+            a0 += lds.o[(wv * hs + head) * kHeadDim + d] * sc;
+            a1 += lds.o[(wv * hs + head) * kHeadDim + d + 1] * sc;
+            l += lds.l[wv * hs + head] * sc;
         }
         if (n_splits == 1) {
             const float inv = l > 0.f ? 1.f / l : 0.f;
