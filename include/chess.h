@@ -124,9 +124,12 @@ int chess_summarize(chess_ctx* ctx, const void* k_pool, const int32_t* block_tab
  * one); a sequence with no room left (seq_lens[b] >= max_pages_per_seq * page_size) or a negative length is
  * skipped.  The only call that writes the pools.  Follow it with chess_summarize_tail (or chess_decode_step
  * with refresh_tail) on the new lengths to bring the summaries up to date.
+ * page_ids / n_selected (both or neither; may be NULL): the lists that are being reused are extended in the same
+ * launch as chess_extend_window would for the lengths after the append.
  */
 int chess_append_kv(chess_ctx* ctx, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
-                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, void* stream);
+                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, int32_t* page_ids,
+                    int32_t* n_selected, void* stream);
 
 /* The per-decode-step refresh: chess_summarize with from_page[b] = (pages of sequence b) - 1,
  * i.e. the tail page and its chunk and grid, launched on batch * H workgroups only. */

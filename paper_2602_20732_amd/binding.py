@@ -97,7 +97,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_entropy.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, vp, vp]
         lib.chess_trigger_update.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double, vp, i32p, i32p, vp, vp]
         lib.chess_extend_window.argtypes = [vp, i32p, ctypes.c_int32, i32p, i32p, vp]
-        lib.chess_append_kv.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp]
+        lib.chess_append_kv.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, i32p, i32p, vp]
         lib.chess_anchor.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(vp), vp]
         lib.chess_select_shared.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32,
                                             ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
@@ -207,9 +207,9 @@ class Chess:
         self._check(self.lib.chess_extend_window(self._h, _ptr(seq_lens), seq_lens.shape[0], _ptr(page_ids), _ptr(n_selected),
                                                  _stream()))
 
-    def append_kv(self, k_new, v_new, k_pool, v_pool, block_table, seq_lens):
+    def append_kv(self, k_new, v_new, k_pool, v_pool, block_table, seq_lens, page_ids=None, n_selected=None):
         self._check(self.lib.chess_append_kv(self._h, _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
-                                             _ptr(seq_lens), seq_lens.shape[0], _stream()))
+                                             _ptr(seq_lens), seq_lens.shape[0], _ptr(page_ids), _ptr(n_selected), _stream()))
 
     def anchor(self, summaries, seq_lens, window_pages: int, anchors):
         """summaries / anchors: one device tensor each, or sequences of per-layer tensors (one launch)."""

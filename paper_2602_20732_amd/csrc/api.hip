@@ -372,13 +372,15 @@ int chess_trigger_update(chess_ctx* ctx, const float* entropy, int32_t batch, in
 }
 
 int chess_append_kv(chess_ctx* ctx, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
-                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, void* stream)
+                    const int32_t* block_table, const int32_t* seq_lens, int32_t batch, int32_t* page_ids,
+                    int32_t* n_selected, void* stream)
 {
     if (!ctx || !k_new || !v_new || !k_pool || !v_pool || !block_table || !seq_lens) return CHESS_EINVAL;
+    if ((page_ids == nullptr) != (n_selected == nullptr)) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
     hipError_t e = chess::launch_append(ctx, static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                                         static_cast<uint16_t*>(k_pool), static_cast<uint16_t*>(v_pool), block_table,
-                                        seq_lens, batch, static_cast<hipStream_t>(stream));
+                                        seq_lens, batch, page_ids, n_selected, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

@@ -179,7 +179,8 @@ hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const in
 size_t select_lds_bytes(const SelectParams& sp, int max_sel);
 hipError_t decode_occupancy(int page_size, int waves, int group, int* blocks_per_cu);
 hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
-                         const int32_t* block_table, const int32_t* seq_lens, int batch, hipStream_t stream);
+                         const int32_t* block_table, const int32_t* seq_lens, int batch, int32_t* page_ids,
+                         int32_t* n_selected, hipStream_t stream);
 hipError_t launch_extend(chess_ctx* ctx, const int32_t* seq_lens, int batch, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 constexpr int kEntMaxSplits = 32;

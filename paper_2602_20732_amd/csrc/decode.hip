@@ -94,11 +94,20 @@ hipError_t decode_occupancy(int page_size, int waves, int group, int* blocks_per
 __global__ __launch_bounds__(kHeadDim) void append_kernel(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
                                                           uint16_t* __restrict__ k_pool, uint16_t* __restrict__ v_pool,
                                                           const int32_t* __restrict__ block_table,
-                                                          const int32_t* __restrict__ seq_lens, Geom g)
+                                                          const int32_t* __restrict__ seq_lens, Geom g,
+                                                          int32_t* __restrict__ page_ids, int32_t* __restrict__ n_selected)
 {
     const int row = blockIdx.x, b = row / g.n_kv_heads, h = row - b * g.n_kv_heads, dim = threadIdx.x;
     const int L = seq_lens[b], B = g.page_size;
     if (L < 0 || L >= g.max_pages * B) return;        // no room: the sequence is left as it is
+    if (page_ids != nullptr && dim == 0) {            // the row's list follows the tail (what extend_kernel does)
+        const int P = L / B + 1;                      // pages once the token is in
+        int32_t* ids = page_ids + (size_t)row * g.max_sel;
+        int n = min(max(n_selected[row], 0), g.max_sel);
+        int last = n > 0 ? ids[n - 1] : -1;
+        while (last < P - 1 && n < g.max_sel) ids[n++] = ++last;
+        n_selected[row] = n;
+    }
     const int64_t phys = block_table[(size_t)b * g.max_pages + L / B];
     const int t = L % B;
     const size_t blk = ((size_t)phys * g.n_kv_heads + h) * B * kHeadDim;
@@ -107,10 +116,11 @@ __global__ __launch_bounds__(kHeadDim) void append_kernel(const uint16_t* __rest
 }
 
 hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
-                         const int32_t* block_table, const int32_t* seq_lens, int batch, hipStream_t stream)
+                         const int32_t* block_table, const int32_t* seq_lens, int batch, int32_t* page_ids,
+                         int32_t* n_selected, hipStream_t stream)
 {
     return launch(append_kernel, dim3(batch * ctx->geom.n_kv_heads), dim3(kHeadDim), 0, stream, k_new, v_new, k_pool, v_pool,
-                  block_table, seq_lens, ctx->geom);
+                  block_table, seq_lens, ctx->geom, page_ids, n_selected);
 }
 
 // Between reselections the recent window follows the tail: every list is extended by the pages after its last

@@ -113,8 +113,14 @@ def test_list_reuse_between_reselections_follows_the_tail():
     rids, rn = oracle.select(Q, rp, rc, rg, np.array(start, np.int32), g, plan, room)
     assert np.array_equal(ids0, rids) and np.array_equal(n0, rn)
     for step in range(1, steps + 1):
-        lens += 1                                          # the pools already hold the rows (appends are tested above)
-        lib.extend_window(lens, ids, nsel)
+        if step % 2:                                       # the two ways to extend a list: a call of its own ...
+            lens += 1                                      # (the pools already hold the rows)
+            lib.extend_window(lens, ids, nsel)
+        else:                                              # ... or inside the append (which rewrites the row that is there)
+            rows_k = torch.stack([d.k_pool[int(bt[b, int(lens[b]) // B]), :, int(lens[b]) % B, :] for b in range(2)])
+            rows_v = torch.stack([d.v_pool[int(bt[b, int(lens[b]) // B]), :, :, int(lens[b]) % B] for b in range(2)])
+            lib.append_kv(rows_k.contiguous(), rows_v.contiguous(), d.k_pool, d.v_pool, d.block_table, lens, ids, nsel)
+            lens += 1
         lib.sparse_decode(d.q, d.k_pool, d.v_pool, d.block_table, lens, ids, nsel, out, ws)
         if step in (1, 15, 16, 17, 33, steps):
             sl = lens.cpu().numpy()
