@@ -93,6 +93,61 @@ __device__ __forceinline__ void load_tile(Tile<B>& tl, int t, int n_pages, const
     }
 }
 
+// The same in two steps, for the kernels that go through the block table: the block-table entries of a tile are
+// requested one tile earlier than its K / V rows, so that their round trip hides behind the rows of the tile
+// before (a wave's loads return in order: an entry requested just before its rows would hold them back by a
+// whole round trip per tile).
+template <int B>
+struct PageRef {
+    int pp[32 / B];     // physical pages (the same in every lane; made scalar when they are used)
+    int ntok[32 / B];   // valid tokens of each page slot (0 = slot unused)
+};
+
+template <int B>
+__device__ __forceinline__ void lookup_pages(PageRef<B>& r, int t, int n_pages, const int (&raw)[32 / B],
+                                             const int32_t* bt_row, int L, int P)
+{
+    constexpr int PPT = 32 / B;
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) {
+        const bool ok = t * PPT + s < n_pages;
+        int lp = ok ? raw[s] : raw[0];                            // unused slot: alias the tile's first page
+        lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
+        r.pp[s] = bt_row[lp];
+        r.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
+    }
+}
+
+template <int B>
+__device__ __forceinline__ void load_rows(Tile<B>& tl, const PageRef<B>& r, const uint16_t* k_pool, const uint16_t* v_pool,
+                                          int H, int h, int m16, int grp)
+{
+    constexpr int PPT = 32 / B;
+    int64_t phys[PPT];
+#pragma unroll
+    for (int s = 0; s < PPT; ++s) {
+        phys[s] = __builtin_amdgcn_readfirstlane(r.pp[s]);
+        tl.ntok[s] = r.ntok[s];
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int T = 8 * (m16 >> 2) + 4 * c + (m16 & 3);
+        const int slot = T / B, tok = T % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint4* src = reinterpret_cast<const uint4*>(k_pool + ((pg * H + h) * B + tok) * kHeadDim) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) tl.k[c][st] = src[st * 4];
+    }
+    {
+        const int T0 = 8 * grp;
+        const int slot = T0 / B, tok0 = T0 % B;
+        const int64_t pg = PPT == 1 ? phys[0] : (slot ? phys[PPT - 1] : phys[0]);
+        const uint16_t* base = v_pool + ((pg * H + h) * kHeadDim + m16) * B + tok0;
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) tl.v[blk] = *reinterpret_cast<const uint4*>(base + (size_t)blk * 16 * B);
+    }
+}
+
 // Online-softmax state of one wave: all G heads of one KV head.
 template <int B>
 struct WaveAcc {
@@ -190,6 +245,31 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
                                           int grp)
 {
     constexpr int PPT = 32 / B;
+    if constexpr (!kPhysList) {
+        if (t < n_tiles) {
+            // block-table entries run one tile ahead of the rows, page numbers one tile ahead of those
+            PageRef<B> pc, pn, pnn;
+            int raw_nn[PPT];
+            lookup_pages<B>(pc, t, n_pages, raw_cur, bt_row, L, P);
+            lookup_pages<B>(pn, t + stride, n_pages, raw_nxt, bt_row, L, P);
+            fetch_ids<B, kList>(raw_nn, t + 2 * stride, ids, max_sel);
+            Tile<B> cur, nxt;
+            load_rows<B>(cur, pc, k_pool, v_pool, H, h, m16, grp);
+            for (; t < n_tiles; t += stride) {
+                const bool more = t + stride < n_tiles;
+                if (more) pc = pn;                                // after the last tile the request repeats it
+                load_rows<B>(nxt, pc, k_pool, v_pool, H, h, m16, grp);
+                lookup_pages<B>(pnn, t + 2 * stride, n_pages, raw_nn, bt_row, L, P);
+                fetch_ids<B, kList>(raw_nn, t + 3 * stride, ids, max_sel);
+                acc.process(cur, scale_log2, grp);
+                cur = nxt;
+                pn = pnn;
+            }
+        }
+        acc.l_run += __shfl_xor(acc.l_run, 16);
+        acc.l_run += __shfl_xor(acc.l_run, 32);
+        return;
+    }
     if (t < n_tiles) {
         Tile<B> cur, nxt;
         load_tile<B, kPhysList>(cur, t, n_pages, raw_cur, bt_row, phys_list, k_pool, v_pool, H, h, L, P, m16, grp);
