@@ -172,3 +172,30 @@ def test_shared_scope_at_benchmark_shapes(batch, lo, hi, n_layers, sample):
         assert nsel_h[b, 0] == on[0] and np.array_equal(ids_h[b, 0], oids[0]), (b, "page list")
         print(f"[shared {batch}x{n_layers}] seq {b} ({int(lens[b])} tokens): page list exact, {on[0]} pages")
     lib.close()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_shared_scope_random_shapes(seed):
+    """Seeded draws of geometry, batch, lengths, layers, plan and cluster size."""
+    rng = np.random.default_rng(7000 + seed)
+    B, H = int(rng.choice([16, 32])), int(rng.choice([1, 2, 4, 8]))
+    nc, ng = int(rng.choice([1, 2, 4, 5, 8])), int(rng.choice([1, 2, 3, 8]))
+    batch, hi = int(rng.integers(1, 4)), int(rng.choice([400, 2000, 6000]))
+    lens = [hi] + [int(rng.integers(0, hi + 1)) for _ in range(batch - 1)]
+    s, w = int(rng.choice([0, 1, 2])), int(rng.choice([1, 2, 4]))
+    kind = int(rng.choice([oracle.PLAN_BUDGET, oracle.PLAN_RATIO, oracle.PLAN_FLAT]))
+    kw = dict(plan=kind, sink_pages=s, window_pages=w)
+    if kind == oracle.PLAN_RATIO:
+        kw.update(rho_g_bp=int(rng.integers(1, 10001)), rho_c_bp=int(rng.integers(1, 10001)), rho_p_bp=int(rng.integers(1, 10001)))
+    else:
+        kw.update(budget_pages=int(rng.integers(1, 30)), over_chunk=int(rng.integers(1, 12)), over_grid=int(rng.integers(1, 8)))
+    n_layers, cluster = int(rng.integers(1, 7)), int(rng.choice([0, 1, 3, 9]))
+    sp = workload.WorkloadSpec(f"srand{seed}", batch, (0, hi), H, H, B, ("fixed", 96), (1, 1), s, w,
+                               pages_per_chunk=nc, chunks_per_grid=ng)
+    print(f"[shared rand {seed}] page {B} H {H} fan {nc}x{ng} lens {lens} layers {n_layers} plan {kw} cluster {cluster}", flush=True)
+    wls = layers_of(sp, range(900 + 10 * seed, 900 + 10 * seed + n_layers), lens)
+    ids, nsel, anc, oids, onsel, oanc, lib, ds, summs, host = run_both(sp, wls, plan_of(sp, **kw), cluster, max_sel=sp.max_pages)
+    for a, o in zip(anc, oanc):
+        assert np.array_equal(a.view(np.uint32), o.view(np.uint32)), "anchor vectors"
+    assert_lists_equal(ids, nsel, oids, onsel, sp.n_kv_heads)
+    lib.close()
