@@ -6,7 +6,7 @@
  * in place (no KV copy, only page indices change: Sec. 1, Sec. 4.1, App. B "Zero-Copy Logic").
  *
  * C ABI.  Every data pointer is a DEVICE pointer owned by the caller unless it says "host".
- * The library never allocates or frees device memory; K/V pools are read-only.  Every call is
+ * The library never allocates or frees device memory; only chess_append_kv writes the K/V pools.  Every call is
  * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream), does no
  * host synchronisation, and can be captured in a HIP graph.
  *
