@@ -619,6 +619,31 @@ __device__ __forceinline__ int cut_one_wave(const uint64_t* keys, int n_slots, K
     return sh.cnt;
 }
 
+// A level of at most 64 slots: one key per lane of wave 0, each lane counts the keys that rank before its own
+// (key descending, slot ascending) with 64 lane reads; no histogram, no LDS.  Same contract as cut_one_wave.
+template <class KFn, class Out>
+__device__ __forceinline__ int cut_one_lane_each(const uint64_t* keys, int n_slots, KFn k_of, Out emit, Shared& sh)
+{
+    const int tid = threadIdx.x;
+    if (tid < kWave) {
+        const int lane = tid;
+        const uint64_t key = lane < n_slots ? keys[lane] : 0ull;
+        const uint64_t valid = __ballot(key != 0ull);
+        const int k = k_of(__popcll(valid));
+        int rank = 0;
+        for (uint64_t mk = valid; mk != 0ull; mk &= mk - 1) {
+            const int j = __builtin_amdgcn_readfirstlane(__ffsll((long long)mk) - 1);
+            const uint64_t kj = lane_read64(key, j);
+            rank += kj > key || (kj == key && j < lane);
+        }
+        const uint64_t kb = __ballot(key != 0ull && rank < k);
+        if ((kb >> lane) & 1ull) emit(__popcll(kb & __lanemask_lt()), lane);
+        if (lane == 0) sh.cnt = __popcll(kb);
+    }
+    __syncthreads();
+    return sh.cnt;
+}
+
 // Scores of the slots [lo, hi), kFly units per 16-lane group requested before the first is waited for.
 // `unit_of(slot)` is the index of the slot's 128-float vector in `base`, or -1 when the slot has no unit.
 // Lane ln of a group holds probe dims 4 ln .. 4 ln + 3 and 64 + 4 ln .. 64 + 4 ln + 3.  The key of a slot goes
@@ -788,7 +813,7 @@ __device__ __forceinline__ int finish_level(const uint64_t* pub, int n_slots, bo
         if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key, sh)) return -1;
         after_pull();
         prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark(); prof.mark();
-        n = cut_one_wave(keys, n_slots, k_of, emit, sh);
+        n = n_slots <= kWave ? cut_one_lane_each(keys, n_slots, k_of, emit, sh) : cut_one_wave(keys, n_slots, k_of, emit, sh);
     } else if (n_slots <= kRegsSmall * kSelThreads) {
         uint64_t key[kRegsSmall];
         if (!pull_keys<kRegsSmall>(pub, n_slots, local, ov, keys, key, sh)) return -1;
