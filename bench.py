@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense full-KV comparison")
     ap.add_argument("--shared-layers", type=int, default=32,
                     help="layers of the model-wide selection timed beside the step (0 = skip)")
+    ap.add_argument("--fanout", default="", help="NcxNg: pages per chunk x chunks per grid instead of the workload's 8x8")
     ap.add_argument("--cluster", type=int, default=0,
                     help="tuning aid: force the workgroups per (sequence, KV head) of select / decode_step (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -241,6 +242,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     sp = workload.spec(args.workload)
+    if args.fanout:
+        import dataclasses
+        nc_, ng_ = (int(x) for x in args.fanout.lower().split("x"))
+        sp = dataclasses.replace(sp, pages_per_chunk=nc_, chunks_per_grid=ng_)
     seed = workload.default_seed(args.workload)
     pool_bytes = sp.batch * sp.ctx[1] * sp.n_kv_heads * sp.head_dim * 2 * 2
     # ~2 GB of KV, at least 2 pools; cfg3 is defined as a stack of 32 layers with their own KV (about 100 GB)
