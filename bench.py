@@ -129,7 +129,6 @@ def steady_state(lib, sp, plan, pools, summs, n_pools, n_q, out, ws, timed, step
     rows_k = torch.randn((sp.batch, H, d), device="cuda").to(torch.bfloat16)
     rows_v = torch.randn((sp.batch, H, d), device="cuda").to(torch.bfloat16)
     before = [(pools[pi][0].seq_lens - 1).clamp_(min=0) for pi in range(n_pools)]        # the append rewrites the last token
-    since = [((-(-pools[pi][0].seq_lens // sp.page_size)) - pages_between).clamp_(min=0).to(torch.int32) for pi in range(n_pools)]
     torch.cuda.synchronize()
 
     def reuse(i):
@@ -143,7 +142,7 @@ def steady_state(lib, sp, plan, pools, summs, n_pools, n_q, out, ws, timed, step
         pi, qi = i % n_pools, (i // n_pools) % n_q
         wl, qs = pools[pi]
         ids, nsel = lists[(pi, qi)]
-        lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, summs[pi], from_page=since[pi])
+        lib.summarize_recent(wl.k_pool, wl.block_table, wl.seq_lens, pages_between, summs[pi])
         lib.decode_step(qs[qi], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summs[pi], plan, ids, nsel, out, ws,
                         refresh_tail=True)
 

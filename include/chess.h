@@ -136,6 +136,13 @@ int chess_append_kv(chess_ctx* ctx, const void* k_new, const void* v_new, void* 
 int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
                          int32_t batch, void* summaries, void* stream);
 
+/* The catch-up before a reselection (Sec. 3.3: between reselections nothing reads the summaries): chess_summarize
+ * with from_page[b] = max(0, (pages of sequence b) - recent_pages), launched only on the grids those pages can
+ * touch.  recent_pages >= 1 is a host value: an upper bound on the pages any sequence has gained or changed since
+ * its summaries were last current (recent_pages = 1 is chess_summarize_tail). */
+int chess_summarize_recent(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                           int32_t batch, int32_t recent_pages, void* summaries, void* stream);
+
 /*
  * Coarse-to-fine selection (Sec. 3.2, Eq. 4, Alg. 1).  Per (sequence, KV head): the probe is the
  * sum of the group's G query rows; a unit's score is probe . unit vector (fp64).  Level 1 keeps

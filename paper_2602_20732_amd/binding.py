@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
-           "chess_summarize", "chess_summarize_tail", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_extend_window", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
+           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_extend_window", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
            "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
@@ -92,6 +92,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_workspace_bytes.argtypes = [vp, ctypes.POINTER(ctypes.c_size_t)]
         lib.chess_summarize.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, i32p, vp, vp]
         lib.chess_summarize_tail.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, vp, vp]
+        lib.chess_summarize_recent.argtypes = [vp, vp, i32p, i32p, ctypes.c_int32, ctypes.c_int32, vp, vp]
         lib.chess_workspace_init.argtypes = [vp, vp, vp]
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_entropy.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, vp, vp]
@@ -188,6 +189,10 @@ class Chess:
     def summarize_tail(self, k_pool, block_table, seq_lens, summaries):
         self._check(self.lib.chess_summarize_tail(self._h, _ptr(k_pool), _ptr(block_table), _ptr(seq_lens),
                                                   seq_lens.shape[0], _ptr(summaries), _stream()))
+
+    def summarize_recent(self, k_pool, block_table, seq_lens, recent_pages: int, summaries):
+        self._check(self.lib.chess_summarize_recent(self._h, _ptr(k_pool), _ptr(block_table), _ptr(seq_lens),
+                                                    seq_lens.shape[0], recent_pages, _ptr(summaries), _stream()))
 
     def select(self, q, summaries, seq_lens, plan: SelectPlan, page_ids, n_selected, workspace):
         p = plan._c()

@@ -219,14 +219,14 @@ int chess_workspace_bytes(const chess_ctx* ctx, size_t* bytes)
 }
 
 static int summarize_common(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
-                            int32_t batch, const int32_t* from_page, bool tail, void* summaries, void* stream)
+                            int32_t batch, const int32_t* from_page, int recent, void* summaries, void* stream)
 {
     if (!ctx || !k_pool || !block_table || !seq_lens || !summaries) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(summaries)) & 15) return CHESS_EINVAL;
     char* sb = static_cast<char*>(summaries);
     hipError_t e = chess::launch_summarize(ctx, static_cast<const uint16_t*>(k_pool), block_table, seq_lens, batch,
-                                           from_page, tail, reinterpret_cast<float*>(sb + ctx->page_off),
+                                           from_page, recent, reinterpret_cast<float*>(sb + ctx->page_off),
                                            reinterpret_cast<float*>(sb + ctx->chunk_off),
                                            reinterpret_cast<float*>(sb + ctx->grid_off), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
@@ -235,13 +235,20 @@ static int summarize_common(chess_ctx* ctx, const void* k_pool, const int32_t* b
 int chess_summarize(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
                     int32_t batch, const int32_t* from_page, void* summaries, void* stream)
 {
-    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, from_page, false, summaries, stream);
+    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, from_page, 0, summaries, stream);
 }
 
 int chess_summarize_tail(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
                          int32_t batch, void* summaries, void* stream)
 {
-    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, nullptr, true, summaries, stream);
+    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, nullptr, 1, summaries, stream);
+}
+
+int chess_summarize_recent(chess_ctx* ctx, const void* k_pool, const int32_t* block_table, const int32_t* seq_lens,
+                           int32_t batch, int32_t recent_pages, void* summaries, void* stream)
+{
+    if (recent_pages < 1) return CHESS_EINVAL;
+    return summarize_common(ctx, k_pool, block_table, seq_lens, batch, nullptr, recent_pages, summaries, stream);
 }
 
 int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream)

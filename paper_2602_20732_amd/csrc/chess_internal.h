@@ -125,7 +125,7 @@ inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t
 
 // Launchers (each returns a hipError_t from the launch).
 hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_t* block_table,
-                            const int32_t* seq_lens, int batch, const int32_t* from_page, bool tail_only,
+                            const int32_t* seq_lens, int batch, const int32_t* from_page, int recent,
                             float* pages, float* chunks, float* grids, hipStream_t stream);
 
 hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,

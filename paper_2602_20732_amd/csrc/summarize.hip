@@ -6,6 +6,8 @@
 // 256-byte rows.  Each lane adds its 8 columns over the tokens in token order in fp64, so the sum
 // is the same number whatever the launch shape; the mean is rounded to fp32 once.  Page vectors of
 // the grid stay in LDS, chunk and grid means are formed from them without re-reading HBM.
+#include <algorithm>
+
 #include "chess_internal.h"
 
 namespace chess {
@@ -25,7 +27,7 @@ template <int B>
 __global__ __launch_bounds__(256) void summarize_kernel(const uint16_t* __restrict__ k_pool,
                                                         const int32_t* __restrict__ block_table,
                                                         const int32_t* __restrict__ seq_lens,
-                                                        const int32_t* __restrict__ from_page, int tail_only, Geom g,
+                                                        const int32_t* __restrict__ from_page, int recent, Geom g,
                                                         float* __restrict__ pages, float* __restrict__ chunks,
                                                         float* __restrict__ grids)
 {
@@ -35,9 +37,10 @@ __global__ __launch_bounds__(256) void summarize_kernel(const uint16_t* __restri
     if (L <= 0) return;
     const int P = (L + B - 1) / B;
     const int nc = (P + g.n_c - 1) / g.n_c, ng = (nc + g.n_g - 1) / g.n_g;
-    const int gk = tail_only ? ng - 1 : (int)blockIdx.x;
-    if (gk >= ng) return;
-    int fp = tail_only ? P - 1 : (from_page ? from_page[b] : 0);
+    // recent > 0: only the last `recent` pages are new; the grid's workgroups count back from the last grid
+    const int gk = recent > 0 ? ng - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    if (gk >= ng || gk < 0) return;
+    int fp = recent > 0 ? P - recent : (from_page ? from_page[b] : 0);
     fp = fp < 0 ? 0 : fp;
     const int ppg = g.n_c * g.n_g;
     if (gk < fp / ppg) return;                        // every unit of this grid is older than from_page
@@ -113,12 +116,14 @@ __global__ __launch_bounds__(256) void summarize_kernel(const uint16_t* __restri
 }
 
 hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_t* block_table,
-                            const int32_t* seq_lens, int batch, const int32_t* from_page, bool tail_only,
+                            const int32_t* seq_lens, int batch, const int32_t* from_page, int recent,
                             float* pages, float* chunks, float* grids, hipStream_t stream)
 {
     const Geom& g = ctx->geom;
     const size_t lds = (size_t)(g.n_c * g.n_g + g.n_g) * kHeadDim * sizeof(float);
-    const dim3 grid(tail_only ? 1 : g.max_grids, g.n_kv_heads, batch), block(256);
+    const int ppg = g.n_c * g.n_g;
+    const int span = recent > 0 ? std::min(g.max_grids, (recent + ppg - 2) / ppg + 1) : g.max_grids;   // grids `recent` pages can touch
+    const dim3 grid(span, g.n_kv_heads, batch), block(256);
     auto kern = g.page_size == 16 ? summarize_kernel<16> : summarize_kernel<32>;
     if (lds > 64 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -126,7 +131,7 @@ hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_
         if (e != hipSuccess) return e;
     }
     return launch(kern, grid, block, lds, stream, k_pool, block_table, seq_lens,
-                        from_page, tail_only ? 1 : 0, g, pages, chunks, grids);
+                        from_page, recent, g, pages, chunks, grids);
 }
 
 }  // namespace chess

@@ -287,6 +287,32 @@ def test_incremental_and_tail_summaries_match_full_pass():
             assert torch.equal(a[i, :, :n], b[i, :, :n])
 
 
+@pytest.mark.parametrize("recent", [1, 2, 5, 17, 40, 1000])
+def test_recent_pages_catch_up_matches_full_pass(recent):
+    """chess_summarize_recent on summaries that were current `gained` pages ago (the pages since hold junk, and so do
+    their chunks and grids): the result equals a full pass.  recent may exceed what the sequence gained or has."""
+    sp = RAGGED
+    lens1 = [3000, 1239, 641, 17, 3]
+    gained = [min(recent, -(-n // sp.page_size)) for n in lens1]
+    lens0 = [max(0, (-(-n // sp.page_size) - g) * sp.page_size) for n, g in zip(lens1, gained)]   # whole pages earlier
+    wl = to_device(workload.generate(sp, 77, seq_lens=lens1))
+    lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+    full, inc = lib.new_summaries(), lib.new_summaries()
+    lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, full)
+    inc.view(torch.float32).fill_(123.0)
+    lib.summarize(wl.k_pool, wl.block_table, torch.tensor(lens0, dtype=torch.int32, device="cuda"), inc)
+    lib.summarize_recent(wl.k_pool, wl.block_table, wl.seq_lens, recent, inc)
+    torch.cuda.synchronize()
+    B, Nc, Ng = sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    for a, b, per in zip(lib.summary_views(full), lib.summary_views(inc), (1, Nc, Nc * Ng)):
+        for i, L in enumerate(lens1):
+            n = -(-(-(-L // B)) // per)
+            assert torch.equal(a[i, :, :n], b[i, :, :n]), (recent, i, per)
+    with pytest.raises(pk.ChessError):
+        lib.summarize_recent(wl.k_pool, wl.block_table, wl.seq_lens, 0, inc)
+    lib.close()
+
+
 def test_split_count_invariance_and_determinism():
     sp = workload.spec("cfg2", scale=1 / 4)
     wl = to_device(workload.generate(sp, workload.default_seed("cfg2")))
