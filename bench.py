@@ -11,7 +11,11 @@ than the last-level cache); the K timed steps are captured once as a HIP graph a
 
 Prints ONE JSON line: the step time in microseconds (the metric), the dominant kernel's HBM roofline
 from HIP-event timing of that kernel alone, the dense full-KV kernel of this library on the same inputs,
-and the CPU oracle timed on the host cores for the same step.
+and the CPU oracle timed on the host cores for the same step.  Further objects on the same line, each timed the
+same way: `us_per_step_spread` (p10 / median / p90 over separately timed replays), `summarize_full_pass`,
+`shared_scope` (the paper's model-wide selection over --shared-layers layers), `steady_state` (reuse and reselect
+steps of the paper's operating point), `trigger` (the Sec. 3.3 monitor), `selection_quality` (recall against the
+exact top-k; not a parity check).
 """
 from __future__ import annotations
 

@@ -8,7 +8,8 @@
  * C ABI.  Every data pointer is a DEVICE pointer owned by the caller unless it says "host".
  * The library never allocates or frees device memory; only chess_append_kv writes the K/V pools.  Every call is
  * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream), does no
- * host synchronisation, and can be captured in a HIP graph.
+ * host synchronisation, and can be captured in a HIP graph.  A context caches launch shapes: calls on one
+ * context must not run concurrently from several host threads (use one context per thread).
  *
  * Return value: 0 on success, a negative CHESS_E* code on misuse the host can detect (null
  * pointers, shapes outside the configuration).  Data the host cannot see (sequence lengths,
