@@ -149,3 +149,71 @@ def test_list_reuse_between_reselections_follows_the_tail():
     assert int(n9.max()) == 9 and int(ids9.max()) < -(-int(lens.max()) // B)
     small.close()
     lib.close()
+
+
+def test_the_decode_loop_in_a_hip_graph_replays_like_eager():
+    """One iteration of the loop around the step -- anchors + model-wide selection, then per step: append with list
+    extension, sparse attention, entropy of a logits row, trigger update -- captured once and replayed with eager
+    work and synchronisations between the replays; every replay must give what the same calls give eagerly."""
+    sp = workload.WorkloadSpec("loop", 2, (0, 2100), 8, 2, 16, ("fixed", 128), (2, 2), 1, 2, budget_pages=5,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    start = [2000, 900]
+    full = to_device(workload.generate(sp, 31, seq_lens=[n + 40 for n in start]))
+    room = 1 + 5 + 2 + 4
+    lib = pk.Chess(config_of(sp, max_selected=room))
+    plan = gpu_plan(plan_of(sp))
+    H = sp.n_kv_heads
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    logits = (torch.randn((2, 4096), device="cuda", generator=gen) * 3).to(torch.bfloat16)
+    rows_k = torch.randn((2, H, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    rows_v = torch.randn((2, H, 128), device="cuda", generator=gen).to(torch.bfloat16)
+
+    def fresh_state():
+        st = dict(k=full.k_pool.clone(), v=full.v_pool.clone(), lens=torch.tensor(start, dtype=torch.int32, device="cuda"),
+                  summ=lib.new_summaries(), ws=lib.new_workspace(), anc=torch.empty((2, H, 128), device="cuda"),
+                  ids=torch.full((2, H, room), -7, dtype=torch.int32, device="cuda"),
+                  nsel=torch.full((2, H), -7, dtype=torch.int32, device="cuda"),
+                  out=torch.full((2, sp.n_q_heads, 128), float("nan"), device="cuda"), ent=torch.zeros((2,), device="cuda"),
+                  hist=torch.zeros((2, 2), device="cuda"), count=torch.zeros((2,), dtype=torch.int32, device="cuda"),
+                  fire=torch.full((2,), -1, dtype=torch.int32, device="cuda"), stats=torch.zeros((2, 2), dtype=torch.float64, device="cuda"))
+        lib.summarize(st["k"], full.block_table, st["lens"], st["summ"])
+        return st
+
+    def iteration(st):
+        lib.anchor(st["summ"], st["lens"], 2, st["anc"])
+        lib.select_shared([st["anc"]], [st["summ"]], st["lens"], plan, st["ids"], st["nsel"], st["ws"])
+        lib.append_kv(rows_k, rows_v, st["k"], st["v"], full.block_table, st["lens"], st["ids"], st["nsel"])
+        st["lens"].add_(1)
+        lib.sparse_decode(full.q, st["k"], st["v"], full.block_table, st["lens"], st["ids"], st["nsel"], st["out"], st["ws"])
+        lib.entropy(logits, st["ent"], st["ws"])
+        lib.trigger_update(st["ent"], 2, 0.5, 1e9, st["hist"], st["count"], st["fire"], st["stats"])
+
+    # eager: three iterations (the sequences grow by one token each), results after each
+    e = fresh_state()
+    want = []
+    for _ in range(3):
+        iteration(e)
+        torch.cuda.synchronize()
+        want.append({k: e[k].clone() for k in ("ids", "nsel", "out", "ent", "fire", "stats", "lens", "count")})
+    assert lib.workspace_error(e["ws"]) == 0
+    assert int(want[1]["fire"].sum()) == 2, "the trigger must fire when its page of two steps completes"
+
+    g = fresh_state()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        warm = fresh_state()
+        iteration(warm)                                    # every kernel has run once before the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            iteration(g)
+        for rep in range(3):
+            graph.replay()
+            stream.synchronize()
+            for k, v in want[rep].items():
+                assert torch.equal(g[k], v), (rep, k)
+            scratch = torch.empty_like(g["out"])           # eager work between the replays
+            lib.dense_decode(full.q, g["k"], g["v"], full.block_table, g["lens"], scratch, g["ws"])
+            stream.synchronize()
+    assert lib.workspace_error(g["ws"]) == 0
+    lib.close()
