@@ -201,6 +201,20 @@ int chess_extend_window(chess_ctx* ctx, const int32_t* seq_lens, int32_t batch, 
                         void* stream);
 
 /*
+ * The step between reselections (Sec. 3.3) as ONE launch: what chess_append_kv (with the lists) followed by
+ * chess_sparse_decode on the lengths + 1 computes, with the same results bit for bit.  The new token's rows go from
+ * k_new / v_new straight into the attention (they do not make a round trip through the pools); the last workgroup of
+ * a (sequence, KV head) to finish stores them in the pools and, when the token opens a page, adds the page to
+ * the list.  seq_lens: the lengths BEFORE the token (not changed; the caller adds one afterwards).  A sequence with no
+ * room left is attended as it is.  Precondition: every list ends with the tail page of seq_lens (as a selection on
+ * these lengths, chess_append_kv with the lists, chess_extend_window or this call leave it); an empty list
+ * belongs to an empty sequence.  Arguments and errors as for the two calls.
+ */
+int chess_reuse_step(chess_ctx* ctx, const void* q, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                     const int32_t* block_table, const int32_t* seq_lens, int32_t* page_ids, int32_t* n_selected,
+                     int32_t batch, float* out, void* workspace, void* stream);
+
+/*
  * The quality monitor of Sec. 3.3, first half: the entropy (nats) of the output distribution of one decode step,
  * H[b] = -sum_v p_v log p_v with p = softmax(logits[b]).  logits: device, bf16 [batch][row_stride], the first
  * `vocab` entries of a row are used (-inf entries count as probability 0); 16-byte aligned, row_stride a multiple

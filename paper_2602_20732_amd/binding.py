@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
-           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_extend_window", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
+           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
            "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
@@ -97,6 +97,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_entropy.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, vp, vp]
         lib.chess_trigger_update.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double, vp, i32p, i32p, vp, vp]
+        lib.chess_reuse_step.argtypes = [vp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_extend_window.argtypes = [vp, i32p, ctypes.c_int32, i32p, i32p, vp]
         lib.chess_append_kv.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, i32p, i32p, vp]
         lib.chess_anchor.argtypes = [vp, ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(vp), vp]
@@ -207,6 +208,11 @@ class Chess:
                        stats=None):
         self._check(self.lib.chess_trigger_update(self._h, _ptr(entropy), entropy.shape[0], page_steps, tau_entropy,
                                                   tau_variance, _ptr(history), _ptr(count), _ptr(fire), _ptr(stats), _stream()))
+
+    def reuse_step(self, q, k_new, v_new, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, out, workspace):
+        self._check(self.lib.chess_reuse_step(self._h, _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(k_pool), _ptr(v_pool),
+                                              _ptr(block_table), _ptr(seq_lens), _ptr(page_ids), _ptr(n_selected),
+                                              seq_lens.shape[0], _ptr(out), _ptr(workspace), _stream()))
 
     def extend_window(self, seq_lens, page_ids, n_selected):
         self._check(self.lib.chess_extend_window(self._h, _ptr(seq_lens), seq_lens.shape[0], _ptr(page_ids), _ptr(n_selected),

@@ -343,6 +343,30 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
+int chess_reuse_step(chess_ctx* ctx, const void* q, const void* k_new, const void* v_new, void* k_pool, void* v_pool,
+                     const int32_t* block_table, const int32_t* seq_lens, int32_t* page_ids, int32_t* n_selected,
+                     int32_t batch, float* out, void* workspace, void* stream)
+{
+    if (!ctx || !q || !k_new || !v_new || !k_pool || !v_pool || !block_table || !seq_lens || !page_ids || !n_selected ||
+        !out || !workspace)
+        return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(q) |
+         reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) | reinterpret_cast<uintptr_t>(out) |
+         reinterpret_cast<uintptr_t>(workspace)) & 15)
+        return CHESS_EINVAL;
+    SplitShape sh = choose_splits(ctx, batch, ctx->geom.max_sel, true);
+    if (sh.waves != 4) sh.waves = 4;
+    char* wb = static_cast<char*>(workspace);
+    hipError_t e = chess::launch_reuse(ctx, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_new),
+                                       static_cast<const uint16_t*>(v_new), static_cast<uint16_t*>(k_pool),
+                                       static_cast<uint16_t*>(v_pool), block_table, seq_lens, page_ids, n_selected, batch,
+                                       sh.n_splits, out, reinterpret_cast<float*>(wb + ctx->ws_acc_off),
+                                       reinterpret_cast<float*>(wb + ctx->ws_ml_off),
+                                       reinterpret_cast<int32_t*>(wb + ctx->ws_cnt_off), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
 int chess_extend_window(chess_ctx* ctx, const int32_t* seq_lens, int32_t batch, int32_t* page_ids, int32_t* n_selected,
                         void* stream)
 {

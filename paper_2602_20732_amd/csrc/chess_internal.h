@@ -181,6 +181,10 @@ hipError_t decode_occupancy(int page_size, int waves, int group, int* blocks_per
 hipError_t launch_append(chess_ctx* ctx, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool, uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, int batch, int32_t* page_ids,
                          int32_t* n_selected, hipStream_t stream);
+hipError_t launch_reuse(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
+                        uint16_t* v_pool, const int32_t* block_table, const int32_t* seq_lens, int32_t* page_ids,
+                        int32_t* n_selected, int batch, int n_splits, float* out, float* ws_acc, float* ws_ml,
+                        int32_t* arrivals, hipStream_t stream);
 hipError_t launch_extend(chess_ctx* ctx, const int32_t* seq_lens, int batch, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 constexpr int kEntMaxSplits = 32;

@@ -54,6 +54,95 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
     merge_splits<NW>(G, n_splits, row, out_rows, ws_acc, ws_ml);
 }
 
+// The step between reselections (Sec. 3.3) in one launch: attention over the kept list for the sequence WITH the
+// token that is being appended, whose key / value rows are not in the pools yet.  Every split takes them from
+// k_new / v_new straight into the operands of the tile that holds the tail page; the last split of a (sequence,
+// KV head) to finish -- after which nobody reads the tail page or the list any more -- writes the rows to the pools
+// and, when the token opens a new page, the page to the list.  The lists must end with the tail page of seq_lens
+// (as a selection on these lengths, chess_append_kv with the lists, or this call leave them).
+// grid = (n_splits, H_kv, batch), four waves.
+template <int B>
+__global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
+                                                    const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_pool,
+                                                    uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
+                                                    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ page_ids,
+                                                    int32_t* __restrict__ n_selected, Geom g, float scale_log2, int n_splits,
+                                                    float* __restrict__ out, float* __restrict__ ws_acc,
+                                                    float* __restrict__ ws_ml, int32_t* __restrict__ arrivals)
+{
+    constexpr int PPT = 32 / B, NW = 4;
+    extern __shared__ float lds_f[];
+    __shared__ int lds_last;
+    DecodeLds<NW> lds(lds_f, g.group);
+
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m16 = lane & 15, grp = lane >> 4;
+    const int G = g.group, H = g.n_kv_heads;
+    const size_t row = (size_t)b * H + h;
+    int32_t* ids = page_ids + row * g.max_sel;
+    const int32_t* bt_row = block_table + (size_t)b * g.max_pages;
+    const int stride = n_splits * NW;
+    const int t = split + n_splits * wave;
+    int raw_cur[PPT], raw_nxt[PPT];
+    const int L_before = seq_lens[b];
+    const int n_raw = n_selected[row];
+    fetch_ids<B, true>(raw_cur, t, ids, g.max_sel);
+    fetch_ids<B, true>(raw_nxt, t + stride, ids, g.max_sel);
+    NewToken<B> nt;
+    nt.load(k_new + row * kHeadDim, v_new + row * kHeadDim, m16, grp);
+
+    const bool room = L_before >= 0 && L_before < g.max_pages * B;
+    const int L = room ? L_before + 1 : min(max(L_before, 0), g.max_pages * B);
+    const int P = (L + B - 1) / B;
+    const int n_stored = min(max(n_raw, 0), g.max_sel);
+    const bool grow = room && L_before % B == 0 && n_stored < g.max_sel;     // the token opens a page
+    const int n_pages = P == 0 ? 0 : n_stored + (grow ? 1 : 0);
+    const int n_tiles = (n_pages + PPT - 1) / PPT;
+    // the tail page is the list's last entry
+    nt.tile = room && n_pages > 0 ? (n_pages - 1) / PPT : -1;
+    nt.T = ((n_pages - 1) % PPT) * B + L_before % B;
+
+    WaveAcc<B> acc;
+    acc.init(q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim, G, m16, grp);
+    run_tiles_with<B, true, false, true>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool,
+                                         v_pool, H, h, L, P, scale_log2, m16, grp, nt, n_stored);
+
+    float* out_rows = out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
+    const bool split_up = combine_waves<NW>(acc.o, acc.m_run, acc.l_run, lds, G, n_splits, split, row, out_rows, ws_acc, ws_ml);
+    if (split_up && !arrive_last(arrivals + row, n_splits, &lds_last)) return;
+    // every split of the row is past its reads: the token and the page go where the next step looks for them
+    if (room) {
+        const int tid = threadIdx.x;
+        if (tid < kHeadDim) {
+            const int64_t phys = bt_row[L_before / B];
+            const size_t blk = ((size_t)phys * H + h) * B * kHeadDim;
+            const int tok = L_before % B;
+            k_pool[blk + (size_t)tok * kHeadDim + tid] = k_new[row * kHeadDim + tid];
+            v_pool[blk + (size_t)tid * B + tok] = v_new[row * kHeadDim + tid];
+        }
+        if (grow && tid == 0) {
+            ids[n_stored] = P - 1;
+            n_selected[row] = n_stored + 1;
+        }
+    }
+    if (split_up) merge_splits<NW>(G, n_splits, row, out_rows, ws_acc, ws_ml);
+}
+
+hipError_t launch_reuse(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new, uint16_t* k_pool,
+                        uint16_t* v_pool, const int32_t* block_table, const int32_t* seq_lens, int32_t* page_ids,
+                        int32_t* n_selected, int batch, int n_splits, float* out, float* ws_acc, float* ws_ml,
+                        int32_t* arrivals, hipStream_t stream)
+{
+    const Geom& g = ctx->geom;
+    const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
+    const dim3 grid(n_splits, g.n_kv_heads, batch), block(256);
+    const size_t lds = (size_t)(4 * g.group * kHeadDim + 2 * 4 * g.group) * sizeof(float);
+    auto kern = g.page_size == 16 ? reuse_kernel<16> : reuse_kernel<32>;
+    return launch(kern, grid, block, lds, stream, q, k_new, v_new, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected,
+                  g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
+}
+
 hipError_t launch_decode(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_pool, const uint16_t* v_pool,
                          const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
                          const int32_t* n_selected, int batch, int n_splits, int waves, float* out,

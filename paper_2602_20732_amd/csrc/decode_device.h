@@ -105,13 +105,14 @@ struct PageRef {
 
 template <int B>
 __device__ __forceinline__ void lookup_pages(PageRef<B>& r, int t, int n_pages, const int (&raw)[32 / B],
-                                             const int32_t* bt_row, int L, int P)
+                                             const int32_t* bt_row, int L, int P, int n_stored)
 {
     constexpr int PPT = 32 / B;
 #pragma unroll
     for (int s = 0; s < PPT; ++s) {
         const bool ok = t * PPT + s < n_pages;
         int lp = ok ? raw[s] : raw[0];                            // unused slot: alias the tile's first page
+        if (ok && t * PPT + s >= n_stored) lp = P - 1;            // the page the list gains in this launch: the tail page
         lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
         r.pp[s] = bt_row[lp];
         r.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
@@ -147,6 +148,47 @@ __device__ __forceinline__ void load_rows(Tile<B>& tl, const PageRef<B>& r, cons
         for (int blk = 0; blk < 8; ++blk) tl.v[blk] = *reinterpret_cast<const uint4*>(base + (size_t)blk * 16 * B);
     }
 }
+
+// The token a launch appends (its rows are not in the pools yet): this lane's parts of its key and value rows, and
+// where it sits.  `put` replaces the token's slot in the operands of the tile that holds the tail page.
+template <int B>
+struct NewToken {
+    uint4 k[4];          // key row, d = 32 st + 8 grp .. + 7
+    uint16_t v[8];       // value row, d = 16 blk + m16
+    int tile, T;         // tile of the list that holds the tail page (-1: nothing is appended), token slot in it
+    __device__ __forceinline__ void load(const uint16_t* k_row, const uint16_t* v_row, int m16, int grp)
+    {
+        const uint4* ks = reinterpret_cast<const uint4*>(k_row) + grp;
+#pragma unroll
+        for (int st = 0; st < 4; ++st) k[st] = ks[st * 4];
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) v[blk] = v_row[16 * blk + m16];
+    }
+    __device__ __forceinline__ void put(Tile<B>& tl, int m16, int grp) const
+    {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const bool mine = 8 * (m16 >> 2) + 4 * c + (m16 & 3) == T;
+#pragma unroll
+            for (int st = 0; st < 4; ++st) {
+                tl.k[c][st].x = mine ? k[st].x : tl.k[c][st].x; tl.k[c][st].y = mine ? k[st].y : tl.k[c][st].y;
+                tl.k[c][st].z = mine ? k[st].z : tl.k[c][st].z; tl.k[c][st].w = mine ? k[st].w : tl.k[c][st].w;
+            }
+        }
+        const bool mine = (T >> 3) == grp;
+        const int e = T & 7;
+#pragma unroll
+        for (int blk = 0; blk < 8; ++blk) {
+            uint32_t w[4] = {tl.v[blk].x, tl.v[blk].y, tl.v[blk].z, tl.v[blk].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t lo = (w[i] & 0xffff0000u) | v[blk], hi = (w[i] & 0x0000ffffu) | ((uint32_t)v[blk] << 16);
+                w[i] = (mine && (e >> 1) == i) ? ((e & 1) ? hi : lo) : w[i];
+            }
+            tl.v[blk] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+};
 
 // Online-softmax state of one wave: all G heads of one KV head.
 template <int B>
@@ -237,12 +279,14 @@ struct WaveAcc {
 // The next tile is always requested before the current one is computed, in the same straight-line block, so
 // the compiler waits only for the older loads (a load under its own branch would force a wait for everything
 // outstanding).  After the last tile the "next" request repeats the current tile: it hits in cache and is dropped.
-template <int B, bool kList, bool kPhysList>
-__device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
+// nt (may be null): a token appended by this launch; n_stored: list entries that are in memory (the list may gain the
+// tail page in this launch: entries from n_stored on are that page).
+template <int B, bool kList, bool kPhysList, bool kAppend>
+__device__ __forceinline__ void run_tiles_with(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
                                           int (&raw_cur)[32 / B], int (&raw_nxt)[32 / B], const int32_t* ids, int max_sel,
                                           const int32_t* bt_row, const int32_t* phys_list, const uint16_t* k_pool,
                                           const uint16_t* v_pool, int H, int h, int L, int P, float scale_log2, int m16,
-                                          int grp)
+                                          int grp, const NewToken<B>& nt, int n_stored)
 {
     constexpr int PPT = 32 / B;
     if constexpr (!kPhysList) {
@@ -250,8 +294,8 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
             // block-table entries run one tile ahead of the rows, page numbers one tile ahead of those
             PageRef<B> pc, pn, pnn;
             int raw_nn[PPT];
-            lookup_pages<B>(pc, t, n_pages, raw_cur, bt_row, L, P);
-            lookup_pages<B>(pn, t + stride, n_pages, raw_nxt, bt_row, L, P);
+            lookup_pages<B>(pc, t, n_pages, raw_cur, bt_row, L, P, n_stored);
+            lookup_pages<B>(pn, t + stride, n_pages, raw_nxt, bt_row, L, P, n_stored);
             fetch_ids<B, kList>(raw_nn, t + 2 * stride, ids, max_sel);
             Tile<B> cur, nxt;
             load_rows<B>(cur, pc, k_pool, v_pool, H, h, m16, grp);
@@ -259,8 +303,9 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
                 const bool more = t + stride < n_tiles;
                 if (more) pc = pn;                                // after the last tile the request repeats it
                 load_rows<B>(nxt, pc, k_pool, v_pool, H, h, m16, grp);
-                lookup_pages<B>(pnn, t + 2 * stride, n_pages, raw_nn, bt_row, L, P);
+                lookup_pages<B>(pnn, t + 2 * stride, n_pages, raw_nn, bt_row, L, P, n_stored);
                 fetch_ids<B, kList>(raw_nn, t + 3 * stride, ids, max_sel);
+                if (kAppend && t == nt.tile) nt.put(cur, m16, grp);
                 acc.process(cur, scale_log2, grp);
                 cur = nxt;
                 pn = pnn;
@@ -288,6 +333,19 @@ __device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, in
     }
     acc.l_run += __shfl_xor(acc.l_run, 16);
     acc.l_run += __shfl_xor(acc.l_run, 32);
+}
+
+template <int B, bool kList, bool kPhysList>
+__device__ __forceinline__ void run_tiles(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
+                                          int (&raw_cur)[32 / B], int (&raw_nxt)[32 / B], const int32_t* ids, int max_sel,
+                                          const int32_t* bt_row, const int32_t* phys_list, const uint16_t* k_pool,
+                                          const uint16_t* v_pool, int H, int h, int L, int P, float scale_log2, int m16,
+                                          int grp)
+{
+    NewToken<B> none;
+    none.tile = -1;
+    run_tiles_with<B, kList, kPhysList, false>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, max_sel, bt_row,
+                                               phys_list, k_pool, v_pool, H, h, L, P, scale_log2, m16, grp, none, 1 << 30);
 }
 
 // LDS the combine below needs, in floats: [NW][hs][128] accumulators, [NW][hs] maxima, [NW][hs] sums, where the

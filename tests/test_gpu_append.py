@@ -217,3 +217,65 @@ def test_the_decode_loop_in_a_hip_graph_replays_like_eager():
             stream.synchronize()
     assert lib.workspace_error(g["ws"]) == 0
     lib.close()
+
+
+@pytest.mark.parametrize("page,splits", [(16, 0), (16, 1), (16, 3), (32, 0), (32, 2)])
+def test_reuse_step_equals_append_then_attention(page, splits):
+    """chess_reuse_step against chess_append_kv (with the lists) + chess_sparse_decode on copies of the same state,
+    step after step across page boundaries (one sequence starts empty, one is full): outputs, lists and pools must be
+    identical bit for bit; and the first and last steps against the oracle."""
+    sp = workload.WorkloadSpec("reuse1", 4, (0, 1408), 8, 2, page, ("fixed", 128), (2, 2), 1, 2, budget_pages=5,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    start, steps = [1200, 700 - 700 % page, 0, 1408], 2 * page + 3
+    lens_full = [min(n + steps, 1408) for n in start]
+    full = to_device(workload.generate(sp, 41, seq_lens=lens_full))
+    room = 1 + 5 + 2 + 4
+    lib = pk.Chess(config_of(sp, max_selected=room))
+    lib.debug_force_splits(splits, 4)
+    plan = gpu_plan(plan_of(sp))
+    lens = torch.tensor(start, dtype=torch.int32, device="cuda")
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(full.k_pool, full.block_table, lens, summ)
+    ids = torch.full((4, sp.n_kv_heads, room), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((4, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    lib.select(full.q, summ, lens, plan, ids, nsel, ws)
+    torch.cuda.synchronize()
+    bt = full.block_table
+    B = page
+    # state A: two calls; state B: one launch
+    A = dict(k=full.k_pool.clone(), v=full.v_pool.clone(), ids=ids.clone(), nsel=nsel.clone(), lens=lens.clone(),
+             out=torch.full((4, sp.n_q_heads, 128), float("nan"), device="cuda"))
+    Bs = dict(k=full.k_pool.clone(), v=full.v_pool.clone(), ids=ids.clone(), nsel=nsel.clone(), lens=lens.clone(),
+              out=torch.full((4, sp.n_q_heads, 128), float("nan"), device="cuda"))
+    for st in (A, Bs):                                     # nothing behind the current lengths is valid yet
+        for b, n in enumerate(start):
+            for j in range(n // B, -(-lens_full[b] // B)):
+                phys = int(bt[b, j]); t0 = max(n - j * B, 0)
+                st["k"][phys, :, t0:, :] = float("nan"); st["v"][phys, :, :, t0:] = float("nan")
+    gen = torch.Generator(device="cuda").manual_seed(9)
+    for step in range(steps):
+        rk = torch.randn((4, sp.n_kv_heads, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        rv = torch.randn((4, sp.n_kv_heads, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        lib.append_kv(rk, rv, A["k"], A["v"], bt, A["lens"], A["ids"], A["nsel"])
+        A["lens"] = torch.clamp(A["lens"] + 1, max=1408)
+        lib.sparse_decode(full.q, A["k"], A["v"], bt, A["lens"], A["ids"], A["nsel"], A["out"], ws)
+        lib.reuse_step(full.q, rk, rv, Bs["k"], Bs["v"], bt, Bs["lens"], Bs["ids"], Bs["nsel"], Bs["out"], ws)
+        Bs["lens"] = torch.clamp(Bs["lens"] + 1, max=1408)
+        torch.cuda.synchronize()
+        assert torch.equal(A["nsel"], Bs["nsel"]), step
+        live = torch.arange(room, device="cuda").view(1, 1, -1) < A["nsel"].unsqueeze(-1)
+        assert torch.equal(torch.where(live, A["ids"], -1), torch.where(live, Bs["ids"], -1)), step
+        assert torch.equal(A["out"], Bs["out"]), (step, (A["out"] - Bs["out"]).abs().max())
+        if step in (0, steps - 1):
+            for b in range(4):
+                P = -(-int(A["lens"][b]) // B)
+                for j in range(P):
+                    phys = int(bt[b, j]); n = min(B, int(A["lens"][b]) - j * B)
+                    assert torch.equal(A["k"][phys, :, :n].view(torch.int16), Bs["k"][phys, :, :n].view(torch.int16))
+                    assert torch.equal(A["v"][phys, :, :, :n].view(torch.int16), Bs["v"][phys, :, :, :n].view(torch.int16))
+            K, V, Q = workload.bf16_bits(Bs["k"].cpu()), workload.bf16_bits(Bs["v"].cpu()), workload.bf16_bits(full.q.cpu())
+            sl = Bs["lens"].cpu().numpy()
+            ref = oracle.attend(Q, K, V, bt.cpu().numpy(), sl, geom_of(sp), Bs["ids"].cpu().numpy(), Bs["nsel"].cpu().numpy())
+            assert np.abs(Bs["out"].cpu().numpy() - ref).max() <= 2e-3, step
+    assert int(Bs["nsel"][2, 0]) == -(-steps // B), "the sequence that started empty has all its pages in the list"
+    lib.close()
