@@ -99,8 +99,10 @@ __global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__
     const bool grow = room && L_before % B == 0 && n_stored < g.max_sel;     // the token opens a page
     const int n_pages = P == 0 ? 0 : n_stored + (grow ? 1 : 0);
     const int n_tiles = (n_pages + PPT - 1) / PPT;
-    // the tail page is the list's last entry
-    nt.tile = room && n_pages > 0 ? (n_pages - 1) / PPT : -1;
+    // the tail page is the list's last entry -- unless the token opens a page and the row has no room for it: then
+    // (and in the steps after: run_tiles_with looks at the entry) the token is stored but not attended, as with
+    // chess_append_kv + chess_sparse_decode
+    nt.tile = room && n_pages > 0 && (grow || L_before % B != 0) ? (n_pages - 1) / PPT : -1;
     nt.T = ((n_pages - 1) % PPT) * B + L_before % B;
 
     WaveAcc<B> acc;

@@ -35,6 +35,7 @@ struct Tile {
     uint4 k[2][4];      // [product c][d step]
     uint4 v[8];         // [16-row block of d]
     int ntok[32 / B];   // valid tokens of each page slot of the tile (0 = slot unused)
+    int lp[32 / B];     // logical page of each slot (kept by the block-table path only)
 };
 
 // The logical page numbers of tile t as stored in the list (speculative: the index is clamped into the
@@ -101,6 +102,7 @@ template <int B>
 struct PageRef {
     int pp[32 / B];     // physical pages (the same in every lane; made scalar when they are used)
     int ntok[32 / B];   // valid tokens of each page slot (0 = slot unused)
+    int lp[32 / B];     // logical pages
 };
 
 template <int B>
@@ -116,6 +118,7 @@ __device__ __forceinline__ void lookup_pages(PageRef<B>& r, int t, int n_pages, 
         lp = min(max(lp, 0), P - 1);                              // a bad id must not become a bad address
         r.pp[s] = bt_row[lp];
         r.ntok[s] = ok ? (lp == P - 1 ? L - lp * B : B) : 0;
+        r.lp[s] = ok ? lp : -1;
     }
 }
 
@@ -129,6 +132,7 @@ __device__ __forceinline__ void load_rows(Tile<B>& tl, const PageRef<B>& r, cons
     for (int s = 0; s < PPT; ++s) {
         phys[s] = __builtin_amdgcn_readfirstlane(r.pp[s]);
         tl.ntok[s] = r.ntok[s];
+        tl.lp[s] = r.lp[s];
     }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
@@ -305,7 +309,10 @@ __device__ __forceinline__ void run_tiles_with(WaveAcc<B>& acc, int t, int strid
                 load_rows<B>(nxt, pc, k_pool, v_pool, H, h, m16, grp);
                 lookup_pages<B>(pnn, t + 2 * stride, n_pages, raw_nn, bt_row, L, P, n_stored);
                 fetch_ids<B, kList>(raw_nn, t + 3 * stride, ids, max_sel);
-                if (kAppend && t == nt.tile) nt.put(cur, m16, grp);
+                // (the list's last entry is the tail page unless a row ran out of room: then the token is not attended)
+                // (no run-time index into the tile: it would move the tile to scratch memory)
+                const int lp_tail = (PPT == 1 || nt.T < B) ? cur.lp[0] : cur.lp[PPT - 1];
+                if (kAppend && t == nt.tile && lp_tail == P - 1) nt.put(cur, m16, grp);
                 acc.process(cur, scale_log2, grp);
                 cur = nxt;
                 pn = pnn;

@@ -279,3 +279,50 @@ def test_reuse_step_equals_append_then_attention(page, splits):
             assert np.abs(Bs["out"].cpu().numpy() - ref).max() <= 2e-3, step
     assert int(Bs["nsel"][2, 0]) == -(-steps // B), "the sequence that started empty has all its pages in the list"
     lib.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_reuse_step_random_shapes(seed):
+    """Seeded draws of page size, heads, group, batch, lengths (incl. empty and nearly full sequences) and split count:
+    several chess_reuse_step launches against the two calls, bit for bit."""
+    rng = np.random.default_rng(4000 + seed)
+    B, H, G = int(rng.choice([16, 32])), int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4, 7, 16]))
+    batch, hi = int(rng.integers(1, 5)), int(rng.choice([256, 1024, 3072]))
+    steps = int(rng.integers(2, 2 * B + 2))
+    start = [int(rng.integers(0, hi - steps + 1)) for _ in range(batch)]
+    start[0] = hi - int(rng.integers(0, steps))                 # runs out of room on the way
+    s, w, k = int(rng.choice([0, 1, 2])), int(rng.choice([1, 2, 3])), int(rng.integers(1, 12))
+    sp = workload.WorkloadSpec(f"rr{seed}", batch, (0, hi), H * G, H, B, ("fixed", 96), (1, 1), s, w, budget_pages=k,
+                               pages_per_chunk=4, chunks_per_grid=4)
+    lens_full = [min(n + steps, hi) for n in start]
+    full = to_device(workload.generate(sp, 600 + seed, seq_lens=lens_full))
+    room = min(sp.max_pages, s + w + k + (steps // B + 2 if seed % 3 else 0))    # every third case: rows fill up
+    lib = pk.Chess(config_of(sp, max_selected=room))
+    lib.debug_force_splits(int(rng.choice([0, 0, 1, 2, 5])), 4)
+    print(f"[reuse rand {seed}] page {B} H {H} G {G} start {start} steps {steps} s {s} w {w} k {k} room {room}", flush=True)
+    lens = torch.tensor(start, dtype=torch.int32, device="cuda")
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(full.k_pool, full.block_table, lens, summ)
+    ids = torch.full((batch, H, room), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((batch, H), -7, dtype=torch.int32, device="cuda")
+    lib.select(full.q, summ, lens, gpu_plan(plan_of(sp)), ids, nsel, ws)
+    bt = full.block_table
+    mk = lambda: dict(k=full.k_pool.clone(), v=full.v_pool.clone(), ids=ids.clone(), nsel=nsel.clone(), lens=lens.clone(),
+                      out=torch.full((batch, sp.n_q_heads, 128), float("nan"), device="cuda"))
+    A, Bs = mk(), mk()
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    cap = sp.max_pages * B
+    for step in range(steps):
+        rk = torch.randn((batch, H, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        rv = torch.randn((batch, H, 128), device="cuda", generator=gen).to(torch.bfloat16)
+        lib.append_kv(rk, rv, A["k"], A["v"], bt, A["lens"], A["ids"], A["nsel"])
+        A["lens"] = torch.clamp(A["lens"] + 1, max=cap)
+        lib.sparse_decode(full.q, A["k"], A["v"], bt, A["lens"], A["ids"], A["nsel"], A["out"], ws)
+        lib.reuse_step(full.q, rk, rv, Bs["k"], Bs["v"], bt, Bs["lens"], Bs["ids"], Bs["nsel"], Bs["out"], ws)
+        Bs["lens"] = torch.clamp(Bs["lens"] + 1, max=cap)
+        torch.cuda.synchronize()
+        assert torch.equal(A["nsel"], Bs["nsel"]), step
+        live = torch.arange(room, device="cuda").view(1, 1, -1) < A["nsel"].unsqueeze(-1)
+        assert torch.equal(torch.where(live, A["ids"], -1), torch.where(live, Bs["ids"], -1)), step
+        assert torch.equal(A["out"], Bs["out"]), (step, (A["out"] - Bs["out"]).abs().max())
+    lib.close()
