@@ -238,6 +238,12 @@ int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t voc
 int chess_trigger_update(chess_ctx* ctx, const float* entropy, int32_t batch, int32_t page_steps, double tau_entropy,
                          double tau_variance, float* history, int32_t* count, int32_t* fire, double* stats, void* stream);
 
+/* chess_entropy and chess_trigger_update in one launch (same results): the thread that ends up with a sequence's
+ * entropy also updates that sequence's page statistics.  entropy (fp32 [batch]) is still written. */
+int chess_monitor_step(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride,
+                       int32_t page_steps, double tau_entropy, double tau_variance, float* entropy, float* history,
+                       int32_t* count, int32_t* fire, double* stats, void* workspace, void* stream);
+
 /*
  * Block-sparse decode attention over the listed pages, read in place (Sec. 4.3 takes a paged
  * decode kernel over page indices; App. B).  Per q head: softmax(sm_scale * q . K_t) weighted sum

@@ -19,7 +19,7 @@ _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
-           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
+           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_monitor_step", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
            "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
@@ -96,6 +96,8 @@ def load_library() -> ctypes.CDLL:
         lib.chess_workspace_init.argtypes = [vp, vp, vp]
         lib.chess_select.argtypes = [vp, vp, vp, i32p, ctypes.c_int32, ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_entropy.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, vp, vp, vp]
+        lib.chess_monitor_step.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, ctypes.c_int32, ctypes.c_double,
+                                           ctypes.c_double, vp, vp, i32p, i32p, vp, vp, vp]
         lib.chess_trigger_update.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_double, ctypes.c_double, vp, i32p, i32p, vp, vp]
         lib.chess_reuse_step.argtypes = [vp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_extend_window.argtypes = [vp, i32p, ctypes.c_int32, i32p, i32p, vp]
@@ -203,6 +205,13 @@ class Chess:
     def entropy(self, logits, entropy, workspace, vocab=None):
         self._check(self.lib.chess_entropy(self._h, _ptr(logits), logits.shape[0], logits.shape[1] if vocab is None else vocab,
                                            logits.stride(0), _ptr(entropy), _ptr(workspace), _stream()))
+
+    def monitor_step(self, logits, page_steps: int, tau_entropy: float, tau_variance: float, entropy, history, count, fire,
+                     workspace, stats=None, vocab=None):
+        self._check(self.lib.chess_monitor_step(self._h, _ptr(logits), logits.shape[0],
+                                                logits.shape[1] if vocab is None else vocab, logits.stride(0), page_steps,
+                                                tau_entropy, tau_variance, _ptr(entropy), _ptr(history), _ptr(count),
+                                                _ptr(fire), _ptr(stats), _ptr(workspace), _stream()))
 
     def trigger_update(self, entropy, page_steps: int, tau_entropy: float, tau_variance: float, history, count, fire,
                        stats=None):

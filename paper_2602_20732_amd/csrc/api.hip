@@ -376,8 +376,9 @@ int chess_extend_window(chess_ctx* ctx, const int32_t* seq_lens, int32_t batch, 
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
-int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
-                  void* workspace, void* stream)
+static int entropy_common(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
+                          int32_t page_steps, double tau_h, double tau_v, float* history, int32_t* count, int32_t* fire,
+                          double* stats, void* workspace, void* stream)
 {
     if (!ctx || !logits || !entropy || !workspace) return CHESS_EINVAL;
     if (batch < 1 || batch > ctx->cfg.max_batch || vocab < 1 || row_stride < vocab || (row_stride & 7)) return CHESS_EINVAL;
@@ -388,8 +389,25 @@ int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t voc
     char* wb = static_cast<char*>(workspace);
     hipError_t e = chess::launch_entropy(ctx, static_cast<const uint16_t*>(logits), batch, vocab, row_stride, splits, entropy,
                                          reinterpret_cast<float*>(wb + ctx->ws_ent_off),
-                                         reinterpret_cast<int32_t*>(wb + ctx->ws_entcnt_off), static_cast<hipStream_t>(stream));
+                                         reinterpret_cast<int32_t*>(wb + ctx->ws_entcnt_off), page_steps, tau_h, tau_v,
+                                         history, count, fire, stats, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
+int chess_entropy(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride, float* entropy,
+                  void* workspace, void* stream)
+{
+    return entropy_common(ctx, logits, batch, vocab, row_stride, entropy, 0, 0.0, 0.0, nullptr, nullptr, nullptr, nullptr,
+                          workspace, stream);
+}
+
+int chess_monitor_step(chess_ctx* ctx, const void* logits, int32_t batch, int32_t vocab, int64_t row_stride,
+                       int32_t page_steps, double tau_entropy, double tau_variance, float* entropy, float* history,
+                       int32_t* count, int32_t* fire, double* stats, void* workspace, void* stream)
+{
+    if (!history || !count || !fire || page_steps < 1) return CHESS_EINVAL;
+    return entropy_common(ctx, logits, batch, vocab, row_stride, entropy, page_steps, tau_entropy, tau_variance, history,
+                          count, fire, stats, workspace, stream);
 }
 
 int chess_trigger_update(chess_ctx* ctx, const float* entropy, int32_t batch, int32_t page_steps, double tau_entropy,

@@ -188,8 +188,10 @@ hipError_t launch_reuse(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_new
 hipError_t launch_extend(chess_ctx* ctx, const int32_t* seq_lens, int batch, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 constexpr int kEntMaxSplits = 32;
+// page_steps > 0: the thread that ends up with a sequence's entropy also does that sequence's trigger update
 hipError_t launch_entropy(chess_ctx* ctx, const uint16_t* logits, int batch, int vocab, int64_t row_stride, int splits,
-                          float* H, float* partials, int32_t* arrivals, hipStream_t stream);
+                          float* H, float* partials, int32_t* arrivals, int page_steps, double tau_h, double tau_v,
+                          float* history, int32_t* count, int32_t* fire, double* stats, hipStream_t stream);
 hipError_t launch_trigger(const float* H, int batch, int page_steps, double tau_h, double tau_v, float* history,
                           int32_t* count, int32_t* fire, double* stats, hipStream_t stream);
 hipError_t launch_zero(chess_ctx* ctx, int32_t* p, size_t n_words, hipStream_t stream);

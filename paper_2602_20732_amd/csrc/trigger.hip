@@ -29,13 +29,27 @@ __device__ __forceinline__ Ent ent_merge(const Ent& a, const Ent& b)
     return r;
 }
 
+__device__ __forceinline__ void trigger_update_one(float Hb, int b, int page_steps, double tau_h, double tau_v,
+                                                   float* __restrict__ history, int32_t* __restrict__ count,
+                                                   int32_t* __restrict__ fire, double* __restrict__ stats);
+
+// What the monitor call adds to the entropy kernel: the page statistics, done by the thread that has the entropy.
+struct TriggerArgs {
+    int page_steps;                                      // 0: entropy only
+    double tau_h, tau_v;
+    float* history;
+    int32_t* count;
+    int32_t* fire;
+    double* stats;
+};
+
 constexpr int kEntThreads = 256;
 constexpr int kEntFly = 4;                               // 16-byte loads per thread and trip
 
 // partials: [batch][splits][4] floats; arrivals: [batch] int32, zero between launches
 __global__ __launch_bounds__(kEntThreads) void entropy_kernel(const uint16_t* __restrict__ logits, int vocab, int64_t row_stride,
                                                               float* __restrict__ H, float* __restrict__ partials,
-                                                              int32_t* __restrict__ arrivals)
+                                                              int32_t* __restrict__ arrivals, TriggerArgs tr)
 {
     __shared__ Ent lds[kEntThreads];
     __shared__ int flag;
@@ -91,7 +105,9 @@ __global__ __launch_bounds__(kEntThreads) void entropy_kernel(const uint16_t* __
         }
         if (tid == 0) {
             if (n_splits == 1) {
-                H[b] = e.s0 > 0.f ? logf(e.s0) - e.s1 / e.s0 : 0.f;
+                const float Hb = e.s0 > 0.f ? logf(e.s0) - e.s1 / e.s0 : 0.f;
+                H[b] = Hb;
+                if (tr.page_steps > 0) trigger_update_one(Hb, b, tr.page_steps, tr.tau_h, tr.tau_v, tr.history, tr.count, tr.fire, tr.stats);
             } else {
                 float* p = partials + ((size_t)b * n_splits + split) * 4;
                 publish_f32(p, e.m); publish_f32(p + 1, e.s0); publish_f32(p + 2, e.s1);
@@ -100,44 +116,58 @@ __global__ __launch_bounds__(kEntThreads) void entropy_kernel(const uint16_t* __
     }
     if (n_splits == 1) return;
     if (!arrive_last(arrivals + b, n_splits, &flag)) return;
-    if (tid == 0) {
+    // the splits' triplets: lane s of wave 0 takes split s (at most kEntMaxSplits = 32 of them), then the same tree
+    if (tid < 64) {
         Ent e{-INFINITY, 0.f, 0.f};
-        for (int s = 0; s < n_splits; ++s) {
-            const float* p = partials + ((size_t)b * n_splits + s) * 4;
-            e = ent_merge(e, Ent{observe_f32(p), observe_f32(p + 1), observe_f32(p + 2)});
+        if (tid < n_splits) {
+            const float* p = partials + ((size_t)b * n_splits + tid) * 4;
+            e = Ent{observe_f32(p), observe_f32(p + 1), observe_f32(p + 2)};
         }
-        H[b] = e.s0 > 0.f ? logf(e.s0) - e.s1 / e.s0 : 0.f;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            Ent o;
+            o.m = __shfl_xor(e.m, off);
+            o.s0 = __shfl_xor(e.s0, off);
+            o.s1 = __shfl_xor(e.s1, off);
+            e = (tid & off) ? ent_merge(o, e) : ent_merge(e, o);
+        }
+        if (tid == 0) {
+            const float Hb = e.s0 > 0.f ? logf(e.s0) - e.s1 / e.s0 : 0.f;
+            H[b] = Hb;
+            if (tr.page_steps > 0) trigger_update_one(Hb, b, tr.page_steps, tr.tau_h, tr.tau_v, tr.history, tr.count, tr.fire, tr.stats);
+        }
     }
 }
 
 hipError_t launch_entropy(chess_ctx* ctx, const uint16_t* logits, int batch, int vocab, int64_t row_stride, int splits,
-                          float* H, float* partials, int32_t* arrivals, hipStream_t stream)
+                          float* H, float* partials, int32_t* arrivals, int page_steps, double tau_h, double tau_v,
+                          float* history, int32_t* count, int32_t* fire, double* stats, hipStream_t stream)
 {
     (void)ctx;
+    const TriggerArgs tr{page_steps, tau_h, tau_v, history, count, fire, stats};
     return launch(entropy_kernel, dim3(splits, batch), dim3(kEntThreads), 0, stream, logits, vocab, row_stride, H, partials,
-                  arrivals);
+                  arrivals, tr);
 }
 
-// one thread per sequence
-__global__ void trigger_kernel(const float* __restrict__ H, int batch, int page_steps, double tau_h, double tau_v,
-                               float* __restrict__ history, int32_t* __restrict__ count, int32_t* __restrict__ fire,
-                               double* __restrict__ stats)
+// The page statistics of one sequence (what trigger_kernel does per thread).
+__device__ __forceinline__ void trigger_update_one(float Hb, int b, int page_steps, double tau_h, double tau_v,
+                                                   float* __restrict__ history, int32_t* __restrict__ count,
+                                                   int32_t* __restrict__ fire, double* __restrict__ stats)
 {
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= batch) return;
     float* hist = history + (size_t)b * page_steps;
     int c = count[b];
     if (c < 0 || c >= page_steps) c = 0;                  // a state the caller did not initialise
-    hist[c] = H[b];
+    hist[c] = Hb;
     ++c;
     int f = 0;
     if (c == page_steps) {                                // the page is complete
         double s = 0.0, q = 0.0;
-        for (int i = 0; i < page_steps; ++i) s += (double)hist[i];
+        for (int i = 0; i < page_steps - 1; ++i) s += (double)hist[i];
+        s += (double)Hb;                                  // (the entry just stored, without reading it back)
         const double mu = s / (double)page_steps;
         for (int i = 0; i < page_steps; ++i) {
 #pragma clang fp contract(off)                            // product rounded, then added: no fused multiply-add
-            const double d = (double)hist[i] - mu;
+            const double d = (double)(i == page_steps - 1 ? Hb : hist[i]) - mu;
             const double dd = d * d;
             q = q + dd;
         }
@@ -148,6 +178,16 @@ __global__ void trigger_kernel(const float* __restrict__ H, int batch, int page_
     }
     fire[b] = f;
     count[b] = c;
+}
+
+// one thread per sequence
+__global__ void trigger_kernel(const float* __restrict__ H, int batch, int page_steps, double tau_h, double tau_v,
+                               float* __restrict__ history, int32_t* __restrict__ count, int32_t* __restrict__ fire,
+                               double* __restrict__ stats)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= batch) return;
+    trigger_update_one(H[b], b, page_steps, tau_h, tau_v, history, count, fire, stats);
 }
 
 hipError_t launch_trigger(const float* H, int batch, int page_steps, double tau_h, double tau_v, float* history,

@@ -90,3 +90,36 @@ def test_trigger_update_is_bit_exact_and_fires_on_either_threshold():
     with pytest.raises(pk.ChessError):
         lib.trigger_update(torch.as_tensor(Hs[0]).cuda(), 0, tau_h, tau_v, hist, count, fire, stats)
     lib.close()
+
+
+def test_monitor_step_equals_the_two_calls():
+    """chess_monitor_step (entropy + page statistics in one launch) against chess_entropy + chess_trigger_update on
+    the same logits, step by step over three pages: entropies, flags, statistics and counters identical."""
+    lib = make_lib(8)
+    batch, page, vocab = 8, 4, 50000
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    ws = lib.new_workspace()
+
+    def state():
+        return dict(H=torch.zeros((batch,), device="cuda"), hist=torch.zeros((batch, page), device="cuda"),
+                    count=torch.zeros((batch,), dtype=torch.int32, device="cuda"),
+                    fire=torch.full((batch,), -1, dtype=torch.int32, device="cuda"),
+                    stats=torch.zeros((batch, 2), dtype=torch.float64, device="cuda"))
+    A, B = state(), state()
+    fired = 0
+    for t in range(3 * page):
+        scale = torch.rand((batch, 1), device="cuda", generator=gen) * 4 + 0.1
+        logits = (torch.randn((batch, vocab), device="cuda", generator=gen) * scale).to(torch.bfloat16)
+        lib.entropy(logits, A["H"], ws)
+        lib.trigger_update(A["H"], page, 9.5, 0.6, A["hist"], A["count"], A["fire"], A["stats"])
+        lib.monitor_step(logits, page, 9.5, 0.6, B["H"], B["hist"], B["count"], B["fire"], ws, stats=B["stats"])
+        torch.cuda.synchronize()
+        for k in A:
+            assert torch.equal(A[k], B[k]), (t, k)
+        fired += int(A["fire"].sum())
+    assert 0 < fired < 3 * batch, "thresholds chosen so that some pages fire and some do not"
+    ref = oracle.entropy(logits.view(torch.int16).cpu().numpy().view(np.uint16))
+    assert np.abs(B["H"].cpu().numpy() - ref).max() <= ATOL
+    with pytest.raises(pk.ChessError):
+        lib.monitor_step(logits, 0, 1.0, 1.0, B["H"], B["hist"], B["count"], B["fire"], ws)
+    lib.close()
