@@ -44,6 +44,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense full-KV comparison")
     ap.add_argument("--shared-layers", type=int, default=32,
                     help="layers of the model-wide selection timed beside the step (0 = skip)")
+    ap.add_argument("--batch", type=int, default=0, help="sequences per step instead of the workload's own batch")
     ap.add_argument("--fanout", default="", help="NcxNg: pages per chunk x chunks per grid instead of the workload's 8x8")
     ap.add_argument("--cluster", type=int, default=0,
                     help="tuning aid: force the workgroups per (sequence, KV head) of select / decode_step (0 = automatic)")
@@ -253,6 +254,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     sp = workload.spec(args.workload)
+    if args.batch > 0:
+        import dataclasses
+        sp = dataclasses.replace(sp, batch=args.batch)
     if args.fanout:
         import dataclasses
         nc_, ng_ = (int(x) for x in args.fanout.lower().split("x"))
