@@ -485,6 +485,10 @@ def main():
                            "frac_of_hbm_peak": round(dense_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                            "bytes": dense_bytes, "sparse_speedup": round(d_ms / ms_step, 2)}
 
+    # a cluster that gave up a bounded wait would have produced undefined results: no number is printed then
+    if lib.workspace_error(ws) != 0:
+        raise RuntimeError("a kernel gave up a bounded wait during the timed steps (was the device shared?)")
+
     if not args.no_cpu:
         result["cpu_baseline"] = cpu_baseline(sp, pools[0][0], plan)
 
