@@ -4,8 +4,9 @@
 
 namespace chess {
 
+// Three workgroups of four waves per compute unit (at most 170 registers a lane): see run_tiles_with, kSingle.
 template <int B, int NW, bool kList>
-__global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restrict__ q,
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(3))) void decode_kernel(const uint16_t* __restrict__ q,
                                                          const uint16_t* __restrict__ k_pool,
                                                          const uint16_t* __restrict__ v_pool,
                                                          const int32_t* __restrict__ block_table,
@@ -45,8 +46,10 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
 
     WaveAcc<B> acc;
     acc.init(q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim, G, m16, grp);
-    run_tiles<B, kList, false>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool, v_pool, H, h, L, P,
-                 scale_log2, m16, grp);
+    NewToken<B> none;
+    none.tile = -1;
+    run_tiles_with<B, kList, false, false, true>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr,
+                                                 k_pool, v_pool, H, h, L, P, scale_log2, m16, grp, none, 1 << 30);
 
     float* out_rows = out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     if (!combine_waves<NW>(acc.o, acc.m_run, acc.l_run, lds, G, n_splits, split, row, out_rows, ws_acc, ws_ml)) return;
@@ -61,7 +64,8 @@ __global__ __launch_bounds__(64 * NW) void decode_kernel(const uint16_t* __restr
 // and, when the token opens a new page, the page to the list.  The lists must end with the tail page of seq_lens
 // (as a selection on these lengths, chess_append_kv with the lists, or this call leave them).
 // grid = (n_splits, H_kv, batch), four waves.
-template <int B>
+// kSingle: one tile in registers at a time; faster while a wave has only a few tiles (the host decides).
+template <int B, bool kSingle>
 __global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
                                                     const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_pool,
                                                     uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__
 
     WaveAcc<B> acc;
     acc.init(q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim, G, m16, grp);
-    run_tiles_with<B, true, false, true>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool,
+    run_tiles_with<B, true, false, true, kSingle>(acc, t, stride, n_tiles, n_pages, raw_cur, raw_nxt, ids, g.max_sel, bt_row, nullptr, k_pool,
                                          v_pool, H, h, L, P, scale_log2, m16, grp, nt, n_stored);
 
     float* out_rows = out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
@@ -140,7 +144,11 @@ hipError_t launch_reuse(chess_ctx* ctx, const uint16_t* q, const uint16_t* k_new
     const float scale_log2 = ctx->sm_scale * 1.4426950408889634f;
     const dim3 grid(n_splits, g.n_kv_heads, batch), block(256);
     const size_t lds = (size_t)(4 * g.group * kHeadDim + 2 * 4 * g.group) * sizeof(float);
-    auto kern = g.page_size == 16 ? reuse_kernel<16> : reuse_kernel<32>;
+    // without the prefetch of the next tile while a wave has at most four tiles of the longest possible list
+    const int tiles = (g.max_sel + kTileTokens / g.page_size - 1) / (kTileTokens / g.page_size);
+    const bool single = tiles <= 4 * 4 * n_splits;
+    auto kern = g.page_size == 16 ? (single ? reuse_kernel<16, true> : reuse_kernel<16, false>)
+                                  : (single ? reuse_kernel<32, true> : reuse_kernel<32, false>);
     return launch(kern, grid, block, lds, stream, q, k_new, v_new, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected,
                   g, scale_log2, n_splits, out, ws_acc, ws_ml, arrivals);
 }

@@ -285,7 +285,10 @@ struct WaveAcc {
 // outstanding).  After the last tile the "next" request repeats the current tile: it hits in cache and is dropped.
 // nt (may be null): a token appended by this launch; n_stored: list entries that are in memory (the list may gain the
 // tail page in this launch: entries from n_stored on are that page).
-template <int B, bool kList, bool kPhysList, bool kAppend>
+// kSingle: one tile in registers at a time (no request for the next tile while this one is computed): with a
+// third less registers three workgroups fit on a compute unit instead of two, which hides more latency than the
+// prefetch did (measured on lists and on whole sequences; the block-table path only).
+template <int B, bool kList, bool kPhysList, bool kAppend, bool kSingle = false>
 __device__ __forceinline__ void run_tiles_with(WaveAcc<B>& acc, int t, int stride, int n_tiles, int n_pages,
                                           int (&raw_cur)[32 / B], int (&raw_nxt)[32 / B], const int32_t* ids, int max_sel,
                                           const int32_t* bt_row, const int32_t* phys_list, const uint16_t* k_pool,
@@ -301,6 +304,22 @@ __device__ __forceinline__ void run_tiles_with(WaveAcc<B>& acc, int t, int strid
             lookup_pages<B>(pc, t, n_pages, raw_cur, bt_row, L, P, n_stored);
             lookup_pages<B>(pn, t + stride, n_pages, raw_nxt, bt_row, L, P, n_stored);
             fetch_ids<B, kList>(raw_nn, t + 2 * stride, ids, max_sel);
+            if constexpr (kSingle) {
+                Tile<B> cur;
+                for (; t < n_tiles; t += stride) {
+                    load_rows<B>(cur, pc, k_pool, v_pool, H, h, m16, grp);
+                    lookup_pages<B>(pnn, t + 2 * stride, n_pages, raw_nn, bt_row, L, P, n_stored);
+                    fetch_ids<B, kList>(raw_nn, t + 3 * stride, ids, max_sel);
+                    const int lp_tail = (PPT == 1 || nt.T < B) ? cur.lp[0] : cur.lp[PPT - 1];
+                    if (kAppend && t == nt.tile && lp_tail == P - 1) nt.put(cur, m16, grp);
+                    acc.process(cur, scale_log2, grp);
+                    pc = pn;
+                    pn = pnn;
+                }
+                acc.l_run += __shfl_xor(acc.l_run, 16);
+                acc.l_run += __shfl_xor(acc.l_run, 32);
+                return;
+            }
             Tile<B> cur, nxt;
             load_rows<B>(cur, pc, k_pool, v_pool, H, h, m16, grp);
             for (; t < n_tiles; t += stride) {
