@@ -94,3 +94,52 @@ def test_cfg4b_full():
 def test_cfg5_full_and_equal_norm_variant():
     run_case("cfg5", [0])
     run_case("cfg5adv", [0], dense_seq=None)
+
+
+@pytest.mark.parametrize("name,sample", [("cfg4a", 5), ("cfg3", 13), ("cfg5", 0)])
+def test_reuse_step_at_benchmark_shapes(name, sample):
+    """The step between reselections as bench.py times it: the lists selected one token earlier, then
+    chess_reuse_step with the last token's rows.  The pools must end up unchanged (the token's own rows are written
+    back), the output must be bit-identical to chess_append_kv + chess_sparse_decode, and on a sampled sequence equal
+    the oracle's attention over the list on the full length."""
+    sp = workload.spec(name)
+    wl = workload.generate(sp, workload.default_seed(name), device="cuda")
+    lib = pk.Chess(config_of(sp))
+    plan = plan_of(sp)
+    B, H = sp.page_size, sp.n_kv_heads
+    before = (wl.seq_lens - 1).clamp_(min=0)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(wl.k_pool, wl.block_table, before, summ)
+    ids = torch.full((sp.batch, H, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((sp.batch, H), -7, dtype=torch.int32, device="cuda")
+    lib.select(wl.q, summ, before, gpu_plan(plan), ids, nsel, ws)
+    # the last token's rows, taken out of the pools
+    bt = wl.block_table
+    pos = before.long()
+    phys = bt[torch.arange(sp.batch, device="cuda"), pos // B].long()
+    rk = torch.stack([wl.k_pool[phys[b], :, int(pos[b]) % B, :] for b in range(sp.batch)]).contiguous()
+    rv = torch.stack([wl.v_pool[phys[b], :, :, int(pos[b]) % B] for b in range(sp.batch)]).contiguous()
+    k2, v2 = wl.k_pool.clone(), wl.v_pool.clone()
+    for b in range(sp.batch):                                   # the slot is junk until the call stores the token
+        k2[phys[b], :, int(pos[b]) % B, :] = float("nan")
+        v2[phys[b], :, :, int(pos[b]) % B] = float("nan")
+    ids1, nsel1, ids2, nsel2 = ids.clone(), nsel.clone(), ids.clone(), nsel.clone()
+    out1 = torch.full((sp.batch, sp.n_q_heads, 128), float("nan"), device="cuda")
+    out2 = torch.full_like(out1, float("nan"))
+    lib.reuse_step(wl.q, rk, rv, k2, v2, bt, before, ids1, nsel1, out1, ws)
+    k3, v3 = k2.clone(), v2.clone()                              # (k2 has the token by now; junk it again for the two calls)
+    for b in range(sp.batch):
+        k3[phys[b], :, int(pos[b]) % B, :] = float("nan")
+        v3[phys[b], :, :, int(pos[b]) % B] = float("nan")
+    lib.append_kv(rk, rv, k3, v3, bt, before, ids2, nsel2)
+    lib.sparse_decode(wl.q, k3, v3, bt, wl.seq_lens, ids2, nsel2, out2, ws)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    assert torch.equal(out1, out2) and torch.equal(nsel1, nsel2)
+    assert torch.equal(k2.view(torch.int16), wl.k_pool.view(torch.int16)) and torch.equal(v2.view(torch.int16), wl.v_pool.view(torch.int16))
+    K, V, Q, bts, sls = host_subset(wl, [sample])
+    ref = oracle.attend(Q, K, V, bts, sls, geom_of(sp), ids1[sample:sample + 1].cpu().numpy(), nsel1[sample:sample + 1].cpu().numpy())
+    err = np.abs(out1[sample].cpu().numpy() - ref[0]).max()
+    print(f"[{name}] reuse step, seq {sample}: max|out - oracle| = {err:.2e}")
+    assert err <= ATOL
+    lib.close()
