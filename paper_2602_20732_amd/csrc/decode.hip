@@ -65,8 +65,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(3))) vo
 // (as a selection on these lengths, chess_append_kv with the lists, or this call leave them).
 // grid = (n_splits, H_kv, batch), four waves.
 // kSingle: one tile in registers at a time; faster while a wave has only a few tiles (the host decides).
+// Two workgroups per compute unit either way (squeezed into the registers of three, the kernel was slower).
 template <int B, bool kSingle>
-__global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void reuse_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k_new,
                                                     const uint16_t* __restrict__ v_new, uint16_t* __restrict__ k_pool,
                                                     uint16_t* __restrict__ v_pool, const int32_t* __restrict__ block_table,
                                                     const int32_t* __restrict__ seq_lens, int32_t* __restrict__ page_ids,
@@ -94,7 +95,8 @@ __global__ __launch_bounds__(256) void reuse_kernel(const uint16_t* __restrict__
     fetch_ids<B, true>(raw_cur, t, ids, g.max_sel);
     fetch_ids<B, true>(raw_nxt, t + stride, ids, g.max_sel);
     NewToken<B> nt;
-    nt.load(k_new + row * kHeadDim, v_new + row * kHeadDim, m16, grp);
+    nt.k_row = k_new + row * kHeadDim;
+    nt.v_row = v_new + row * kHeadDim;
 
     const bool room = L_before >= 0 && L_before < g.max_pages * B;
     const int L = room ? L_before + 1 : min(max(L_before, 0), g.max_pages * B);

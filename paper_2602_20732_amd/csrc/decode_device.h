@@ -153,23 +153,24 @@ __device__ __forceinline__ void load_rows(Tile<B>& tl, const PageRef<B>& r, cons
     }
 }
 
-// The token a launch appends (its rows are not in the pools yet): this lane's parts of its key and value rows, and
-// where it sits.  `put` replaces the token's slot in the operands of the tile that holds the tail page.
+// The token a launch appends (its rows are not in the pools yet) and where it sits.  `put` replaces the token's slot
+// in the operands of the tile that holds the tail page; it reads this lane's parts of the two rows then (the one
+// wave that needs them asks for them behind its tile's own loads: nothing waits longer than it would anyway, and no
+// other wave carries them in registers).
 template <int B>
 struct NewToken {
-    uint4 k[4];          // key row, d = 32 st + 8 grp .. + 7
-    uint16_t v[8];       // value row, d = 16 blk + m16
-    int tile, T;         // tile of the list that holds the tail page (-1: nothing is appended), token slot in it
-    __device__ __forceinline__ void load(const uint16_t* k_row, const uint16_t* v_row, int m16, int grp)
+    const uint16_t* k_row;   // key row, 128 bf16
+    const uint16_t* v_row;   // value row
+    int tile, T;             // tile of the list that holds the tail page (-1: nothing is appended), token slot in it
+    __device__ __forceinline__ void put(Tile<B>& tl, int m16, int grp) const
     {
+        uint4 k[4];          // d = 32 st + 8 grp .. + 7
+        uint16_t v[8];       // d = 16 blk + m16
         const uint4* ks = reinterpret_cast<const uint4*>(k_row) + grp;
 #pragma unroll
         for (int st = 0; st < 4; ++st) k[st] = ks[st * 4];
 #pragma unroll
         for (int blk = 0; blk < 8; ++blk) v[blk] = v_row[16 * blk + m16];
-    }
-    __device__ __forceinline__ void put(Tile<B>& tl, int m16, int grp) const
-    {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             const bool mine = 8 * (m16 >> 2) + 4 * c + (m16 & 3) == T;
