@@ -575,6 +575,65 @@ def test_shared_scope_is_linear_in_the_layers(layers):
         assert nsel[b] == plan.sink_pages + plan.window_pages + min(k, cnt[b, 2]) and cnt[b, 2] <= k
 
 
+def test_shared_scope_never_draws_safety_pages_from_the_budget():
+    """Sec. 3.2 unites the sink and recent-window pages with the selection; they are not drawn from it.  Two cases
+    in which a safety page WOULD take a budget slot if it were a candidate at page level:
+    (1) every key row identical in both layers: all scores tie, ties go to the lowest index, so the kept pages are
+        the lowest pages AFTER the sinks;
+    (2) the sink pages and the window pages carry the anchor's own direction (planted), so they outscore every
+        other page: the kept pages must still be the top k of the pages between them (brute force, numpy)."""
+    L, H, d, B, Nc, Ng, s, w, k = 128 * 16, 2, 128, 16, 4, 4, 2, 3, 6
+    P = L // B
+    g = oracle.Geometry(4, H, d, B, Nc, Ng, P)
+    sl = np.array([L], np.int32)
+    rng = np.random.default_rng(20732)
+
+    def layer(Klog):
+        K, _, bt = pack_pools(Klog, np.zeros_like(Klog), B, perm=rng.permutation(P))
+        return oracle.summarize(K, bt, sl, g)
+
+    def run(summ, plan):
+        probes = [oracle.anchor(pv, sl, g, w) for (pv, cv, gv) in summ]
+        return probes, oracle.select_shared(probes, [x[0] for x in summ], [x[1] for x in summ], [x[2] for x in summ],
+                                            sl, g, plan, s + k + w)
+
+    # (1) exact ties at every level
+    row = np.linspace(-1, 1, d, dtype=np.float32)
+    summ = [layer(np.tile(row, (L, H, 1))) for _ in range(2)]
+    for kw in (dict(plan=oracle.PLAN_BUDGET), dict(plan=oracle.PLAN_FLAT)):
+        _, (ids, nsel) = run(summ, oracle.Plan(sink_pages=s, window_pages=w, budget_pages=k, **kw))
+        assert ids[0, :nsel[0]].tolist() == list(range(s)) + list(range(s, s + k)) + list(range(P - w, P))
+
+    # (2) planted: sinks and window along one direction t, everything else small noise
+    t = rng.standard_normal((H, d)).astype(np.float32)
+    summ = []
+    for _ in range(2):
+        Klog = 0.05 * rng.standard_normal((L, H, d)).astype(np.float32)
+        Klog[:s * B] += t
+        Klog[(P - w) * B:] += t
+        summ.append(layer(Klog))
+    plan = oracle.Plan(plan=oracle.PLAN_FLAT, sink_pages=s, window_pages=w, budget_pages=k)
+    probes, (ids, nsel) = run(summ, plan)
+    flat = np.concatenate([pv[0].astype(np.float64).transpose(1, 0, 2).reshape(P, H * d) for (pv, _, _) in summ], axis=1)
+    probe = np.concatenate([p[0].astype(np.float64).reshape(H * d) for p in probes])
+    score = flat @ probe
+    assert score[:s].min() > score[s:P - w].max() and score[P - w:].min() > score[s:P - w].max(), "the plant must dominate"
+    cand = np.arange(s, P - w)
+    top = cand[np.argsort(-score[cand], kind="stable")][:k]
+    assert nsel[0] == s + k + w
+    assert ids[0, :nsel[0]].tolist() == list(range(s)) + sorted(top.tolist()) + list(range(P - w, P))
+    # the per-head cascade on the same plant (one layer, anchor probe): the same rule
+    pv, cv, gv = summ[0]
+    Q = np.zeros((1, 4, d), np.uint16)
+    hplan = oracle.Plan(plan=oracle.PLAN_FLAT, sink_pages=s, window_pages=w, budget_pages=k, probe=oracle.PROBE_ANCHOR)
+    hid, hn = oracle.select(Q, pv, cv, gv, sl, g, hplan, s + k + w)
+    a = oracle.anchor(pv, sl, g, w)
+    for h in range(H):
+        sc = pv[0, h].astype(np.float64) @ a[0, h].astype(np.float64)
+        top = cand[np.argsort(-sc[cand], kind="stable")][:k]
+        assert hid[0, h, :hn[0, h]].tolist() == list(range(s)) + sorted(top.tolist()) + list(range(P - w, P))
+
+
 # ------------------------------------------------------------------ Sec. 3.3: entropy / variance of the entropy per page
 def test_entropy_closed_forms_and_library_routine():
     """Uniform logits: log V.  One logit far above the rest: ~0.  Two levels: the closed form

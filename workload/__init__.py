@@ -1,10 +1,14 @@
 """Seeded synthetic inputs for the CHESS decode hot path.
 
 This module serves both the CPU oracle's tests and the HIP path's tests and
-benchmark.  It holds NONE of the method's arithmetic: no summaries, no scores,
-no selection, no attention -- only random numbers, the topic-segment recipe of
-the benchmark configurations, and the packing of logical K/V rows into the
-paged pool layout.
+benchmark.  It holds none of the method's floating-point arithmetic: no
+summaries, no scores, no selection, no attention -- only random numbers, the
+topic-segment recipe of the benchmark configurations, and the packing of
+logical K/V rows into the paged pool layout.  One integer formula of the
+method is restated here, ``WorkloadSpec.budget_for`` (the page budget of a
+sequence, k = max(1, ceil(P * bp / 10^4))): it sizes the ``page_ids`` rows a
+configuration needs and serves as a length check in the tests and the
+benchmark; neither the oracle nor the kernels call it.
 
 Random numbers come from a stateless counter-based generator (a 64-bit
 multiply-xorshift finaliser applied to ``key + counter``), written with integer
@@ -127,6 +131,7 @@ class WorkloadSpec:
         return self.n_q_heads // self.n_kv_heads
 
     def budget_for(self, pages: int) -> int:
+        """Page budget k of a sequence of `pages` pages (buffer sizing and length checks only)."""
         if self.budget_pages > 0:
             return self.budget_pages
         return max(1, -(-pages * self.budget_bp // 10000))
