@@ -6,7 +6,8 @@
  * in place (no KV copy, only page indices change: Sec. 1, Sec. 4.1, App. B "Zero-Copy Logic").
  *
  * C ABI.  Every data pointer is a DEVICE pointer owned by the caller unless it says "host".
- * The library never allocates or frees device memory; only chess_append_kv writes the K/V pools.  Every call is
+ * The library never allocates or frees device memory; only chess_append_kv and chess_reuse_step write the K/V
+ * pools (the appended token's rows, nothing else).  Every call is
  * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream), does no
  * host synchronisation, and can be captured in a HIP graph.  A context caches launch shapes: calls on one
  * context must not run concurrently from several host threads (use one context per thread).
@@ -22,7 +23,8 @@
  *   block table  int32 [batch][max_pages_per_seq]     logical page -> physical page
  *   seq_lens     int32 [batch]                        tokens in each sequence
  *   q            bf16 [batch][n_q_heads][d]           q head hq belongs to KV head hq / G
- *   summaries    fp32, three arrays in one buffer (byte offsets from chess_summary_layout):
+ *   summaries    fp32 (or bf16, see chess_config.summary_dtype), three arrays in one buffer (byte offsets from
+ *                chess_summary_layout):
  *                  pages  [batch][H][max_pages_per_seq][d]
  *                  chunks [batch][H][ceil(max_pages_per_seq / N_c)][d]
  *                  grids  [batch][H][ceil(max_chunks / N_g)][d]       all in logical order
@@ -56,6 +58,16 @@ extern "C" {
 #define CHESS_PROBE_ANCHOR 1 /* Eq. 3: the mean of the page vectors of the recent window (the last          */
                              /* window_pages pages), keys only; q is then not read and may be NULL          */
 
+/* How many units a level keeps once its count k is known (Alg. 1 stage 2 thresholds at a quantile). */
+#define CHESS_CUT_COUNT     0 /* exactly k units; ties at the cut go to the lower index                      */
+#define CHESS_CUT_THRESHOLD 1 /* every unit whose score is >= the k-th largest score (S >= tau as printed in */
+                              /* Alg. 1): ties at the cut are all kept, so a level may keep more than k      */
+
+/* Storage type of the summary vectors (the paper only says "compact vector"). */
+#define CHESS_SUMMARY_F32  0  /* fp32: the fp64 mean rounded once                                            */
+#define CHESS_SUMMARY_BF16 1  /* bf16: that fp32 value rounded to nearest-even bf16; parents average the     */
+                              /* stored (bf16) child vectors; half the bytes the selection reads             */
+
 #define CHESS_MAX_LAYERS 64   /* most layers one chess_select_shared call can take */
 
 typedef struct chess_ctx chess_ctx; /* opaque; small host-side state only */
@@ -71,6 +83,12 @@ typedef struct {
     int32_t max_pages_per_seq;  /* row stride of the block table and of the page summaries   */
     int32_t max_selected_pages; /* row stride of page_ids                                    */
     float   sm_scale;           /* softmax scale; 0 means 1 / sqrt(head_dim)                 */
+    int32_t summary_dtype;      /* CHESS_SUMMARY_*                                           */
+    int32_t shared_device;      /* non-zero: other work may run on this GPU at the same time.  chess_select,
+                                   chess_decode_step and chess_select_shared then give every (sequence, KV head)
+                                   (every sequence) to ONE workgroup: no workgroup ever waits for another, so no
+                                   launch depends on what else is resident.  0: the device is this library's
+                                   while a call runs, and short batches are spread over cooperating workgroups */
 } chess_config;
 
 typedef struct {
@@ -85,6 +103,11 @@ typedef struct {
     int32_t rho_c_bp;           /*   clamp(ceil(n * rho), 1, n) of its n active units        */
     int32_t rho_p_bp;
     int32_t probe;              /* CHESS_PROBE_*; the anchor needs window_pages >= 1         */
+    int32_t cut_rule;           /* CHESS_CUT_*                                               */
+    const int32_t* budget_per_seq; /* DEVICE int32 [batch] or NULL: a value > 0 replaces budget_pages / budget_bp
+                                   for that sequence (clamped to max_selected_pages - s - w); <= 0 keeps the
+                                   plan's own budget.  Ignored by CHESS_PLAN_RATIO.  With it the host sizes every
+                                   level for the largest budget the configuration allows */
 } chess_select_plan;
 
 /* Create / destroy the host-side context.  `cfg` is a host pointer and is copied.  Queries the
@@ -278,31 +301,13 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
                       int32_t batch, const chess_select_plan* plan, int32_t* page_ids, int32_t* n_selected, float* out,
                       void* workspace, void* stream);
 
-/* Synchronous check (copies one word back, waits for the device): *flag is non-zero if any kernel
- * using this workspace gave up a bounded wait -- which cannot happen unless the device was shared
- * with work that kept this library's workgroups from becoming resident together.  Results written
- * by such a launch are undefined; re-initialise the workspace before reuse. */
-int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag);
-
-/* Test hook: force the number of workgroups that cooperate on one (sequence, KV head) in
- * chess_select and chess_decode_step (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
-int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster);
-
-/* Test hook: on = 1 makes every level of chess_select find its cut by the general path (radix select
- * on the keys in LDS) that otherwise only serves tied or very large levels; 0 restores the automatic
- * choice.  The selected pages are the same either way. */
-int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on);
-
-/* Test hook: the number of polls after which a workgroup of chess_select / chess_decode_step gives up waiting for
- * the keys of the other members of its cluster (0 restores the default, 32768, about 30 ms).  With a limit of 1 or
- * 2 the waits fail on purpose: every workgroup still leaves normally, the workspace's error flag is raised, the
- * results are undefined and the workspace must be re-initialised. */
-int chess_debug_set_poll_limit(chess_ctx* ctx, int32_t polls);
-
-/* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 1024,
- * waves in {1, 4}); n_splits = 0 restores the automatic choice.  CHESS_EINVAL if the forced shape would
- * not fit the workspace for max_batch sequences. */
-int chess_debug_force_splits(chess_ctx* ctx, int32_t n_splits, int32_t waves);
+/* Synchronous check: copies the workspace's error word back on `stream` and waits for that stream (so it sees
+ * every launch made on it before; work on other streams is not waited for).  *flag is non-zero if any kernel
+ * using this workspace gave up a bounded wait -- which cannot happen unless the device was shared with work
+ * that kept this library's workgroups from becoming resident together (see chess_config.shared_device).
+ * Results written by such a launch are undefined, and published words are left behind: check the flag (or
+ * re-initialise the workspace) before the workspace is used again. */
+int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag, void* stream);
 
 const char* chess_strerror(int code);
 int chess_version(void);

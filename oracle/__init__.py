@@ -24,6 +24,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
 PROBE_QUERY, PROBE_ANCHOR = 0, 1         # what units are scored against: the query sum, or the Eq. 3 key anchor
+CUT_COUNT, CUT_THRESHOLD = 0, 1          # a level keeps exactly k units / every unit scoring >= the k-th (Alg. 1's S >= tau)
 
 
 def build(force: bool = False) -> str:
@@ -43,7 +44,7 @@ class _Geom(ctypes.Structure):
 class _Plan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("plan", "sink_pages", "window_pages", "budget_pages", "budget_bp", "over_chunk", "over_grid",
-                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe")]
+                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe", "cut_rule")]
 
 
 @dataclass(frozen=True)
@@ -82,10 +83,20 @@ class Plan:
     rho_c_bp: int = 10000
     rho_p_bp: int = 10000
     probe: int = PROBE_QUERY
+    cut_rule: int = CUT_COUNT
+    budget_per_seq: "tuple | None" = None    # per-sequence page budgets (an entry > 0 replaces the plan's budget)
 
     def _c(self) -> _Plan:
         return _Plan(self.plan, self.sink_pages, self.window_pages, self.budget_pages, self.budget_bp,
-                     self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe)
+                     self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe,
+                     self.cut_rule)
+
+    def _per_seq(self, batch: int):
+        if self.budget_per_seq is None:
+            return None
+        a = np.ascontiguousarray(np.asarray(self.budget_per_seq, dtype=np.int32))
+        assert a.shape == (batch,)
+        return a
 
 
 _lib = None
@@ -161,9 +172,10 @@ def select(q, page_vec, chunk_vec, grid_vec, seq_lens, geom: Geometry, plan: Pla
     kc = np.zeros(shp + (geom.max_chunks,), np.uint8)
     cnt = np.zeros(shp + (3,), np.int32)
     g, p = geom._c(), plan._c()
+    per = plan._per_seq(batch)
     rc = _load().oracle_select(_p(q, ctypes.c_uint16), _p(page_vec, ctypes.c_float), _p(chunk_vec, ctypes.c_float),
                                _p(grid_vec, ctypes.c_float), _p(sl, ctypes.c_int32), ctypes.c_int32(batch),
-                               ctypes.byref(g), ctypes.byref(p), ctypes.c_int32(max_sel),
+                               ctypes.byref(g), ctypes.byref(p), _p(per, ctypes.c_int32), ctypes.c_int32(max_sel),
                                _p(ids, ctypes.c_int32), _p(nsel, ctypes.c_int32),
                                _p(kg, ctypes.c_uint8), _p(kc, ctypes.c_uint8), _p(cnt, ctypes.c_int32))
     if rc != 0:
@@ -204,8 +216,10 @@ def select_shared(probes, page_vecs, chunk_vecs, grid_vecs, seq_lens, geom: Geom
     nsel = np.zeros((batch,), np.int32)
     cnt = np.zeros((batch, 3), np.int32)
     g, p = geom._c(), plan._c()
+    per = plan._per_seq(batch)
     rc = _load().oracle_select_shared(ctypes.c_int32(n_layers), pp, p1, p2, p3, _p(sl, ctypes.c_int32),
-                                      ctypes.c_int32(batch), ctypes.byref(g), ctypes.byref(p), ctypes.c_int32(max_sel),
+                                      ctypes.c_int32(batch), ctypes.byref(g), ctypes.byref(p), _p(per, ctypes.c_int32),
+                                      ctypes.c_int32(max_sel),
                                       _p(ids, ctypes.c_int32), _p(nsel, ctypes.c_int32), _p(cnt, ctypes.c_int32))
     del kp, k1, k2, k3
     if rc != 0:

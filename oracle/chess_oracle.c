@@ -43,6 +43,9 @@
  *     ascending; an inactive unit is never ranked (no zero fill);
  *   - sink and window pages are not candidates at page level, the budget is
  *     on top of them.
+ *   - ORACLE_CUT_THRESHOLD is Alg. 1 stage 2 as printed (keep S >= tau), with tau the score of the
+ *     ceil(rho * n)-th active unit in rank order (the paper leaves the quantile's interpolation open);
+ *     ORACLE_CUT_COUNT is the exact-count rule the benchmark spec asks for.
  *   - Sec. 3.3 names its two metrics "average Entropy" H_p and "Varentropy" Var(H)_p of a page p and says the
  *     second captures temporal instability: read here as the mean and the population variance, over the
  *     steps that generated page p, of the per-step entropy; reselection fires when either is above its
@@ -59,6 +62,7 @@
 
 enum { ORACLE_PLAN_BUDGET = 0, ORACLE_PLAN_RATIO = 1, ORACLE_PLAN_FLAT = 2 };
 enum { ORACLE_PROBE_QUERY = 0, ORACLE_PROBE_ANCHOR = 1 };
+enum { ORACLE_CUT_COUNT = 0, ORACLE_CUT_THRESHOLD = 1 };
 
 typedef struct {
     int32_t n_q_heads;       /* H_q                                        */
@@ -81,6 +85,10 @@ typedef struct {
     int32_t over_grid;     /* budget plan: grid oversampling                */
     int32_t rho_g_bp, rho_c_bp, rho_p_bp; /* ratio plan, basis points       */
     int32_t probe;         /* ORACLE_PROBE_*: what the units are scored against */
+    int32_t cut_rule;      /* ORACLE_CUT_COUNT: a level keeps exactly k units (ties to the lower index);
+                              ORACLE_CUT_THRESHOLD: Alg. 1 stage 2 as printed, tau = the k-th largest score of the
+                              level's active units and every active unit with S >= tau is kept (ties at the cut
+                              are all kept, so the count can exceed k) */
 } oracle_plan;
 
 static double bf16_value(uint16_t h)
@@ -243,11 +251,33 @@ static int ranked_cmp(const void *a, const void *b)
     return (x->index > y->index) - (x->index < y->index);
 }
 
-/* keep the first k of n candidates in rank order; mark them in keep[index] */
-static void keep_top(ranked *cand, int64_t n, int64_t k, uint8_t *keep)
+/*
+ * Keep k of n candidates; mark them in keep[index]; returns how many were kept.
+ * ORACLE_CUT_COUNT: the first k in rank order.  ORACLE_CUT_THRESHOLD (Alg. 1 stage 2: tau = Quantile, mask
+ * S >= tau): tau is the score of the k-th candidate in rank order and every candidate with score >= tau is kept.
+ */
+static int64_t keep_top(ranked *cand, int64_t n, int64_t k, int cut_rule, uint8_t *keep)
 {
     qsort(cand, (size_t)n, sizeof *cand, ranked_cmp);
-    for (int64_t i = 0; i < k && i < n; ++i) keep[cand[i].index] = 1;
+    if (k > n) k = n;
+    if (k <= 0) return 0;
+    int64_t kept = k;
+    if (cut_rule == ORACLE_CUT_THRESHOLD) {
+        const double tau = cand[k - 1].score;
+        while (kept < n && cand[kept].score >= tau) ++kept;
+    }
+    for (int64_t i = 0; i < kept; ++i) keep[cand[i].index] = 1;
+    return kept;
+}
+
+/* the page budget k of sequence b: its own entry of budget_per_seq when that is given and positive, else the
+ * plan's fixed budget, else the plan's fraction of the sequence's P pages (at least one page) */
+static int64_t ceil_bp(int64_t n, int64_t bp);
+static int64_t clamp_i(int64_t x, int64_t lo, int64_t hi);
+static int64_t budget_of(const oracle_plan *pl, const int32_t *budget_per_seq, int b, int64_t P)
+{
+    if (budget_per_seq && budget_per_seq[b] > 0) return budget_per_seq[b];
+    return pl->budget_pages > 0 ? pl->budget_pages : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
 }
 
 static int64_t ceil_bp(int64_t n, int64_t bp) { return (n * bp + 9999) / 10000; }
@@ -263,7 +293,7 @@ static int64_t clamp_i(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo :
  */
 int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_vec, const float *grid_vec,
                   const int32_t *seq_lens, int32_t batch, const oracle_geom *g, const oracle_plan *pl,
-                  int32_t max_sel, int32_t *page_ids, int32_t *n_selected,
+                  const int32_t *budget_per_seq, int32_t max_sel, int32_t *page_ids, int32_t *n_selected,
                   uint8_t *kept_grid, uint8_t *kept_chunk, int32_t *counts)
 {
     const int d = g->head_dim, B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
@@ -289,8 +319,7 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
                 if (P > max_sel) { rc = -1; break; }
                 for (int64_t j = 0; j < P; ++j) ids[n++] = (int32_t)j;
             } else {
-                const int64_t k = pl->budget_pages > 0 ? pl->budget_pages
-                                                       : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
+                const int64_t k = budget_of(pl, budget_per_seq, b, P);
                 const int64_t kc_target = ceil_div((int64_t)pl->over_chunk * k, Nc);
                 probe_for(pl, q, page_vec, g, b, h, P, probe);
 
@@ -303,7 +332,7 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
                 if (pl->plan == ORACLE_PLAN_RATIO) k_g = clamp_i(ceil_bp(m, pl->rho_g_bp), 1, m);
                 else if (pl->plan == ORACLE_PLAN_FLAT) k_g = m;
                 else k_g = clamp_i(ceil_div((int64_t)pl->over_grid * kc_target, Ng), 0, m);
-                keep_top(cand, m, k_g, kg);
+                k_g = keep_top(cand, m, k_g, pl->cut_rule, kg);
 
                 /* level 2: chunks whose parent grid was kept */
                 m = 0;
@@ -314,7 +343,7 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
                 if (pl->plan == ORACLE_PLAN_RATIO) k_c = clamp_i(ceil_bp(m, pl->rho_c_bp), 1, m);
                 else if (pl->plan == ORACLE_PLAN_FLAT) k_c = m;
                 else k_c = clamp_i(kc_target, 0, m);
-                keep_top(cand, m, k_c, kc);
+                k_c = keep_top(cand, m, k_c, pl->cut_rule, kc);
 
                 /* level 3: pages whose parent chunk was kept, safety pages excluded */
                 m = 0;
@@ -324,7 +353,7 @@ int oracle_select(const uint16_t *q, const float *page_vec, const float *chunk_v
                 }
                 if (pl->plan == ORACLE_PLAN_RATIO) k_p = m == 0 ? 0 : clamp_i(ceil_bp(m, pl->rho_p_bp), 1, m);
                 else k_p = clamp_i(k, 0, m);
-                keep_top(cand, m, k_p, kp);
+                k_p = keep_top(cand, m, k_p, pl->cut_rule, kp);
 
                 /* union with sinks and the recent window, ascending */
                 if (s + k_p + w > max_sel) { rc = -1; break; }
@@ -389,8 +418,8 @@ static double shared_score(int32_t n_layers, const float *const *probes, const f
  */
 int oracle_select_shared(int32_t n_layers, const float *const *probes, const float *const *page_vec,
                          const float *const *chunk_vec, const float *const *grid_vec, const int32_t *seq_lens,
-                         int32_t batch, const oracle_geom *g, const oracle_plan *pl, int32_t max_sel,
-                         int32_t *page_ids, int32_t *n_selected, int32_t *counts)
+                         int32_t batch, const oracle_geom *g, const oracle_plan *pl, const int32_t *budget_per_seq,
+                         int32_t max_sel, int32_t *page_ids, int32_t *n_selected, int32_t *counts)
 {
     const int B = g->page_size, Nc = g->pages_per_chunk, Ng = g->chunks_per_grid;
     const int64_t cs = chunk_stride(g), gs = grid_stride(g);
@@ -411,7 +440,7 @@ int oracle_select_shared(int32_t n_layers, const float *const *probes, const flo
             if (P > max_sel) { rc = -1; break; }
             for (int64_t j = 0; j < P; ++j) ids[n++] = (int32_t)j;
         } else {
-            const int64_t k = pl->budget_pages > 0 ? pl->budget_pages : clamp_i(ceil_bp(P, pl->budget_bp), 1, P);
+            const int64_t k = budget_of(pl, budget_per_seq, b, P);
             const int64_t kc_target = ceil_div((int64_t)pl->over_chunk * k, Nc);
 
             int64_t m = 0;                          /* level 1: every grid */
@@ -422,7 +451,7 @@ int oracle_select_shared(int32_t n_layers, const float *const *probes, const flo
             if (pl->plan == ORACLE_PLAN_RATIO) k_g = clamp_i(ceil_bp(m, pl->rho_g_bp), 1, m);
             else if (pl->plan == ORACLE_PLAN_FLAT) k_g = m;
             else k_g = clamp_i(ceil_div((int64_t)pl->over_grid * kc_target, Ng), 0, m);
-            keep_top(cand, m, k_g, kg);
+            k_g = keep_top(cand, m, k_g, pl->cut_rule, kg);
 
             m = 0;                                  /* level 2: chunks of kept grids */
             for (int64_t u = 0; u < nc; ++u) if (kg[u / Ng]) {
@@ -432,7 +461,7 @@ int oracle_select_shared(int32_t n_layers, const float *const *probes, const flo
             if (pl->plan == ORACLE_PLAN_RATIO) k_c = clamp_i(ceil_bp(m, pl->rho_c_bp), 1, m);
             else if (pl->plan == ORACLE_PLAN_FLAT) k_c = m;
             else k_c = clamp_i(kc_target, 0, m);
-            keep_top(cand, m, k_c, kc);
+            k_c = keep_top(cand, m, k_c, pl->cut_rule, kc);
 
             m = 0;                                  /* level 3: pages of kept chunks, safety pages excluded */
             for (int64_t u = s; u < P - w; ++u) if (kc[u / Nc]) {
@@ -441,7 +470,7 @@ int oracle_select_shared(int32_t n_layers, const float *const *probes, const flo
             }
             if (pl->plan == ORACLE_PLAN_RATIO) k_p = m == 0 ? 0 : clamp_i(ceil_bp(m, pl->rho_p_bp), 1, m);
             else k_p = clamp_i(k, 0, m);
-            keep_top(cand, m, k_p, kp);
+            k_p = keep_top(cand, m, k_p, pl->cut_rule, kp);
 
             if (s + k_p + w > max_sel) { rc = -1; break; }
             for (int64_t j = 0; j < P; ++j)

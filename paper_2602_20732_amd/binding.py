@@ -13,6 +13,8 @@ import torch
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
 PROBE_QUERY, PROBE_ANCHOR = 0, 1
+CUT_COUNT, CUT_THRESHOLD = 0, 1
+SUMMARY_F32, SUMMARY_BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libchess.so")
@@ -30,13 +32,15 @@ class ChessError(RuntimeError):
 class _CConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("n_q_heads", "n_kv_heads", "head_dim", "page_size", "pages_per_chunk", "chunks_per_grid",
-                 "max_batch", "max_pages_per_seq", "max_selected_pages")] + [("sm_scale", ctypes.c_float)]
+                 "max_batch", "max_pages_per_seq", "max_selected_pages")] + [("sm_scale", ctypes.c_float),
+                                                                              ("summary_dtype", ctypes.c_int32),
+                                                                              ("shared_device", ctypes.c_int32)]
 
 
 class _CPlan(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
                 ("plan", "sink_pages", "window_pages", "budget_pages", "budget_bp", "over_chunk", "over_grid",
-                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe")]
+                 "rho_g_bp", "rho_c_bp", "rho_p_bp", "probe", "cut_rule")] + [("budget_per_seq", ctypes.c_void_p)]
 
 
 @dataclass(frozen=True)
@@ -51,6 +55,8 @@ class Config:
     chunks_per_grid: int = 8
     head_dim: int = 128
     sm_scale: float = 0.0
+    summary_dtype: int = SUMMARY_F32
+    shared_device: bool = False
 
 
 @dataclass(frozen=True)
@@ -66,10 +72,14 @@ class SelectPlan:
     rho_c_bp: int = 10000
     rho_p_bp: int = 10000
     probe: int = PROBE_QUERY
+    cut_rule: int = CUT_COUNT
+    budget_per_seq: object = None      # device int32 tensor [batch] or None (the caller keeps it alive)
 
     def _c(self) -> _CPlan:
+        per = None if self.budget_per_seq is None else ctypes.c_void_p(self.budget_per_seq.data_ptr())
         return _CPlan(self.plan, self.sink_pages, self.window_pages, self.budget_pages, self.budget_bp,
-                      self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe)
+                      self.over_chunk, self.over_grid, self.rho_g_bp, self.rho_c_bp, self.rho_p_bp, self.probe,
+                      self.cut_rule, per)
 
 
 def library_path() -> str:
@@ -112,7 +122,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_debug_force_cluster.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_force_general_cut.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_set_poll_limit.argtypes = [vp, ctypes.c_int32]
-        lib.chess_workspace_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        lib.chess_workspace_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
         lib.chess_strerror.argtypes = [ctypes.c_int]
         lib.chess_strerror.restype = ctypes.c_char_p
         lib.chess_version.restype = ctypes.c_int
@@ -136,7 +146,8 @@ class Chess:
         self.lib = load_library()
         self.cfg = cfg
         c = _CConfig(cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_size, cfg.pages_per_chunk,
-                     cfg.chunks_per_grid, cfg.max_batch, cfg.max_pages_per_seq, cfg.max_selected_pages, cfg.sm_scale)
+                     cfg.chunks_per_grid, cfg.max_batch, cfg.max_pages_per_seq, cfg.max_selected_pages, cfg.sm_scale,
+                     cfg.summary_dtype, int(bool(cfg.shared_device)))
         h = ctypes.c_void_p()
         self._check(self.lib.chess_create(ctypes.byref(c), ctypes.byref(h)))
         self._h = h
@@ -270,7 +281,7 @@ class Chess:
 
     def workspace_error(self, workspace) -> int:
         flag = ctypes.c_int32()
-        self._check(self.lib.chess_workspace_error(self._h, _ptr(workspace), ctypes.byref(flag)))
+        self._check(self.lib.chess_workspace_error(self._h, _ptr(workspace), ctypes.byref(flag), _stream()))
         return flag.value
 
     def debug_force_cluster(self, cluster: int):

@@ -27,11 +27,15 @@ bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
     if (pl->sink_pages < 0 || pl->window_pages < 0) return false;
     if (pl->probe != CHESS_PROBE_QUERY && pl->probe != CHESS_PROBE_ANCHOR) return false;
     if (pl->probe == CHESS_PROBE_ANCHOR && pl->window_pages < 1) return false;
+    if (pl->cut_rule != CHESS_CUT_COUNT && pl->cut_rule != CHESS_CUT_THRESHOLD) return false;
     const int64_t cand = std::max<int64_t>(0, P - pl->sink_pages - pl->window_pages);   // pages that may compete
     int64_t kmax = 0;
     if (pl->plan != CHESS_PLAN_RATIO) {
         if (pl->budget_pages < 0 || (pl->budget_pages == 0 && (pl->budget_bp < 1 || pl->budget_bp > 10000))) return false;
         kmax = pl->budget_pages > 0 ? pl->budget_pages : clampi(ceil_bp(P, pl->budget_bp), 1, P);
+        // budgets the host cannot see: size every level for the largest one a page_ids row can hold
+        if (pl->budget_per_seq != nullptr)
+            kmax = std::max<int64_t>(kmax, std::max<int64_t>(1, (int64_t)g.max_sel - pl->sink_pages - pl->window_pages));
     }
     Bounds b{};
     switch (pl->plan) {
@@ -135,6 +139,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     if (cfg->max_batch < 1 || cfg->max_pages_per_seq < 1 || cfg->max_selected_pages < 1) return CHESS_EINVAL;
     if (cfg->max_selected_pages > cfg->max_pages_per_seq) return CHESS_EINVAL;
     if (!(cfg->sm_scale >= 0.f) || !std::isfinite(cfg->sm_scale)) return CHESS_EINVAL;
+    if (cfg->summary_dtype != CHESS_SUMMARY_F32 && cfg->summary_dtype != CHESS_SUMMARY_BF16) return CHESS_EINVAL;
+    if (cfg->summary_dtype == CHESS_SUMMARY_BF16) return CHESS_ENOTSUP;
 
     chess_ctx* c = new (std::nothrow) chess_ctx();
     if (!c) return CHESS_ENOMEM;
@@ -265,7 +271,7 @@ int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream)
 // All workgroups of the grid have to fit on the device at once (the members wait for each other's keys).
 static int64_t choose_cluster(const chess_ctx* ctx, int64_t pairs, int64_t capacity)
 {
-    if (pairs >= ctx->n_cu) return 1;
+    if (pairs >= ctx->n_cu || ctx->cfg.shared_device != 0) return 1;
     const int64_t tiles = cdiv(ctx->geom.max_sel, chess::kTileTokens / ctx->geom.page_size);
     return std::max<int64_t>(1, std::min<int64_t>(capacity / pairs, clampi(cdiv(tiles, 8), 8, 12)));
 }
@@ -289,6 +295,8 @@ static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::
     sp.probe = plan->probe;
     sp.poll_limit = ctx->poll_limit > 0 ? ctx->poll_limit : (1 << 15);
     sp.general_cut = ctx->force_general_cut;
+    sp.budget_per_seq = plan->plan == CHESS_PLAN_RATIO ? nullptr : plan->budget_per_seq;
+    if (plan->cut_rule != CHESS_CUT_COUNT) return CHESS_ENOTSUP;
     *out = sp;
     return CHESS_OK;
 }
@@ -330,7 +338,7 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     const int64_t capacity = (int64_t)ctx->occ_blocks * ctx->n_cu;
     int64_t cluster = choose_cluster(ctx, pairs, capacity);
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
-    cluster = clampi(cluster, 1, chess::kSelMaxCluster);
+    cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSelMaxCluster);
 
     sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
     const chess::SelectWs ws = select_ws(ctx, workspace);
@@ -484,7 +492,7 @@ int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* 
     if (capacity < batch) return CHESS_ENOTSUP;
     int64_t cluster = capacity / batch;
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, cluster);
-    cluster = clampi(cluster, 1, chess::kSharedMaxCluster);
+    cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSharedMaxCluster);
     sp.local_grids = 0;
     const chess::SelectWs ws = select_ws(ctx, workspace);
     hipError_t e = chess::launch_select_shared(ctx, tab, seq_lens, batch, (int)cluster, sp, ws, lds, page_ids, n_selected,
@@ -521,7 +529,7 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
     const int64_t capacity = (int64_t)ctx->step_occ_blocks * ctx->n_cu;
     int64_t cluster = choose_cluster(ctx, pairs, capacity);
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
-    cluster = clampi(cluster, 1, chess::kSelMaxCluster);
+    cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSelMaxCluster);
     if (pairs * cluster > 4LL * ctx->n_cu + pairs) return CHESS_ENOTSUP;   // partial rows of the workspace
     sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
 
@@ -538,10 +546,15 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
-int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag)
+int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag, void* stream)
 {
     if (!ctx || !workspace || !flag) return CHESS_EINVAL;
-    hipError_t e = hipMemcpy(flag, static_cast<const char*>(workspace) + ctx->ws_err_off, sizeof(int32_t), hipMemcpyDeviceToHost);
+    // ordered behind everything launched on the caller's stream (a copy on the null stream would not wait for
+    // work on a non-blocking stream)
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(flag, static_cast<const char*>(workspace) + ctx->ws_err_off, sizeof(int32_t),
+                                  hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include "../../include/chess.h"
+#include "../../include/chess_debug.h"
 
 namespace chess {
 
@@ -30,7 +31,17 @@ struct SelectParams {
     int32_t poll_limit;              // polls before a wait for published keys is given up
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
     int32_t local_grids;             // every member scores all grids itself (no exchange at the grid level)
+    const int32_t* budget_per_seq;   // device [batch] or null: a value > 0 is that sequence's page budget
 };
+
+// The page budget the plan fixes for sequence b, or 0 when it is derived from the sequence's page count:
+// budget_per_seq[b] when given and positive (clamped to what a page_ids row can hold), else budget_pages.
+__device__ __forceinline__ int fixed_budget(const SelectParams& sp, const Geom& g, int b)
+{
+    const int per = sp.budget_per_seq != nullptr ? sp.budget_per_seq[b] : 0;
+    const int room = g.max_sel - sp.sink - sp.window;
+    return per > 0 ? (per < room ? per : (room > 1 ? room : 1)) : sp.budget_pages;
+}
 
 #ifndef CHESS_SEL_THREADS
 #define CHESS_SEL_THREADS 256

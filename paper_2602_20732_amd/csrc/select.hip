@@ -29,6 +29,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     int32_t* ids = page_ids + row * g.max_sel;
     const int B = g.page_size;
     const int L_raw = seq_lens[b];
+    const int k_fixed = fixed_budget(sp, g, b);
     double pr[8];
     if (sp.probe == CHESS_PROBE_QUERY)                                // requested before anything waits on the length
         load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     CascadeResult res;
     const bool ok = cascade<false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
                                    grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, m == 0, keys,
-                                   kept_grids, kept_chunks, sel_pages, sh, &res, prof, nullptr, [] {});
+                                   kept_grids, kept_chunks, sel_pages, sh, &res, prof, nullptr, [] {}, k_fixed);
     if (!ok) {
         if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;

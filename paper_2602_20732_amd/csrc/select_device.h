@@ -901,7 +901,8 @@ __device__ __forceinline__ PubLayout pub_layout(uint64_t* row_words, const Geom&
 // The three levels for one (sequence, KV head) with P > sink + window pages.  Member m of C scores the m-th
 // part of every level.  With want_l3 every member ends up with the kept page numbers in sel_pages[0 .. n_kp);
 // without it a member returns as soon as its level-3 keys are published (n_kp = 0).  sh.hist must be all
-// zero and sh.n_mem zero on entry.  Returns false if a wait was given up.
+// zero and sh.n_mem zero on entry.  Returns false if a wait was given up.  k_fixed > 0: the page budget of this
+// sequence (fixed_budget); 0: derived from its page count.
 // The levels run through one copy of the code (a loop, not three inlined bodies): the kernel executes every
 // instruction about once, so its time is sensitive to how much code it has to fetch.
 //
@@ -923,12 +924,12 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
                                         const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
                                         Shared& sh, CascadeResult* res, Prof& prof, const uint64_t* tail_words,
-                                        TailFn refresh_tail, const int32_t* __restrict__ bt_row = nullptr,
+                                        TailFn refresh_tail, int k_fixed, const int32_t* __restrict__ bt_row = nullptr,
                                         int32_t* phys_by_slot = nullptr, int32_t* sel_phys = nullptr)
 {
     const int s = sp.sink, w = sp.window;
     const int nc = ceil_div_i(P, g.n_c), ng = ceil_div_i(nc, g.n_g);
-    const int k_budget = sp.budget_pages > 0 ? sp.budget_pages : clamp_i(ceil_bp(P, sp.budget_bp), 1, P);
+    const int k_budget = k_fixed > 0 ? k_fixed : clamp_i(ceil_bp(P, sp.budget_bp), 1, P);
     const int kc_target = ceil_div_i(sp.over_chunk * k_budget, g.n_c);
     const int plan = sp.plan;
     const bool general = sp.general_cut != 0;
@@ -1075,12 +1076,12 @@ __device__ __forceinline__ bool cascade(const float* __restrict__ pages_row, con
                                         const SelectParams& sp, const PubLayout& pubs, int m, int C, bool want_l3,
                                         uint64_t* keys, int32_t* kept_grids, int32_t* kept_chunks, int32_t* sel_pages,
                                         Shared& sh, CascadeResult* res, Prof& prof, const uint64_t* tail_words,
-                                        TailFn refresh_tail, const int32_t* __restrict__ bt_row = nullptr,
+                                        TailFn refresh_tail, int k_fixed, const int32_t* __restrict__ bt_row = nullptr,
                                         int32_t* phys_by_slot = nullptr, int32_t* sel_phys = nullptr)
 {
     const HeadScorer scorer{pages_row, chunks_row, grids_row, pr};
     return cascade_with<kPhys>(scorer, P, g, sp, pubs, m, C, want_l3, keys, kept_grids, kept_chunks, sel_pages, sh, res,
-                               prof, tail_words, refresh_tail, bt_row, phys_by_slot, sel_phys);
+                               prof, tail_words, refresh_tail, k_fixed, bt_row, phys_by_slot, sel_phys);
 }
 
 // Clear the published words of one (sequence, KV head) after everybody is done with them.

@@ -167,6 +167,7 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
     if (tid < 3) sh.tail_key[tid] = 0ull;
     if (tid == 0) sh.poll_limit = sp.poll_limit;
     const int L = min(max(seq_lens[b], 0), g.max_pages * B);
+    const int k_fixed = fixed_budget(sp, g, b);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
     // the list is the same for every KV head of the sequence: it is written H times, in the layout the
@@ -187,7 +188,7 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
     CascadeResult res;
     const SharedScorer scorer{tab, b, g, red};
     const bool ok = cascade_with<false>(scorer, P, g, sp, pubs, m, C, m == 0, keys, kept_grids, kept_chunks, sel_pages, sh,
-                                        &res, prof, nullptr, [] {});
+                                        &res, prof, nullptr, [] {}, k_fixed);
     if (!ok) {
         if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;

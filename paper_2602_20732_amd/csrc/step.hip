@@ -151,6 +151,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     const uint16_t* q_rows = a.q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     float* out_rows = a.out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     const int L_raw = a.seq_lens[b];
+    const int k_fixed = fixed_budget(sp, g, b);
     double pr[8];
     if (sp.probe == CHESS_PROBE_QUERY) load_probe(q_rows, G, pr);     // requested before anything waits on the length
     for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
         if (safety_early && tid < s + w) safety_phys = bt_row[safety_lp];
         // kept pages and their physical pages go straight to their places in the list, behind the sinks
         const bool ok = cascade<true>(pages_row, chunks_row, grids_row, pr, P, g, sp, pubs, m, C, true, keys, kept_grids,
-                                      kept_chunks, ids_l + s, sh, &res, prof, tail_words, refresh_tail, bt_row,
+                                      kept_chunks, ids_l + s, sh, &res, prof, tail_words, refresh_tail, k_fixed, bt_row,
                                       phys_by_slot, phys_l + s);
         if (!ok) {
             if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

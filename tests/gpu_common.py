@@ -21,7 +21,10 @@ def config_of(sp: workload.WorkloadSpec, max_selected=None, max_batch=None) -> p
 
 
 def gpu_plan(op: oracle.Plan) -> pk.SelectPlan:
-    return pk.SelectPlan(**{f: getattr(op, f) for f in op.__dataclass_fields__})
+    kw = {f: getattr(op, f) for f in op.__dataclass_fields__}
+    if kw["budget_per_seq"] is not None:                     # the library takes the per-sequence budgets from device memory
+        kw["budget_per_seq"] = torch.as_tensor(list(kw["budget_per_seq"]), dtype=torch.int32, device="cuda")
+    return pk.SelectPlan(**kw)
 
 
 @dataclass

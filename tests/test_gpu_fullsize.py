@@ -17,9 +17,9 @@ pytestmark = pytest.mark.gpu
 ATOL = 1e-2
 
 
-def run_case(name, sample, dense_seq=0, seed=None):
+def run_case(name, sample, dense_seq=0, seed=None, layer=0):
     sp = workload.spec(name)
-    wl = workload.generate(sp, workload.default_seed(name) if seed is None else seed, device="cuda")
+    wl = workload.generate(sp, workload.default_seed(name) if seed is None else seed, layer=layer, device="cuda")
     lib = pk.Chess(config_of(sp))
     plan = plan_of(sp)
     summ, ws = lib.new_summaries(), lib.new_workspace()
@@ -35,10 +35,25 @@ def run_case(name, sample, dense_seq=0, seed=None):
     # the same step through the single-launch entry point, as bench.py times it
     ids2, nsel2, out2 = torch.full_like(ids, -7), torch.full_like(nsel, -7), torch.full_like(out, float("nan"))
     lib.decode_step(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, gpu_plan(plan), ids2, nsel2, out2, ws)
+    # ... and exactly the call bench.py times: the tail page / chunk / grid vectors are stale (junk here) and the
+    # launch refreshes them itself (refresh_tail), automatic cluster, before it scores them
+    summ3 = summ.clone()
+    pv3, cv3, gv3 = lib.summary_views(summ3)
+    for b in range(sp.batch):
+        P = -(-int(wl.seq_lens[b]) // sp.page_size)
+        if P > 0:
+            tp = P - 1; tc = tp // sp.pages_per_chunk; tg = tc // sp.chunks_per_grid
+            pv3[b, :, tp] = 12345.0; cv3[b, :, tc] = -777.0; gv3[b, :, tg] = 31.0
+    ids3, nsel3, out3 = torch.full_like(ids, -7), torch.full_like(nsel, -7), torch.full_like(out, float("nan"))
+    lib.decode_step(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ3, gpu_plan(plan), ids3, nsel3, out3, ws,
+                    refresh_tail=True)
     torch.cuda.synchronize()
     assert lib.workspace_error(ws) == 0
     assert torch.equal(ids2, ids) and torch.equal(nsel2, nsel), (name, "fused step: page lists differ")
+    assert torch.equal(summ3, summ), (name, "fused step with refresh_tail: the refreshed summaries differ bit-wise")
+    assert torch.equal(ids3, ids) and torch.equal(nsel3, nsel), (name, "fused step with refresh_tail: page lists differ")
     out2_h = out2.cpu().numpy()
+    out3_h = out3.cpu().numpy()
     pv, cv, gv = (t.cpu().numpy() for t in lib.summary_views(summ))
     ids_h, nsel_h, out_h, dense_h = ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dense.cpu().numpy()
     assert np.isfinite(out_h).all() and np.isfinite(dense_h).all()
@@ -57,8 +72,10 @@ def run_case(name, sample, dense_seq=0, seed=None):
         assert np.array_equal(nsel_h[b], rn[i]) and np.array_equal(ids_h[b], rids[i]), (name, b, "page lists")
         err = np.abs(out_h[b] - rout[i]).max()
         err2 = np.abs(out2_h[b] - rout[i]).max()
-        print(f"[{name}] seq {b}: page lists exact, max|out - oracle| = {err:.2e} (two calls), {err2:.2e} (fused step)")
-        assert err <= ATOL and err2 <= ATOL
+        err3 = np.abs(out3_h[b] - rout[i]).max()
+        print(f"[{name}] seq {b}: page lists exact, max|out - oracle| = {err:.2e} (two calls), {err2:.2e} (fused step), "
+              f"{err3:.2e} (fused step refreshing the tail, as timed)")
+        assert err <= ATOL and err2 <= ATOL and err3 <= ATOL
     # every sequence, not only the sampled ones: list shape invariants
     for b in range(sp.batch):
         P = -(-int(wl.seq_lens[b]) // B)
@@ -81,6 +98,11 @@ def test_cfg2_full():
 
 def test_cfg3_one_layer_full_batch():
     run_case("cfg3", [0, 13, 31], dense_seq=13)
+
+
+def test_cfg3_last_layer_of_the_stack():
+    """cfg3 is a stack of 32 layers with fresh seeded KV each; the last one, as bench.py generates it."""
+    run_case("cfg3", [7], dense_seq=None, layer=31)
 
 
 def test_cfg4a_full():

@@ -23,9 +23,16 @@ def lib():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "chess.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(chess_[a-z_]+)\s*\(", text)))
+    """Every function the public header and the test-hook header declare."""
+    names = set()
+    for header in ("chess.h", "chess_debug.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found = set(re.findall(r"\b(chess_[a-z_]+)\s*\(", text))
+        hooks = {n for n in found if n.startswith("chess_debug_")}
+        assert hooks == (found if header == "chess_debug.h" else set()), "test hooks, and only they, belong in chess_debug.h"
+        names |= found
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol(lib):

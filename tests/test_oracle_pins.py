@@ -175,9 +175,10 @@ def test_softmax_is_stable_for_large_logits():
     np.testing.assert_allclose(out[0, 0], softmax_attention(bf16_to_f64(Q[0, 0]), Kl, Vl, 1 / np.sqrt(d)), atol=1e-6)
 
 
-def _exact_cascade(a, Nc, Ng, plan, rho=None, k=None):
+def _exact_cascade(a, Nc, Ng, plan, rho=None, k=None, threshold=False):
     """Brute-force cascade on exact rational page scores ``a`` (no sink / window), written independently
-    of the oracle: every level sorts (score desc, index asc) with Python's sort on Fractions."""
+    of the oracle: every level sorts (score desc, index asc) with Python's sort on Fractions.
+    threshold: Alg. 1 stage 2 as printed -- a level keeps every active unit whose score is >= the kk-th largest."""
     P = len(a)
     nc, ng = -(-P // Nc), -(-(-(-P // Nc)) // Ng)
     ps = [Fraction(x) for x in a]
@@ -185,7 +186,11 @@ def _exact_cascade(a, Nc, Ng, plan, rho=None, k=None):
     gs = [sum(cs[u * Ng:min(nc, (u + 1) * Ng)]) / len(cs[u * Ng:min(nc, (u + 1) * Ng)]) for u in range(ng)]
 
     def top(cands, sc, kk):
-        return set(sorted(cands, key=lambda i: (-sc[i], i))[:kk])
+        order = sorted(cands, key=lambda i: (-sc[i], i))
+        if threshold and 0 < kk <= len(order):
+            tau = sc[order[kk - 1]]
+            return {i for i in cands if sc[i] >= tau}
+        return set(order[:kk])
 
     def cnt(n, bp):
         return max(1, min(n, -(-n * bp // 10000)))
@@ -255,6 +260,102 @@ def test_cascade_matches_exact_bruteforce_with_many_ties(seed):
     ids, nsel = oracle.select(Q, pv, cv, gv, sl, g, oracle.Plan(plan=oracle.PLAN_FLAT, sink_pages=0, window_pages=0,
                                                                  budget_pages=k), P)
     assert ids[0, 0, :nsel[0, 0]].tolist() == _exact_cascade(a, Nc, Ng, "flat", k=k)
+
+
+# ------------------------------------------------------------------ Alg. 1 stage 2 as printed: S >= tau keeps every tie
+@pytest.mark.parametrize("seed", range(8))
+def test_threshold_rule_matches_exact_bruteforce_with_many_ties(seed):
+    """Small integer scores, so every level has ties at its cut: under the threshold rule all of them survive, and
+    the next level counts its active units from that larger set.  Exact rational brute force (dyadic cases)."""
+    rng = np.random.default_rng(100 + seed)
+    Nc, Ng = int(rng.choice([1, 2, 4])), int(rng.choice([1, 2, 4]))
+    P = Nc * Ng * int(rng.integers(2, 9))
+    a = rng.integers(-2, 3, size=P).tolist()
+    K, V, Q, bt, sl, g = _one_hot_problem(a, Nc, Ng)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    rho = [int(x) for x in rng.choice([2500, 3300, 5000, 7500], 3)]
+    plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=0, window_pages=0, rho_g_bp=rho[0], rho_c_bp=rho[1],
+                       rho_p_bp=rho[2], cut_rule=oracle.CUT_THRESHOLD)
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, g, plan, P)
+    want = _exact_cascade(a, Nc, Ng, "ratio", rho=rho, threshold=True)
+    assert ids[0, 0, :nsel[0, 0]].tolist() == want
+    exact_count = _exact_cascade(a, Nc, Ng, "ratio", rho=rho)
+    assert len(want) >= len(exact_count)
+    k = int(rng.integers(1, P))
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, g, oracle.Plan(plan=oracle.PLAN_FLAT, sink_pages=0, window_pages=0,
+                                                                 budget_pages=k, cut_rule=oracle.CUT_THRESHOLD), P)
+    want = _exact_cascade(a, Nc, Ng, "flat", k=k, threshold=True)
+    assert ids[0, 0, :nsel[0, 0]].tolist() == want and len(want) >= k
+    kth = sorted(a, reverse=True)[k - 1]
+    assert want == [i for i in range(P) if a[i] >= kth]
+
+
+def test_threshold_rule_special_cases(ragged):
+    """No ties (continuous scores): the threshold rule keeps exactly the count rule's units.  All keys identical:
+    every level's units all tie at tau, so every candidate page survives (the list is every page).  Negative
+    scores: tau is taken over the active units only (an inactive unit is never ranked, not even as a zero)."""
+    sp, wl, (K, V, Q, bt, sl) = ragged
+    g = geom_of(sp)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    for kw in (dict(), dict(plan=oracle.PLAN_RATIO, rho_g_bp=6000, rho_c_bp=5000, rho_p_bp=2000)):
+        a = oracle.select(Q, pv, cv, gv, sl, g, plan_of(sp, **kw), sp.max_pages, detail=True)
+        b = oracle.select(Q, pv, cv, gv, sl, g, plan_of(sp, cut_rule=oracle.CUT_THRESHOLD, **kw), sp.max_pages, detail=True)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    # identical keys
+    L, d, B = 48 * 4, 16, 4
+    rng = np.random.default_rng(3)
+    Klog = np.tile(rng.standard_normal((1, 1, d)).astype(np.float32), (L, 1, 1))
+    K2, V2, bt2 = pack_pools(Klog, Klog, B)
+    g2 = oracle.Geometry(1, 1, d, B, 2, 2, 48)
+    Q2 = f32_to_bf16_bits(rng.standard_normal((1, 1, d)).astype(np.float32))
+    sl2 = np.array([L], np.int32)
+    s2 = oracle.summarize(K2, bt2, sl2, g2)
+    plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=1, window_pages=2, rho_g_bp=3000, rho_c_bp=3000, rho_p_bp=3000,
+                       cut_rule=oracle.CUT_THRESHOLD)
+    ids, nsel, kg, kc, cnt = oracle.select(Q2, *s2, sl2, g2, plan, 48, detail=True)
+    assert nsel[0, 0] == 48 and ids[0, 0].tolist() == list(range(48)) and cnt[0, 0].tolist() == [12, 24, 45]
+    # negative scores (every page scores below zero; half of the grids are inactive at chunk level)
+    a = [-5, -6, -1, -2, -9, -9, -7, -8]
+    K3, V3, Q3, bt3, sl3, g3 = _one_hot_problem(a, 2, 2)
+    s3 = oracle.summarize(K3, bt3, sl3, g3)
+    plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=0, window_pages=0, rho_g_bp=5000, rho_c_bp=5000, rho_p_bp=5000,
+                       cut_rule=oracle.CUT_THRESHOLD)
+    ids, nsel = oracle.select(Q3, *s3, sl3, g3, plan, 8)
+    assert ids[0, 0, :nsel[0, 0]].tolist() == [2]          # grid 0 (mean -3.5) -> chunk 1 (-1.5) -> page 2 (-1)
+
+
+# ------------------------------------------------------------------ per-sequence budgets
+def test_per_sequence_budgets(ragged):
+    """budget_per_seq[b] > 0 is sequence b's page budget k; an entry <= 0 falls back to the plan's own budget.
+    Flat plan: brute-force top-k_b per sequence (numpy); budget plan: the same lists as one call per sequence with
+    that fixed budget."""
+    sp, wl, (K, V, Q, bt, sl) = ragged
+    g = geom_of(sp)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g)
+    per = (7, 0, 3)
+    s, w = sp.sink_pages, sp.window_pages
+    ps, _, _ = oracle.scores(Q, pv, cv, gv, sl, g)
+    flat = plan_of(sp, plan=oracle.PLAN_FLAT, budget_per_seq=per)
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, g, flat, sp.max_pages)
+    for b in range(sp.batch):
+        P = -(-int(sl[b]) // sp.page_size)
+        k = per[b] if per[b] > 0 else max(1, -(-P * sp.budget_bp // 10000))
+        for h in range(sp.n_kv_heads):
+            cand = np.arange(s, P - w)
+            top = cand[np.argsort(-ps[b, h, cand], kind="stable")][:k]
+            assert ids[b, h, :nsel[b, h]].tolist() == list(range(s)) + sorted(top.tolist()) + list(range(P - w, P))
+    both = oracle.select(Q, pv, cv, gv, sl, g, plan_of(sp, budget_per_seq=per), sp.max_pages, detail=True)
+    for b in range(sp.batch):
+        one = oracle.select(Q[b:b + 1], pv[b:b + 1], cv[b:b + 1], gv[b:b + 1], sl[b:b + 1], g,
+                            plan_of(sp, budget_pages=max(per[b], 0)), sp.max_pages, detail=True)
+        assert all(np.array_equal(x[b:b + 1], y) for x, y in zip(both, one))
+    # the model-wide scope takes the same per-sequence budgets
+    probes = [oracle.anchor(pv, sl, g, w)]
+    sids, sn, scnt = oracle.select_shared(probes, [pv], [cv], [gv], sl, g, plan_of(sp, budget_per_seq=per), sp.max_pages, detail=True)
+    for b in range(sp.batch):
+        P = -(-int(sl[b]) // sp.page_size)
+        k = per[b] if per[b] > 0 else max(1, -(-P * sp.budget_bp // 10000))
+        assert sn[b] == s + w + min(k, scnt[b, 2]) and scnt[b, 2] <= k
 
 
 # ------------------------------------------------------------------ P7: Table 1 budgets
