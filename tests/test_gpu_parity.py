@@ -451,3 +451,60 @@ def test_error_codes():
         pk.Chess(pk.Config(8, 3, 16, 1, 64, 8))          # 8 q heads over 3 kv heads
     with pytest.raises(pk.ChessError):
         pk.Chess(pk.Config(8, 2, 24, 1, 64, 8))          # page size
+
+
+@pytest.mark.parametrize("plan_kw", [dict(plan=oracle.PLAN_BUDGET), dict(plan=oracle.PLAN_FLAT),
+                                     dict(plan=oracle.PLAN_BUDGET, probe=oracle.PROBE_ANCHOR)])
+def test_per_sequence_budgets(plan_kw):
+    """budget_per_seq (device int32 [batch]): ragged budgets in one batch, an entry <= 0 falls back to the plan's
+    own budget; select, the fused step and the model-wide scope against the oracle with the same budgets."""
+    sp = RAGGED
+    wl = workload.generate(sp, 79, seq_lens=RAGGED_LENS)
+    per = (12, 0, 3, 5, 2)
+    check_all(sp, wl, plan_of(sp, budget_per_seq=per, **plan_kw), max_sel=sp.max_pages, label=f"per-seq budgets {plan_kw}")
+    # a budget above what a page_ids row can hold is clamped to the room the row has
+    small = 1 + 2 + 6
+    plan = plan_of(sp, budget_per_seq=(500, 0, 3, 5, 2), **plan_kw)
+    lib = pk.Chess(config_of(sp, max_selected=small))
+    gpu = run_gpu(lib, wl, plan, dense=False)
+    ref = run_oracle(wl, plan_of(sp, budget_per_seq=(6, 0, 3, 5, 2), **plan_kw), small, dense=False)
+    assert np.array_equal(gpu.ids, ref.ids) and np.array_equal(gpu.nsel, ref.nsel)
+    assert np.array_equal(gpu.step_ids, ref.ids) and np.array_equal(gpu.step_nsel, ref.nsel)
+    lib.close()
+
+
+def test_shared_device_switch_never_waits():
+    """chess_config.shared_device: every (sequence, KV head) is one workgroup's, so no launch waits for another
+    workgroup.  With a poll limit of 1 (any wait would give up at once and raise the error flag) select, the fused
+    step with its tail refresh and the model-wide selection must still return the oracle's lists, flag clear."""
+    sp = workload.spec("cfg2", scale=1 / 2)
+    wl = workload.generate(sp, workload.default_seed("cfg2"))
+    plan = plan_of(sp)
+    ref = run_oracle(wl, plan, sp.max_selected, dense=False)
+    d = to_device(wl)
+    import dataclasses
+    lib = pk.Chess(dataclasses.replace(config_of(sp), shared_device=True))
+    lib.debug_set_poll_limit(1)
+    lib.debug_force_cluster(8)                                       # must not override the switch
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    ids = torch.full((1, sp.n_kv_heads, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((1, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+    lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
+    assert lib.workspace_error(ws) == 0
+    assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+    ids.fill_(-7); nsel.fill_(-7)
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws,
+                    refresh_tail=True)
+    assert lib.workspace_error(ws) == 0
+    assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+    assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
+    anc = torch.empty((1, sp.n_kv_heads, 128), device="cuda")
+    lib.anchor(summ, d.seq_lens, plan.window_pages, anc)
+    lib.select_shared([anc], [summ], d.seq_lens, gpu_plan(plan), ids, nsel, ws)
+    assert lib.workspace_error(ws) == 0
+    oanc = oracle.anchor(ref.pages, ref.host[4], geom_of(sp), plan.window_pages)
+    sids, sn = oracle.select_shared([oanc], [ref.pages], [ref.chunks], [ref.grids], ref.host[4], geom_of(sp), plan, sp.max_selected)
+    assert all(np.array_equal(ids[:, h].cpu().numpy(), sids) for h in range(sp.n_kv_heads))
+    lib.close()
