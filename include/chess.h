@@ -47,6 +47,7 @@ extern "C" {
 #define CHESS_ENOTSUP  (-2)  /* valid request this build cannot serve (e.g. too many candidates for LDS) */
 #define CHESS_EHIP     (-3)  /* the HIP runtime reported an error at launch                   */
 #define CHESS_ENOMEM   (-4)  /* host allocation of the context failed                         */
+#define CHESS_ESCRATCH (-5)  /* chess_sparse_decode_static: the call needs more than CHESS_STATIC_SCRATCH_BYTES */
 
 /* How the per-level keep-counts of the cascade are derived (Sec. 3.2; Alg. 1 stage 2). */
 #define CHESS_PLAN_BUDGET 0  /* page budget k; chunk / grid counts from oversampling factors  */
@@ -69,6 +70,8 @@ extern "C" {
                               /* stored (bf16) child vectors; half the bytes the selection reads             */
 
 #define CHESS_MAX_LAYERS 64   /* most layers one chess_select_shared call can take */
+
+#define CHESS_STATIC_SCRATCH_BYTES (4u << 20)   /* device scratch chess_sparse_decode_static owns, per GPU */
 
 typedef struct chess_ctx chess_ctx; /* opaque; small host-side state only */
 
@@ -308,6 +311,19 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
  * Results written by such a launch are undefined, and published words are left behind: check the flag (or
  * re-initialise the workspace) before the workspace is used again. */
 int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag, void* stream);
+
+/*
+ * chess_sparse_decode for callers that cannot allocate device memory (code under HIP graph capture that was not
+ * handed a workspace, tight serving loops, harnesses that forbid hipMalloc): the same kernels and results, with
+ * the split partials and arrival counters in a device array the library owns (CHESS_STATIC_SCRATCH_BYTES per
+ * GPU, alive until the process ends) instead of a caller's workspace.  No allocation of any kind happens in the
+ * call.  CHESS_ESCRATCH if batch * H_kv * (splits chosen for this shape) needs more than the array holds.
+ * Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two streams, two
+ * contexts) race; calls on one stream are safe.
+ */
+int chess_sparse_decode_static(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
+                               const int32_t* n_selected, int32_t batch, float* out, void* stream);
 
 const char* chess_strerror(int code);
 int chess_version(void);

@@ -21,7 +21,7 @@ _LIB_PATH = os.path.join(_HERE, "libchess.so")
 _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
-           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_monitor_step", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_dense_decode", "chess_decode_step",
+           "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_monitor_step", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_sparse_decode_static", "chess_dense_decode", "chess_decode_step",
            "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
@@ -116,6 +116,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_select_shared.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int32, i32p, ctypes.c_int32,
                                             ctypes.POINTER(_CPlan), i32p, i32p, vp, vp]
         lib.chess_sparse_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp, vp]
+        lib.chess_sparse_decode_static.argtypes = [vp, vp, vp, vp, i32p, i32p, i32p, i32p, ctypes.c_int32, vp, vp]
         lib.chess_dense_decode.argtypes = [vp, vp, vp, vp, i32p, i32p, ctypes.c_int32, vp, vp, vp]
         lib.chess_decode_step.argtypes = [vp, vp, vp, vp, i32p, i32p, vp, ctypes.c_int32, ctypes.c_int32, vp, i32p, i32p, vp, vp, vp]
         lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
@@ -266,6 +267,11 @@ class Chess:
         self._check(self.lib.chess_sparse_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
                                                  _ptr(seq_lens), _ptr(page_ids), _ptr(n_selected), seq_lens.shape[0],
                                                  _ptr(out), _ptr(workspace), _stream()))
+
+    def sparse_decode_static(self, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, out):
+        self._check(self.lib.chess_sparse_decode_static(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),
+                                                        _ptr(seq_lens), _ptr(page_ids), _ptr(n_selected), seq_lens.shape[0],
+                                                        _ptr(out), _stream()))
 
     def dense_decode(self, q, k_pool, v_pool, block_table, seq_lens, out, workspace):
         self._check(self.lib.chess_dense_decode(self._h, _ptr(q), _ptr(k_pool), _ptr(v_pool), _ptr(block_table),

@@ -4,13 +4,40 @@
 #include <cmath>
 #include <cstdlib>
 #include <initializer_list>
+#include <mutex>
 #include <new>
 
 #include "chess_internal.h"
 
+// Device memory chess_sparse_decode_static works in instead of a caller's workspace: split partials and arrival
+// counters.  Every GPU the library runs on holds its own copy at its own address, for the life of the process.
+// In host code this name is only a handle for hipGetSymbolAddress: kernels and fills get the looked-up address.
+static __device__ __align__(256) unsigned char scratch[CHESS_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using chess::kHeadDim;
+
+// Per device: the address of that device's copy of `scratch`, looked up once (by chess_create, with the device
+// current).
+constexpr int kMaxDevices = 64;
+void* g_scratch_of_device[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+void* scratch_of_current_device(int dev)
+{
+    if (dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_of_device[dev] == nullptr) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();                    // leave no sticky error behind; the static entry point reports it
+            return nullptr;
+        }
+        g_scratch_of_device[dev] = p;
+    }
+    return g_scratch_of_device[dev];
+}
 
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline int64_t ceil_bp(int64_t n, int64_t bp) { return (n * bp + 9999) / 10000; }
@@ -197,6 +224,7 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_zero_bytes = c->workspace_bytes - c->ws_keys_off;
     c->force_splits = 0;
     c->force_waves = 4;
+    c->static_scratch = scratch_of_current_device(dev);
     *out = c;
     return CHESS_OK;
 }
@@ -587,6 +615,38 @@ int chess_sparse_decode(chess_ctx* ctx, const void* q, const void* k_pool, const
     return decode_common(ctx, q, k_pool, v_pool, block_table, seq_lens, page_ids, n_selected, batch, out, workspace, stream);
 }
 
+int chess_sparse_decode_static(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
+                               const int32_t* block_table, const int32_t* seq_lens, const int32_t* page_ids,
+                               const int32_t* n_selected, int32_t batch, float* out, void* stream)
+{
+    if (!ctx || !q || !k_pool || !v_pool || !block_table || !seq_lens || !page_ids || !n_selected || !out) return CHESS_EINVAL;
+    if (batch < 1 || batch > ctx->cfg.max_batch) return CHESS_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) | reinterpret_cast<uintptr_t>(q) |
+         reinterpret_cast<uintptr_t>(out)) & 15) return CHESS_EINVAL;
+    // the array's address was looked up for the device the context was created on
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != ctx->device || ctx->static_scratch == nullptr) return CHESS_EHIP;
+    const SplitShape sh = choose_splits(ctx, batch, ctx->geom.max_sel, true);
+    // layout inside the array: arrival counters [rows] | partial rows [rows][splits][G][128] | (m, l) [rows][splits][G]
+    const size_t rows = (size_t)batch * ctx->geom.n_kv_heads;
+    const size_t part_rows = sh.n_splits > 1 ? rows * sh.n_splits * ctx->geom.group : 0;
+    const size_t acc_off = align_up(rows * sizeof(int32_t), 256);
+    const size_t ml_off = align_up(acc_off + part_rows * kHeadDim * sizeof(float), 256);
+    const size_t need = ml_off + part_rows * 2 * sizeof(float);
+    if (need > (size_t)CHESS_STATIC_SCRATCH_BYTES) return CHESS_ESCRATCH;
+    char* base = static_cast<char*>(ctx->static_scratch);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // whatever the previous call on this GPU left where the counters are (another context's partials, say) goes
+    // first: a small fill kernel, not a memset node, so that the call can be captured in a graph
+    hipError_t e = chess::launch_zero(ctx, reinterpret_cast<int32_t*>(base), rows, s);
+    if (e != hipSuccess) return CHESS_EHIP;
+    e = chess::launch_decode(ctx, static_cast<const uint16_t*>(q), static_cast<const uint16_t*>(k_pool),
+                             static_cast<const uint16_t*>(v_pool), block_table, seq_lens, page_ids, n_selected, batch,
+                             sh.n_splits, sh.waves, out, reinterpret_cast<float*>(base + acc_off),
+                             reinterpret_cast<float*>(base + ml_off), reinterpret_cast<int32_t*>(base), s);
+    return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
+}
+
 int chess_dense_decode(chess_ctx* ctx, const void* q, const void* k_pool, const void* v_pool,
                        const int32_t* block_table, const int32_t* seq_lens, int32_t batch, float* out,
                        void* workspace, void* stream)
@@ -613,6 +673,7 @@ const char* chess_strerror(int code)
     case CHESS_ENOTSUP: return "not supported (a selection level would have more candidates than fit in LDS)";
     case CHESS_EHIP: return "HIP runtime error at kernel launch";
     case CHESS_ENOMEM: return "out of host memory";
+    case CHESS_ESCRATCH: return "the call needs more device scratch than chess_sparse_decode_static owns (CHESS_STATIC_SCRATCH_BYTES)";
     default: return "unknown error code";
     }
 }

@@ -122,6 +122,7 @@ struct chess_ctx {
     int step_occ_lds, step_occ_blocks;                     // ... and of the fused step kernel
     int shared_occ_lds, shared_occ_blocks;                 // ... and of the model-wide select kernel
     size_t ws_zero_off, ws_zero_bytes;                     // the part chess_workspace_init clears
+    void* static_scratch;                                  // this device's copy of the library's own scratch array (or null)
 };
 
 namespace chess {
