@@ -78,7 +78,8 @@ def shared_scope(lib, sp, seq_lens, lens, plan, n_layers, timed):
     summs, probes = [], []
     for _ in range(n_layers):
         s = lib.new_summaries()
-        s.view(torch.float32).normal_(generator=gen)
+        for t in lib.summary_views(s):
+            t.normal_(generator=gen)
         summs.append(s)
         probes.append(torch.empty((sp.batch, sp.n_kv_heads, sp.head_dim), device="cuda"))
     ws = lib.new_workspace()

@@ -62,7 +62,14 @@ extern "C" {
 /* How many units a level keeps once its count k is known (Alg. 1 stage 2 thresholds at a quantile). */
 #define CHESS_CUT_COUNT     0 /* exactly k units; ties at the cut go to the lower index                      */
 #define CHESS_CUT_THRESHOLD 1 /* every unit whose score is >= the k-th largest score (S >= tau as printed in */
-                              /* Alg. 1): ties at the cut are all kept, so a level may keep more than k      */
+                              /* Alg. 1): ties at the cut are all kept, so a level may keep more than k.     */
+                              /* Grid and chunk lists are sized for every unit; a page list that outgrows    */
+                              /* max_selected_pages is cut short (lowest pages first) and the launch raises  */
+                              /* CHESS_FLAG_OVERFLOW in the workspace's error word                           */
+
+/* Bits of the word chess_workspace_error reads. */
+#define CHESS_FLAG_WAIT     1 /* a bounded wait between workgroups was given up: results undefined          */
+#define CHESS_FLAG_OVERFLOW 2 /* CHESS_CUT_THRESHOLD kept more pages than a page_ids row holds: list cut short */
 
 /* Storage type of the summary vectors (the paper only says "compact vector"). */
 #define CHESS_SUMMARY_F32  0  /* fp32: the fp64 mean rounded once                                            */
@@ -305,11 +312,12 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
                       void* workspace, void* stream);
 
 /* Synchronous check: copies the workspace's error word back on `stream` and waits for that stream (so it sees
- * every launch made on it before; work on other streams is not waited for).  *flag is non-zero if any kernel
- * using this workspace gave up a bounded wait -- which cannot happen unless the device was shared with work
- * that kept this library's workgroups from becoming resident together (see chess_config.shared_device).
- * Results written by such a launch are undefined, and published words are left behind: check the flag (or
- * re-initialise the workspace) before the workspace is used again. */
+ * every launch made on it before; work on other streams is not waited for).  *flag receives CHESS_FLAG_* bits,
+ * which stay set until chess_workspace_init.  CHESS_FLAG_WAIT: a kernel using this workspace gave up a bounded
+ * wait -- which cannot happen unless the device was shared with work that kept this library's workgroups from
+ * becoming resident together (see chess_config.shared_device).  Results written by such a launch are undefined,
+ * and published words are left behind: check the flag (or re-initialise the workspace) before the workspace is
+ * used again.  CHESS_FLAG_OVERFLOW: see CHESS_CUT_THRESHOLD; the workspace stays usable. */
 int chess_workspace_error(chess_ctx* ctx, const void* workspace, int32_t* flag, void* stream);
 
 /*

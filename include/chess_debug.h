@@ -15,6 +15,11 @@ extern "C" {
  * chess_select and chess_decode_step (1..32, capped by what can be resident at once); 0 restores the automatic choice. */
 int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster);
 
+/* Test hook: the schedule of the selection levels in chess_select and chess_decode_step: 1 = lazy (grids, chunks
+ * of kept grids, pages of kept chunks: three memory phases), 2 = merged (all chunks scored together with the grids:
+ * two phases); 0 restores the automatic choice.  The selected pages are the same either way. */
+int chess_debug_force_schedule(chess_ctx* ctx, int32_t schedule);
+
 /* Test hook: on = 1 makes every level of chess_select find its cut by the general path (radix select
  * on the keys in LDS) that otherwise only serves tied or very large levels; 0 restores the automatic
  * choice.  The selected pages are the same either way. */

@@ -24,6 +24,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 PLAN_BUDGET, PLAN_RATIO, PLAN_FLAT = 0, 1, 2
 PROBE_QUERY, PROBE_ANCHOR = 0, 1         # what units are scored against: the query sum, or the Eq. 3 key anchor
+SUMMARY_F32, SUMMARY_BF16 = 0, 1         # storage type of the summary vectors
 CUT_COUNT, CUT_THRESHOLD = 0, 1          # a level keeps exactly k units / every unit scoring >= the k-th (Alg. 1's S >= tau)
 
 
@@ -38,7 +39,8 @@ def build(force: bool = False) -> str:
 
 class _Geom(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in
-                ("n_q_heads", "n_kv_heads", "head_dim", "page_size", "pages_per_chunk", "chunks_per_grid", "max_pages")]
+                ("n_q_heads", "n_kv_heads", "head_dim", "page_size", "pages_per_chunk", "chunks_per_grid", "max_pages",
+                 "summary_dtype")]
 
 
 class _Plan(ctypes.Structure):
@@ -56,6 +58,7 @@ class Geometry:
     pages_per_chunk: int
     chunks_per_grid: int
     max_pages: int
+    summary_dtype: int = 0          # SUMMARY_F32 | SUMMARY_BF16: how a summary vector is stored (the arrays stay float32)
 
     @property
     def max_chunks(self) -> int:
@@ -67,7 +70,7 @@ class Geometry:
 
     def _c(self) -> _Geom:
         return _Geom(self.n_q_heads, self.n_kv_heads, self.head_dim, self.page_size, self.pages_per_chunk,
-                     self.chunks_per_grid, self.max_pages)
+                     self.chunks_per_grid, self.max_pages, self.summary_dtype)
 
 
 @dataclass(frozen=True)

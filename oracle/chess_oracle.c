@@ -37,6 +37,8 @@
  *     per-head dots, Eq. 1's Flatten restricted to the group);
  *   - a partial tail page / last chunk / last grid is averaged over the
  *     members that exist;
+ *   - the paper calls a summary a "compact vector" and gives no storage type: fp32 (the fp64 mean rounded once),
+ *     or bf16 (that fp32 value rounded to nearest-even bf16; parents average the stored children): a switch;
  *   - "top rho fraction" keeps exactly ceil(rho * n) of the n units that are
  *     active at that level (the reading under which Table 1's budgets are the
  *     products of the three ratios); rank order is score descending, index
@@ -63,6 +65,7 @@
 enum { ORACLE_PLAN_BUDGET = 0, ORACLE_PLAN_RATIO = 1, ORACLE_PLAN_FLAT = 2 };
 enum { ORACLE_PROBE_QUERY = 0, ORACLE_PROBE_ANCHOR = 1 };
 enum { ORACLE_CUT_COUNT = 0, ORACLE_CUT_THRESHOLD = 1 };
+enum { ORACLE_SUMMARY_F32 = 0, ORACLE_SUMMARY_BF16 = 1 };
 
 typedef struct {
     int32_t n_q_heads;       /* H_q                                        */
@@ -73,6 +76,10 @@ typedef struct {
     int32_t chunks_per_grid; /* N_g                                        */
     int32_t max_pages;       /* row stride of the block table and of the
                                 per-level summary arrays (in pages)        */
+    int32_t summary_dtype;   /* ORACLE_SUMMARY_*: how a summary vector is stored.  F32: the fp64 mean rounded to
+                                fp32 once.  BF16: that fp32 value rounded to the nearest bf16 (ties to even); a
+                                chunk / grid then averages its children AS STORED.  The arrays stay float
+                                either way (a bf16 value is a float whose low 16 bits are zero)            */
 } oracle_geom;
 
 typedef struct {
@@ -100,6 +107,20 @@ static double bf16_value(uint16_t h)
 }
 
 static int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+/* a mean as the summaries store it (finite values): fp32, or fp32 rounded to the nearest bf16, ties to even */
+static float stored_mean(double mean, int summary_dtype)
+{
+    float f = (float)mean;
+    if (summary_dtype == ORACLE_SUMMARY_BF16) {
+        uint32_t u;
+        memcpy(&u, &f, sizeof u);
+        u += 0x7fffu + ((u >> 16) & 1u);
+        u &= 0xffff0000u;
+        memcpy(&f, &u, sizeof f);
+    }
+    return f;
+}
 
 /* max row counts of the chunk and grid arrays for a given page stride */
 static int64_t chunk_stride(const oracle_geom *g) { return ceil_div(g->max_pages, g->pages_per_chunk); }
@@ -142,7 +163,7 @@ void oracle_summarize(const uint16_t *k_pool, const int32_t *block_table, const 
                 for (int i = 0; i < d; ++i) {
                     double acc = 0.0;
                     for (int t = 0; t < n; ++t) acc += k_at(k_pool, g, phys, h, t, i);
-                    pv[j * d + i] = (float)(acc / (double)n);
+                    pv[j * d + i] = stored_mean(acc / (double)n, g->summary_dtype);
                 }
             }
             for (int64_t c = 0; c < nc; ++c) {               /* Eq. 2, chunks */
@@ -150,7 +171,7 @@ void oracle_summarize(const uint16_t *k_pool, const int32_t *block_table, const 
                 for (int i = 0; i < d; ++i) {
                     double acc = 0.0;
                     for (int64_t j = lo; j < hi; ++j) acc += (double)pv[j * d + i];
-                    cv[c * d + i] = (float)(acc / (double)(hi - lo));
+                    cv[c * d + i] = stored_mean(acc / (double)(hi - lo), g->summary_dtype);
                 }
             }
             for (int64_t k = 0; k < ng; ++k) {               /* Eq. 2, grids */
@@ -158,7 +179,7 @@ void oracle_summarize(const uint16_t *k_pool, const int32_t *block_table, const 
                 for (int i = 0; i < d; ++i) {
                     double acc = 0.0;
                     for (int64_t c = lo; c < hi; ++c) acc += (double)cv[c * d + i];
-                    gv[k * d + i] = (float)(acc / (double)(hi - lo));
+                    gv[k * d + i] = stored_mean(acc / (double)(hi - lo), g->summary_dtype);
                 }
             }
         }

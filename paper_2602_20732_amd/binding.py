@@ -22,7 +22,7 @@ _lib = None
 
 EXPORTS = ["chess_create", "chess_destroy", "chess_summary_bytes", "chess_summary_layout", "chess_workspace_bytes", "chess_workspace_init",
            "chess_summarize", "chess_summarize_tail", "chess_summarize_recent", "chess_append_kv", "chess_select", "chess_anchor", "chess_select_shared", "chess_entropy", "chess_trigger_update", "chess_monitor_step", "chess_extend_window", "chess_reuse_step", "chess_sparse_decode", "chess_sparse_decode_static", "chess_dense_decode", "chess_decode_step",
-           "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
+           "chess_debug_force_splits", "chess_debug_force_cluster", "chess_debug_force_schedule", "chess_debug_force_general_cut", "chess_debug_set_poll_limit", "chess_workspace_error", "chess_strerror", "chess_version"]
 
 
 class ChessError(RuntimeError):
@@ -122,6 +122,7 @@ def load_library() -> ctypes.CDLL:
         lib.chess_debug_force_splits.argtypes = [vp, ctypes.c_int32, ctypes.c_int32]
         lib.chess_debug_force_cluster.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_force_general_cut.argtypes = [vp, ctypes.c_int32]
+        lib.chess_debug_force_schedule.argtypes = [vp, ctypes.c_int32]
         lib.chess_debug_set_poll_limit.argtypes = [vp, ctypes.c_int32]
         lib.chess_workspace_error.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32), vp]
         lib.chess_strerror.argtypes = [ctypes.c_int]
@@ -186,14 +187,16 @@ class Chess:
         return ws
 
     def summary_views(self, summaries: torch.Tensor):
-        """(pages, chunks, grids) fp32 views [max_batch, H_kv, units, d] of a summaries buffer."""
+        """(pages, chunks, grids) views [max_batch, H_kv, units, d] of a summaries buffer, fp32 or bf16 by the
+        configuration's summary_dtype."""
         c = self.cfg
         mc = -(-c.max_pages_per_seq // c.pages_per_chunk)
         mg = -(-mc // c.chunks_per_grid)
+        dt, size = (torch.bfloat16, 2) if c.summary_dtype == SUMMARY_BF16 else (torch.float32, 4)
         out = []
         for off, units in zip(self.summary_offsets, (c.max_pages_per_seq, mc, mg)):
             n = c.max_batch * c.n_kv_heads * units * c.head_dim
-            out.append(summaries[off:off + 4 * n].view(torch.float32).view(c.max_batch, c.n_kv_heads, units, c.head_dim))
+            out.append(summaries[off:off + size * n].view(dt).view(c.max_batch, c.n_kv_heads, units, c.head_dim))
         return tuple(out)
 
     # ---- the C entry points
@@ -292,6 +295,10 @@ class Chess:
 
     def debug_force_cluster(self, cluster: int):
         self._check(self.lib.chess_debug_force_cluster(self._h, cluster))
+
+    def debug_force_schedule(self, schedule: int):
+        """0 = automatic, 1 = lazy, 2 = merged."""
+        self._check(self.lib.chess_debug_force_schedule(self._h, schedule))
 
     def debug_force_general_cut(self, on: bool):
         self._check(self.lib.chess_debug_force_general_cut(self._h, int(bool(on))))

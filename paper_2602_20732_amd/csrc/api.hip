@@ -45,7 +45,7 @@ inline int64_t clampi(int64_t x, int64_t lo, int64_t hi) { return x < lo ? lo : 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Largest keep-counts any sequence of at most max_pages pages can reach under `pl`.
-struct Bounds { int64_t kg, kc, kp, slots, lists; };
+struct Bounds { int64_t kg, kc, kp, kp_exact, slots, lists; };
 
 bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
 {
@@ -88,7 +88,15 @@ bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
     default:
         return false;
     }
-    b.slots = std::max<int64_t>(ng, std::max<int64_t>(b.kg * g.n_g, b.kc * g.n_c));
+    b.kp_exact = b.kp;
+    if (pl->cut_rule == CHESS_CUT_THRESHOLD) {
+        // ties at a cut are all kept, so a level can keep up to everything it has: the lists and the page slots are
+        // sized for that, and only a page list that outgrows its page_ids row is an error (reported by the kernels)
+        b.kg = ng;
+        b.kc = nc;
+        b.kp = std::min<int64_t>(cand, std::max<int64_t>(0, (int64_t)g.max_sel - pl->sink_pages - pl->window_pages));
+    }
+    b.slots = std::max<int64_t>(ng + nc, b.kc * g.n_c);       // grid and chunk keys by unit, side by side; then the page slots
     b.lists = std::max<int64_t>(b.kg, b.kc);
     *out = b;
     return true;
@@ -167,7 +175,6 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     if (cfg->max_selected_pages > cfg->max_pages_per_seq) return CHESS_EINVAL;
     if (!(cfg->sm_scale >= 0.f) || !std::isfinite(cfg->sm_scale)) return CHESS_EINVAL;
     if (cfg->summary_dtype != CHESS_SUMMARY_F32 && cfg->summary_dtype != CHESS_SUMMARY_BF16) return CHESS_EINVAL;
-    if (cfg->summary_dtype == CHESS_SUMMARY_BF16) return CHESS_ENOTSUP;
 
     chess_ctx* c = new (std::nothrow) chess_ctx();
     if (!c) return CHESS_ENOMEM;
@@ -189,10 +196,11 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
 
     const size_t rows = (size_t)cfg->max_batch * g.n_kv_heads;
     const size_t vec = kHeadDim * sizeof(float);
+    const size_t svec = kHeadDim * (cfg->summary_dtype == CHESS_SUMMARY_BF16 ? sizeof(uint16_t) : sizeof(float));
     c->page_off = 0;
-    c->chunk_off = align_up(c->page_off + rows * g.max_pages * vec, 256);
-    c->grid_off = align_up(c->chunk_off + rows * g.max_chunks * vec, 256);
-    c->summary_bytes = align_up(c->grid_off + rows * g.max_grids * vec, 256);
+    c->chunk_off = align_up(c->page_off + rows * g.max_pages * svec, 256);
+    c->grid_off = align_up(c->chunk_off + rows * g.max_chunks * svec, 256);
+    c->summary_bytes = align_up(c->grid_off + rows * g.max_grids * svec, 256);
 
     c->max_splits = 256;
     const size_t part_rows = (size_t)(4 * c->n_cu + rows) * g.group;       // see choose_splits
@@ -204,14 +212,14 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->ws_meta_off = align_up(c->ws_tail_off + rows * 4 * sizeof(uint64_t), 256);
     c->ws_cnt_off = align_up(c->ws_meta_off + rows * chess::kSelMetaStride * sizeof(int32_t), 256);
     c->ws_err_off = align_up(c->ws_cnt_off + rows * sizeof(int32_t), 256);
-    c->ws_prof_off = align_up(c->ws_err_off + 256, 256);            // profiling builds only: 48 words per row
-    c->ws_ent_off = align_up(c->ws_prof_off + rows * 48 * sizeof(int32_t), 256);
+    c->ws_ent_off = align_up(c->ws_err_off + 256, 256);
     c->ws_entcnt_off = align_up(c->ws_ent_off + (size_t)cfg->max_batch * chess::kEntMaxSplits * 4 * sizeof(float), 256);
     c->workspace_bytes = align_up(c->ws_entcnt_off + (size_t)cfg->max_batch * sizeof(int32_t), 256);
     c->dec_blocks4 = c->dec_blocks1 = 2;
     if (chess::decode_occupancy(g.page_size, 4, g.group, &v) == hipSuccess && v > 0) c->dec_blocks4 = v;
     if (chess::decode_occupancy(g.page_size, 1, g.group, &v) == hipSuccess && v > 0) c->dec_blocks1 = v;
     c->force_cluster = 0;
+    c->force_schedule = 0;
     c->force_general_cut = 0;
     c->poll_limit = 0;
     c->occ_lds = -1;
@@ -222,6 +230,10 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     c->step_occ_blocks = 0;
     c->ws_zero_off = c->ws_keys_off;
     c->ws_zero_bytes = c->workspace_bytes - c->ws_keys_off;
+    c->ws_prof_off = c->workspace_bytes;
+#ifdef CHESS_PROF
+    c->workspace_bytes += align_up(rows * 2 * 24 * sizeof(int32_t), 256);   // profiling builds: two timelines of 24 stamps per row, at the end
+#endif
     c->force_splits = 0;
     c->force_waves = 4;
     c->static_scratch = scratch_of_current_device(dev);
@@ -260,9 +272,8 @@ static int summarize_common(chess_ctx* ctx, const void* k_pool, const int32_t* b
     if ((reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(summaries)) & 15) return CHESS_EINVAL;
     char* sb = static_cast<char*>(summaries);
     hipError_t e = chess::launch_summarize(ctx, static_cast<const uint16_t*>(k_pool), block_table, seq_lens, batch,
-                                           from_page, recent, reinterpret_cast<float*>(sb + ctx->page_off),
-                                           reinterpret_cast<float*>(sb + ctx->chunk_off),
-                                           reinterpret_cast<float*>(sb + ctx->grid_off), static_cast<hipStream_t>(stream));
+                                           from_page, recent, sb + ctx->page_off, sb + ctx->chunk_off, sb + ctx->grid_off,
+                                           static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
 
@@ -304,12 +315,23 @@ static int64_t choose_cluster(const chess_ctx* ctx, int64_t pairs, int64_t capac
     return std::max<int64_t>(1, std::min<int64_t>(capacity / pairs, clampi(cdiv(tiles, 8), 8, 12)));
 }
 
+// Which schedule the levels run on (select_device.h).  merged: all chunks are scored with the grids, which saves a
+// dependent memory phase and an exchange for n_c - k_g N_g more chunk vectors; it pays while the launch is bound by
+// its chain of memory round trips rather than by bytes, i.e. while the (sequence, head) pairs do not outnumber the
+// compute units several times over.  Otherwise lazy, and every member scores all grids itself when they are few.
+static void choose_schedule(const chess_ctx* ctx, int64_t pairs, int64_t cluster, chess::SelectParams* sp)
+{
+    const int svec = kHeadDim * (ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16 ? 2 : 4);
+    sp->merged = ctx->force_schedule > 0 ? ctx->force_schedule == 2 : pairs <= 2 * (int64_t)ctx->n_cu;
+    sp->local_grids = pairs * cluster * ctx->geom.max_grids * svec <= (4LL << 20);   // repeated grid reads stay small
+}
+
 // Checks a plan against the configuration and fills the kernel-side parameters.
 static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::SelectParams* out)
 {
     Bounds bd;
     if (!plan_bounds(ctx, plan, &bd)) return CHESS_EINVAL;
-    if ((int64_t)plan->sink_pages + plan->window_pages + bd.kp > ctx->geom.max_sel) return CHESS_EINVAL;
+    if ((int64_t)plan->sink_pages + plan->window_pages + bd.kp_exact > ctx->geom.max_sel) return CHESS_EINVAL;
     chess::SelectParams sp{};
     sp.plan = plan->plan; sp.sink = plan->sink_pages; sp.window = plan->window_pages;
     sp.budget_pages = plan->budget_pages; sp.budget_bp = plan->budget_bp;
@@ -324,7 +346,7 @@ static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::
     sp.poll_limit = ctx->poll_limit > 0 ? ctx->poll_limit : (1 << 15);
     sp.general_cut = ctx->force_general_cut;
     sp.budget_per_seq = plan->plan == CHESS_PLAN_RATIO ? nullptr : plan->budget_per_seq;
-    if (plan->cut_rule != CHESS_CUT_COUNT) return CHESS_ENOTSUP;
+    sp.keep_ties = plan->cut_rule == CHESS_CUT_THRESHOLD;
     *out = sp;
     return CHESS_OK;
 }
@@ -356,9 +378,10 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
 
     // cluster size: the members of a cluster wait for each other's keys, so every workgroup of the grid has to fit
     // on the device at once
+    const bool bf16 = ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16;
     if (ctx->occ_lds != (int)lds) {
         int blocks = 0;
-        if (chess::select_occupancy((int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        if (chess::select_occupancy(bf16, (int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
         ctx->occ_lds = (int)lds;
         ctx->occ_blocks = blocks;
     }
@@ -368,13 +391,11 @@ int chess_select(chess_ctx* ctx, const void* q, const void* summaries, const int
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSelMaxCluster);
 
-    sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
+    choose_schedule(ctx, pairs, cluster, &sp);
     const chess::SelectWs ws = select_ws(ctx, workspace);
     const char* sb = static_cast<const char*>(summaries);
-    hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q),
-                                        reinterpret_cast<const float*>(sb + ctx->page_off),
-                                        reinterpret_cast<const float*>(sb + ctx->chunk_off),
-                                        reinterpret_cast<const float*>(sb + ctx->grid_off), seq_lens, batch, (int)cluster,
+    hipError_t e = chess::launch_select(ctx, static_cast<const uint16_t*>(q), sb + ctx->page_off, sb + ctx->chunk_off,
+                                        sb + ctx->grid_off, seq_lens, batch, (int)cluster,
                                         sp, ws, lds, page_ids, n_selected, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHESS_OK : CHESS_EHIP;
 }
@@ -510,7 +531,7 @@ int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* 
     if (lds + 10240 > (size_t)ctx->lds_per_block) return CHESS_ENOTSUP;  // the kernel's static LDS is below 10 KB
     if (ctx->shared_occ_lds != (int)lds) {
         int blocks = 0;
-        if (chess::select_shared_occupancy((int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        if (chess::select_shared_occupancy(ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16, (int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
         ctx->shared_occ_lds = (int)lds;
         ctx->shared_occ_blocks = blocks;
     }
@@ -522,6 +543,7 @@ int chess_select_shared(chess_ctx* ctx, const float* const* probes, const void* 
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, cluster);
     cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSharedMaxCluster);
     sp.local_grids = 0;
+    sp.merged = 0;                                   // a unit is n_layers * H_kv rows here: the launch is bound by bytes
     const chess::SelectWs ws = select_ws(ctx, workspace);
     hipError_t e = chess::launch_select_shared(ctx, tab, seq_lens, batch, (int)cluster, sp, ws, lds, page_ids, n_selected,
                                                static_cast<hipStream_t>(stream));
@@ -548,7 +570,7 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
 
     if (ctx->step_occ_lds != (int)lds) {
         int blocks = 0;
-        if (chess::step_occupancy(ctx->geom.page_size, (int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
+        if (chess::step_occupancy(ctx->geom.page_size, ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16, (int)lds, &blocks) != hipSuccess) return CHESS_EHIP;
         ctx->step_occ_lds = (int)lds;
         ctx->step_occ_blocks = blocks;
     }
@@ -559,13 +581,12 @@ int chess_decode_step(chess_ctx* ctx, const void* q, const void* k_pool, const v
     if (ctx->force_cluster > 0) cluster = std::min<int64_t>(ctx->force_cluster, capacity / pairs);
     cluster = ctx->cfg.shared_device != 0 ? 1 : clampi(cluster, 1, chess::kSelMaxCluster);
     if (pairs * cluster > 4LL * ctx->n_cu + pairs) return CHESS_ENOTSUP;   // partial rows of the workspace
-    sp.local_grids = pairs * cluster * ctx->geom.max_grids * 512 <= (4LL << 20);   // repeated grid reads stay small
+    choose_schedule(ctx, pairs, cluster, &sp);
 
     const chess::SelectWs ws = select_ws(ctx, workspace);
     char* sb = static_cast<char*>(summaries);
     char* wb = static_cast<char*>(workspace);
-    chess::StepLaunch sl{static_cast<const uint16_t*>(q), reinterpret_cast<float*>(sb + ctx->page_off),
-                         reinterpret_cast<float*>(sb + ctx->chunk_off), reinterpret_cast<float*>(sb + ctx->grid_off),
+    chess::StepLaunch sl{static_cast<const uint16_t*>(q), sb + ctx->page_off, sb + ctx->chunk_off, sb + ctx->grid_off,
                          static_cast<const uint16_t*>(k_pool), static_cast<const uint16_t*>(v_pool), block_table, seq_lens,
                          page_ids, n_selected, out, reinterpret_cast<float*>(wb + ctx->ws_acc_off),
                          reinterpret_cast<float*>(wb + ctx->ws_ml_off), reinterpret_cast<int32_t*>(wb + ctx->ws_cnt_off),
@@ -590,6 +611,13 @@ int chess_debug_force_cluster(chess_ctx* ctx, int32_t cluster)
 {
     if (!ctx || cluster < 0 || cluster > chess::kSelMaxCluster) return CHESS_EINVAL;
     ctx->force_cluster = cluster;
+    return CHESS_OK;
+}
+
+int chess_debug_force_schedule(chess_ctx* ctx, int32_t schedule)
+{
+    if (!ctx || schedule < 0 || schedule > 2) return CHESS_EINVAL;
+    ctx->force_schedule = schedule;
     return CHESS_OK;
 }
 

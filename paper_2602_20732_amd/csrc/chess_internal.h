@@ -31,6 +31,8 @@ struct SelectParams {
     int32_t poll_limit;              // polls before a wait for published keys is given up
     int32_t general_cut;             // test hook: every level takes the general (LDS radix) cut
     int32_t local_grids;             // every member scores all grids itself (no exchange at the grid level)
+    int32_t merged;                  // all chunks are scored together with the grids (one memory phase and one exchange fewer)
+    int32_t keep_ties;               // the threshold rule: a level keeps every unit that ties with its k-th
     const int32_t* budget_per_seq;   // device [batch] or null: a value > 0 is that sequence's page budget
 };
 
@@ -56,14 +58,27 @@ struct SelectWs {
     int64_t key_stride;              //   all zero between launches
     uint64_t* tail;                  // [rows][4] keys of the refreshed tail grid / chunk / page; zero between launches
     int32_t* meta;                   // [rows][kSelMetaStride], zero between launches
-    int32_t* error;                  // one word: set if a wait for published keys was given up
+    int32_t* error;                  // one word of kErr* bits
 #ifdef CHESS_PROF
-    int32_t* prof;                   // [rows][16] phase durations in 10 ns ticks (profiling builds only)
+    int32_t* prof;                   // [rows][Prof::kSlots] phase timestamps in 10 ns ticks (profiling builds only)
 #endif
 };
+constexpr int kErrWait = 1;          // a wait for published keys was given up
+constexpr int kErrOverflow = 2;      // the threshold rule kept more units than a list has room for (the list was cut short)
 
-// Values that cross workgroups inside one launch travel as agent-scope atomics, which are coherent
-// across the per-XCD L2s; plain stores would need an L2 write-back / invalidate on each side.
+// Values that cross workgroups inside one launch travel as agent-scope atomics: on gfx950 these are loads and
+// stores with the sc1 bit, which do not live in the per-XCD L2s as cached copies (a store is written through to
+// the memory side that all eight XCDs share before it is acknowledged, a load is served from there), so they are
+// coherent across the device without any cache maintenance.  Two kinds of message:
+//  * a published word that IS the message (a key, polled until it is non-zero) needs no ordering against anything
+//    else;
+//  * data announced by something else (split partials by the arrival counter): the writer's waves wait until their
+//    sc1 stores are acknowledged (s_waitcnt 0: by then they are at the shared memory side) before the workgroup's
+//    barrier and the arrival, and the reader's sc1 loads, issued after it has seen the last arrival, are served from
+//    that same place.  The language-level equivalent, a release fence before and an acquire fence after the arrival
+//    at agent scope, was measured: it compiles to a write-back and an invalidate of the whole L2 (buffer_wbl2 sc1 /
+//    buffer_inv sc1), which these accesses do not need, and costs 12 us per sparse-decode launch (14 -> 26 us).  So
+//    the ordering rests on the hardware behaviour above, with relaxed atomics, not on the abstract memory model.
 __device__ __forceinline__ void publish_u64(uint64_t* p, uint64_t v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -86,7 +101,7 @@ __device__ __forceinline__ float observe_f32(const float* p)
 // next launch.  Nobody waits.  The counter must be 0 before the first launch.
 __device__ __forceinline__ bool arrive_last(int32_t* counter, int expected, int* lds_flag)
 {
-    __builtin_amdgcn_s_waitcnt(0);                   // this wave's published stores are acknowledged
+    __builtin_amdgcn_s_waitcnt(0);                   // this wave's published stores are acknowledged, its loads have returned
     __syncthreads();
     if (threadIdx.x == 0) {
         const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -115,6 +130,7 @@ struct chess_ctx {
     size_t ws_keys_off, ws_tail_off, ws_meta_off, ws_cnt_off, ws_err_off, ws_prof_off;   // select scratch, decode arrival counters, error word
     int64_t key_stride;
     int force_cluster;                                     // 0 = automatic
+    int force_schedule;                                    // 0 = automatic, 1 = lazy, 2 = merged
     int force_general_cut;                                 // 0 = automatic
     int poll_limit;                                        // 0 = the default
     int dec_blocks4, dec_blocks1;                          // decode workgroups per CU with 4 waves / 1 wave
@@ -136,20 +152,21 @@ inline hipError_t launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t
 }
 
 // Launchers (each returns a hipError_t from the launch).
+// (summary arrays travel as void*: fp32 or bf16 by the context's summary_dtype)
 hipError_t launch_summarize(chess_ctx* ctx, const uint16_t* k_pool, const int32_t* block_table,
                             const int32_t* seq_lens, int batch, const int32_t* from_page, int recent,
-                            float* pages, float* chunks, float* grids, hipStream_t stream);
+                            void* pages, void* chunks, void* grids, hipStream_t stream);
 
-hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,
-                         const float* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
+hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const void* pages, const void* chunks,
+                         const void* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
                          const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream);
 // Device pointers of one fused decode-step launch.
 struct StepLaunch {
     const uint16_t* q;
-    float* pages;
-    float* chunks;
-    float* grids;
+    void* pages;
+    void* chunks;
+    void* grids;
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const int32_t* block_table;
@@ -165,8 +182,8 @@ struct StepLaunch {
 hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
                        const SelectWs& ws, size_t lds_bytes, int union_off, hipStream_t stream);
 size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off);
-hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu);
-hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu);
+hipError_t step_occupancy(int page_size, bool bf16, int lds_bytes, int* blocks_per_cu);
+hipError_t select_occupancy(bool bf16, int lds_bytes, int* blocks_per_cu);
 
 // The model-wide scope: per-layer probes (fp32 [batch][H_kv][128]) and summary buffers, passed by value.
 constexpr int kMaxLayers = CHESS_MAX_LAYERS;
@@ -184,7 +201,7 @@ struct AnchorTable {
 };
 hipError_t launch_anchor(chess_ctx* ctx, const AnchorTable& tab, int n_layers, const int32_t* seq_lens, int batch,
                          int window, hipStream_t stream);
-hipError_t select_shared_occupancy(int lds_bytes, int* blocks_per_cu);
+hipError_t select_shared_occupancy(bool bf16, int lds_bytes, int* blocks_per_cu);
 hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const int32_t* seq_lens, int batch, int cluster,
                                 const SelectParams& sp, const SelectWs& ws, size_t lds_bytes, int32_t* page_ids,
                                 int32_t* n_selected, hipStream_t stream);

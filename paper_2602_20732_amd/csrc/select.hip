@@ -5,11 +5,12 @@
 
 namespace chess {
 
-// grid = (C, H_kv, batch)
+// grid = (C, H_kv, batch); T = storage type of the summaries (float or bf16 bits)
+template <class T>
 __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __restrict__ q,
-                                                             const float* __restrict__ pages,
-                                                             const float* __restrict__ chunks,
-                                                             const float* __restrict__ grids,
+                                                             const T* __restrict__ pages,
+                                                             const T* __restrict__ chunks,
+                                                             const T* __restrict__ grids,
                                                              const int32_t* __restrict__ seq_lens, Geom g,
                                                              SelectParams sp, SelectWs ws,
                                                              int32_t* __restrict__ page_ids,
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
 
     const int m = blockIdx.x, C = gridDim.x, h = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     Prof prof;
-    prof.mark();
+    prof.mark(0);
     const size_t row = (size_t)b * g.n_kv_heads + h;
     int32_t* ids = page_ids + row * g.max_sel;
     const int B = g.page_size;
@@ -32,11 +33,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     const int k_fixed = fixed_budget(sp, g, b);
     double pr[8];
     if (sp.probe == CHESS_PROBE_QUERY)                                // requested before anything waits on the length
-        load_probe(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);
-    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
-    if (tid == 0) sh.n_mem = 0;
-    if (tid < 3) sh.tail_key[tid] = 0ull;
-    if (tid == 0) sh.poll_limit = sp.poll_limit;
+        load_probe<T>(q + ((size_t)b * g.n_q_heads + (size_t)h * g.group) * kHeadDim, g.group, pr);
+    init_shared(sh, sp.poll_limit);
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
@@ -47,17 +45,17 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
         }
         return;
     }
-    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor(pages + row * g.max_pages * kHeadDim, P, w, pr);
+    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor<T>(pages + row * g.max_pages * kHeadDim, P, w, pr);
     __syncthreads();
-    prof.mark();                                                      // 1: prologue done
+    prof.mark(1);                                                     // prologue done
 
-    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g, sp);
+    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g);
     CascadeResult res;
-    const bool ok = cascade<false>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
-                                   grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, m == 0, keys,
-                                   kept_grids, kept_chunks, sel_pages, sh, &res, prof, nullptr, [] {}, k_fixed);
+    const bool ok = cascade<false, T>(pages + row * g.max_pages * kHeadDim, chunks + row * g.max_chunks * kHeadDim,
+                                      grids + row * g.max_grids * kHeadDim, pr, P, g, sp, pubs, m, C, m == 0, keys,
+                                      kept_grids, kept_chunks, sel_pages, sh, &res, prof, nullptr, [] {}, k_fixed);
     if (!ok) {
-        if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_fetch_or(ws.error, kErrWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     if (C > 1) {
@@ -65,6 +63,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
         if (arrive_last(ws.meta + row * kSelMetaStride, C, &sh.flag)) clear_published(pubs, res);
     }
     if (m != 0) return;
+    if (res.overflow && tid == 0) __hip_atomic_fetch_or(ws.error, kErrOverflow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     // ---- union with the safety pages: sinks, kept pages, window -- already ascending
     const int n_kp = res.n_kp, n_sel = s + n_kp + w;
@@ -77,9 +76,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(const uint16_t* __r
     }
     if (tid == 0) n_selected[row] = n_sel;
 #ifdef CHESS_PROF
-    prof.mark();
-    if (tid == 0)
-        for (int i = 1; i < prof.n; ++i) ws.prof[row * 48 + i] = (int)(prof.t[i] - prof.t[i - 1]);
+    prof.mark(15);
+    if (tid == 0) prof.store(ws.prof + row * Prof::kSlots);
 #endif
 }
 
@@ -88,23 +86,29 @@ size_t select_lds_bytes(const SelectParams& sp, int max_sel)
     return (size_t)sp.cap_keys * 8 + ((size_t)(sp.cap_kg + sp.cap_kc + max_sel) * 4 + 7) / 8 * 8;
 }
 
-hipError_t select_occupancy(int lds_bytes, int* blocks_per_cu)
+hipError_t select_occupancy(bool bf16, int lds_bytes, int* blocks_per_cu)
 {
+    const void* kern = bf16 ? reinterpret_cast<const void*>(select_kernel<uint16_t>) : reinterpret_cast<const void*>(select_kernel<float>);
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_kernel, kSelThreads, lds_bytes);
+    return bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_kernel<uint16_t>, kSelThreads, lds_bytes)
+                : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_kernel<float>, kSelThreads, lds_bytes);
 }
 
-hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const float* pages, const float* chunks,
-                         const float* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
+hipError_t launch_select(chess_ctx* ctx, const uint16_t* q, const void* pages, const void* chunks,
+                         const void* grids, const int32_t* seq_lens, int batch, int cluster, const SelectParams& sp,
                          const SelectWs& ws, size_t lds_bytes, int32_t* page_ids, int32_t* n_selected,
                          hipStream_t stream)
 {
     const dim3 grid(cluster, ctx->geom.n_kv_heads, batch), block(kSelThreads);
-    return launch(select_kernel, grid, block, lds_bytes, stream, q, pages, chunks, grids, seq_lens, ctx->geom, sp, ws, page_ids,
+    if (ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16)
+        return launch(select_kernel<uint16_t>, grid, block, lds_bytes, stream, q, static_cast<const uint16_t*>(pages),
+                      static_cast<const uint16_t*>(chunks), static_cast<const uint16_t*>(grids), seq_lens, ctx->geom, sp, ws,
+                      page_ids, n_selected);
+    return launch(select_kernel<float>, grid, block, lds_bytes, stream, q, static_cast<const float*>(pages),
+                  static_cast<const float*>(chunks), static_cast<const float*>(grids), seq_lens, ctx->geom, sp, ws, page_ids,
                   n_selected);
 }
 

@@ -15,6 +15,7 @@
 namespace chess {
 
 // grid = (ceil(rows / 16), n_layers), 256 threads: a 16-lane group per (layer, sequence, KV head)
+template <class T>
 __global__ __launch_bounds__(256) void anchor_kernel(AnchorTable tab, const int32_t* __restrict__ seq_lens, int rows, Geom g,
                                                      int window)
 {
@@ -23,24 +24,29 @@ __global__ __launch_bounds__(256) void anchor_kernel(AnchorTable tab, const int3
     const int b = row / g.n_kv_heads;
     const int L = min(max(seq_lens[b], 0), g.max_pages * g.page_size);
     const int P = (L + g.page_size - 1) / g.page_size;
-    const float* pages = reinterpret_cast<const float*>(tab.summaries[l] + tab.page_off);
+    const T* pages = reinterpret_cast<const T*>(tab.summaries[l] + tab.page_off);
     double pr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (P > 0) load_anchor(pages + (size_t)row * g.max_pages * kHeadDim, P, window, pr);
-    float4* dst = reinterpret_cast<float4*>(tab.anchors[l] + (size_t)row * kHeadDim);
-    dst[ln] = make_float4((float)pr[0], (float)pr[1], (float)pr[2], (float)pr[3]);
-    dst[16 + ln] = make_float4((float)pr[4], (float)pr[5], (float)pr[6], (float)pr[7]);
+    if (P > 0) load_anchor<T>(pages + (size_t)row * g.max_pages * kHeadDim, P, window, pr);
+    // the anchor is an fp32 vector [128] in dim order, whatever arrangement the lanes hold it in
+    float* dst = tab.anchors[l] + (size_t)row * kHeadDim;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dst[Vec<T>::lane_dim(ln, i)] = (float)pr[i];
 }
 
 hipError_t launch_anchor(chess_ctx* ctx, const AnchorTable& tab, int n_layers, const int32_t* seq_lens, int batch,
                          int window, hipStream_t stream)
 {
     const int rows = batch * ctx->geom.n_kv_heads;
-    return launch(anchor_kernel, dim3((rows + 15) / 16, n_layers), dim3(256), 0, stream, tab, seq_lens, rows, ctx->geom,
+    if (ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16)
+        return launch(anchor_kernel<uint16_t>, dim3((rows + 15) / 16, n_layers), dim3(256), 0, stream, tab, seq_lens, rows,
+                      ctx->geom, window);
+    return launch(anchor_kernel<float>, dim3((rows + 15) / 16, n_layers), dim3(256), 0, stream, tab, seq_lens, rows, ctx->geom,
                   window);
 }
 
 constexpr int kSharedSlots = 8;                      // slots a workgroup scores together
 
+template <class T>
 struct SharedScorer {
     static constexpr int kShareRound = 1;
     const SharedTable& tab;
@@ -48,61 +54,56 @@ struct SharedScorer {
     const Geom& g;
     double* red;                                     // LDS [16 groups][kSharedSlots]
 
-    // One pass: the N slots s0 .. s0 + N - 1 (N is a template parameter so that exactly N vectors per row are
-    // requested, all before the first is used: a run-time count would make the compiler wait for each).
-    template <int N, class Map>
-    __device__ __forceinline__ void pass(int level, int s0, Map unit_of, bool local, uint64_t* keys, uint64_t* pub) const
+    // One pass: the N work slots s0 .. s0 + N - 1, all of one level (N is a template parameter so that exactly N
+    // vectors per row are requested, all before the first is used: a run-time count would make the compiler wait
+    // for each).
+    template <int N, class Target>
+    __device__ __forceinline__ void pass(int s0, Target target, bool local, uint64_t* keys, uint64_t* pub) const
     {
         const int tid = threadIdx.x, g16 = tid >> 4, ln = tid & 15;
         const int H = g.n_kv_heads, R = tab.n_layers * H;
+        const int level = target(s0).array;          // (never the merged schedule: a pass stays inside one array)
         const size_t level_off = level == 0 ? tab.grid_off : level == 1 ? tab.chunk_off : tab.page_off;
         const size_t units = level == 0 ? g.max_grids : level == 1 ? g.max_chunks : g.max_pages;
         int unit[N];
         double part[N];
 #pragma unroll
         for (int x = 0; x < N; ++x) {
-            unit[x] = unit_of(s0 + x);
+            unit[x] = target(s0 + x).unit;
             part[x] = 0.0;
         }
         // two rows per trip: 2 N vectors in flight per group.  A trip's second row may not exist: it then reads the
         // first row again with a zero probe (adding exact zeros)
         for (int r = g16; r < R; r += 2 * kSelGroups) {
-            float4 pa[2], pb[2];
-            const float* base[2];
+            double pr[2][8];
+            const T* base[2];
 #pragma unroll
             for (int y = 0; y < 2; ++y) {
                 const bool have = r + y * kSelGroups < R;
                 const int ry = have ? r + y * kSelGroups : r;
                 const int l = ry / H, h = ry - l * H;
                 const size_t row = (size_t)b * H + h;
-                const float4* p0 = reinterpret_cast<const float4*>(tab.probes[l] + row * kHeadDim);
-                base[y] = reinterpret_cast<const float*>(tab.summaries[l] + level_off) + row * units * kHeadDim;
-                pa[y] = p0[ln];
-                pb[y] = p0[16 + ln];
-                if (!have) { pa[y] = make_float4(0.f, 0.f, 0.f, 0.f); pb[y] = pa[y]; }
+                const float* p0 = tab.probes[l] + row * kHeadDim;
+                base[y] = reinterpret_cast<const T*>(tab.summaries[l] + level_off) + row * units * kHeadDim;
+                // the probe in the arrangement the vectors are held in (two runs of four consecutive dims)
+                const float4 pa = *reinterpret_cast<const float4*>(p0 + Vec<T>::lane_dim(ln, 0));
+                const float4 pb = *reinterpret_cast<const float4*>(p0 + Vec<T>::lane_dim(ln, 4));
+                pr[y][0] = have ? (double)pa.x : 0.0; pr[y][1] = have ? (double)pa.y : 0.0;
+                pr[y][2] = have ? (double)pa.z : 0.0; pr[y][3] = have ? (double)pa.w : 0.0;
+                pr[y][4] = have ? (double)pb.x : 0.0; pr[y][5] = have ? (double)pb.y : 0.0;
+                pr[y][6] = have ? (double)pb.z : 0.0; pr[y][7] = have ? (double)pb.w : 0.0;
             }
-            float4 va[2][N], vb[2][N];
+            Vec<T> v[2][N];
 #pragma unroll
             for (int y = 0; y < 2; ++y) {
 #pragma unroll
-                for (int x = 0; x < N; ++x) {
-                    // always load (unit 0 when the slot has no unit): all stay in flight
-                    const float4* p = reinterpret_cast<const float4*>(base[y] + (size_t)max(unit[x], 0) * kHeadDim) + ln;
-                    va[y][x] = p[0];
-                    vb[y][x] = p[16];
-                }
+                for (int x = 0; x < N; ++x)       // always load (unit 0 when the slot has no unit): all stay in flight
+                    v[y][x].load(base[y] + (size_t)max(unit[x], 0) * kHeadDim, ln);
             }
 #pragma unroll
             for (int y = 0; y < 2; ++y) {
 #pragma unroll
-                for (int x = 0; x < N; ++x) {
-                    double d = part[x];
-                    d = fma((double)pa[y].x, (double)va[y][x].x, d); d = fma((double)pa[y].y, (double)va[y][x].y, d);
-                    d = fma((double)pa[y].z, (double)va[y][x].z, d); d = fma((double)pa[y].w, (double)va[y][x].w, d);
-                    d = fma((double)pb[y].x, (double)vb[y][x].x, d); d = fma((double)pb[y].y, (double)vb[y][x].y, d);
-                    d = fma((double)pb[y].z, (double)vb[y][x].z, d); d = fma((double)pb[y].w, (double)vb[y][x].w, d);
-                    part[x] = d;
-                }
+                for (int x = 0; x < N; ++x) part[x] = dot8<T>(pr[y], v[y][x], part[x]);
             }
         }
 #pragma unroll
@@ -115,37 +116,39 @@ struct SharedScorer {
             double d = 0.0;
 #pragma unroll
             for (int j = 0; j < kSelGroups; ++j) d += red[j * kSharedSlots + tid];
-            const int u = unit_of(s0 + tid);
-            if (local) keys[s0 + tid] = u >= 0 ? order_key(d) : 0ull;
-            else publish_u64(pub + s0 + tid, u >= 0 ? order_key(d) : kAbsentKey);
+            const SlotRef ref = target(s0 + tid);
+            if (ref.dest >= 0) {
+                if (local) keys[ref.dest] = ref.unit >= 0 ? order_key(d) : 0ull;
+                else publish_u64(pub + ref.dest, ref.unit >= 0 ? order_key(d) : kAbsentKey);
+            }
         }
         __syncthreads();                              // red is reused by the next pass
     }
 
-    template <class Map>
-    __device__ __forceinline__ void operator()(int level, int lo, int hi, Map unit_of, bool local, uint64_t* keys,
-                                               uint64_t* pub) const
+    template <class Target>
+    __device__ __forceinline__ void operator()(int lo, int hi, Target target, bool local, uint64_t* keys, uint64_t* pub) const
     {
         // the share in passes of equal size (the last may be shorter), at most kSharedSlots slots each
         const int n_pass = (hi - lo + kSharedSlots - 1) / kSharedSlots;
         const int per_pass = n_pass > 0 ? (hi - lo + n_pass - 1) / n_pass : 0;
         for (int s0 = lo; s0 < hi; s0 += per_pass) {
             switch (min(per_pass, hi - s0)) {             // uniform over the workgroup
-            case 1: pass<1>(level, s0, unit_of, local, keys, pub); break;
-            case 2: pass<2>(level, s0, unit_of, local, keys, pub); break;
-            case 3: pass<3>(level, s0, unit_of, local, keys, pub); break;
-            case 4: pass<4>(level, s0, unit_of, local, keys, pub); break;
-            case 5: pass<5>(level, s0, unit_of, local, keys, pub); break;
-            case 6: pass<6>(level, s0, unit_of, local, keys, pub); break;
-            case 7: pass<7>(level, s0, unit_of, local, keys, pub); break;
-            default: pass<8>(level, s0, unit_of, local, keys, pub); break;
+            case 1: pass<1>(s0, target, local, keys, pub); break;
+            case 2: pass<2>(s0, target, local, keys, pub); break;
+            case 3: pass<3>(s0, target, local, keys, pub); break;
+            case 4: pass<4>(s0, target, local, keys, pub); break;
+            case 5: pass<5>(s0, target, local, keys, pub); break;
+            case 6: pass<6>(s0, target, local, keys, pub); break;
+            case 7: pass<7>(s0, target, local, keys, pub); break;
+            default: pass<8>(s0, target, local, keys, pub); break;
             }
         }
     }
 };
 static_assert(kSharedSlots == 8, "the dispatch in SharedScorer lists the pass sizes");
 
-// grid = (C, 1, batch)
+// grid = (C, 1, batch); T = storage type of the summaries
+template <class T>
 __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable tab, const int32_t* __restrict__ seq_lens,
                                                                     Geom g, SelectParams sp, SelectWs ws,
                                                                     int32_t* __restrict__ page_ids,
@@ -162,10 +165,7 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
     const int m = blockIdx.x, C = gridDim.x, b = blockIdx.z, tid = threadIdx.x;
     const int H = g.n_kv_heads, B = g.page_size;
     Prof prof;
-    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
-    if (tid == 0) sh.n_mem = 0;
-    if (tid < 3) sh.tail_key[tid] = 0ull;
-    if (tid == 0) sh.poll_limit = sp.poll_limit;
+    init_shared(sh, sp.poll_limit);
     const int L = min(max(seq_lens[b], 0), g.max_pages * B);
     const int k_fixed = fixed_budget(sp, g, b);
     const int P = (L + B - 1) / B;
@@ -184,13 +184,13 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
     }
     __syncthreads();
 
-    const PubLayout pubs = pub_layout(ws.keys + (size_t)b * ws.key_stride, g, sp);
+    const PubLayout pubs = pub_layout(ws.keys + (size_t)b * ws.key_stride, g);
     CascadeResult res;
-    const SharedScorer scorer{tab, b, g, red};
+    const SharedScorer<T> scorer{tab, b, g, red};
     const bool ok = cascade_with<false>(scorer, P, g, sp, pubs, m, C, m == 0, keys, kept_grids, kept_chunks, sel_pages, sh,
                                         &res, prof, nullptr, [] {}, k_fixed);
     if (!ok) {
-        if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_fetch_or(ws.error, kErrWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return;
     }
     if (C > 1) {
@@ -198,6 +198,7 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
         if (arrive_last(ws.meta + (size_t)b * kSelMetaStride, C, &sh.flag)) clear_published(pubs, res);
     }
     if (m != 0) return;
+    if (res.overflow && tid == 0) __hip_atomic_fetch_or(ws.error, kErrOverflow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
     const int n_kp = res.n_kp, n_sel = s + n_kp + w;
     for (int i = tid; i < H * g.max_sel; i += kSelThreads) {
@@ -211,14 +212,16 @@ __global__ __launch_bounds__(kSelThreads) void select_shared_kernel(SharedTable 
     if (tid < H) n_selected[b * H + tid] = n_sel;
 }
 
-hipError_t select_shared_occupancy(int lds_bytes, int* blocks_per_cu)
+hipError_t select_shared_occupancy(bool bf16, int lds_bytes, int* blocks_per_cu)
 {
+    const void* kern = bf16 ? reinterpret_cast<const void*>(select_shared_kernel<uint16_t>)
+                            : reinterpret_cast<const void*>(select_shared_kernel<float>);
     if (lds_bytes > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_shared_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) return e;
     }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_shared_kernel, kSelThreads, lds_bytes);
+    return bf16 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_shared_kernel<uint16_t>, kSelThreads, lds_bytes)
+                : hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, select_shared_kernel<float>, kSelThreads, lds_bytes);
 }
 
 hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const int32_t* seq_lens, int batch, int cluster,
@@ -226,7 +229,10 @@ hipError_t launch_select_shared(chess_ctx* ctx, const SharedTable& tab, const in
                                 int32_t* n_selected, hipStream_t stream)
 {
     const dim3 grid(cluster, 1, batch), block(kSelThreads);
-    return launch(select_shared_kernel, grid, block, lds_bytes, stream, tab, seq_lens, ctx->geom, sp, ws, page_ids,
+    if (ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16)
+        return launch(select_shared_kernel<uint16_t>, grid, block, lds_bytes, stream, tab, seq_lens, ctx->geom, sp, ws, page_ids,
+                      n_selected);
+    return launch(select_shared_kernel<float>, grid, block, lds_bytes, stream, tab, seq_lens, ctx->geom, sp, ws, page_ids,
                   n_selected);
 }
 

@@ -17,9 +17,9 @@ constexpr int kStepWaves = kSelThreads / kWave;
 
 struct StepArgs {
     const uint16_t* q;
-    float* pages;            // summaries: read; the tail units are rewritten when refresh_tail is set
-    float* chunks;
-    float* grids;
+    void* pages;             // summaries (fp32 or bf16): read; the tail units are rewritten when refresh_tail is set
+    void* chunks;
+    void* grids;
     const uint16_t* k_pool;
     const uint16_t* v_pool;
     const int32_t* block_table;
@@ -38,14 +38,14 @@ struct StepArgs {
 // The per-step refresh of the summaries (Sec. 3.1, Eq. 1-2) of the tail page, its chunk and its grid, done by one
 // workgroup per (sequence, KV head) inside the step: thread c < 128 owns column c and adds in the same order as
 // the summarize kernel (tokens, then the chunk's pages, then the grid's chunks, ascending, fp64, one rounding to
-// fp32 per vector), so the vectors are the ones chess_summarize_tail writes.  They go to the summaries and to
-// `fresh` (LDS, [3][128]: page, chunk, grid); their scores against the probe are published as keys in
-// tail_words[0..2] (grid, chunk, page) when `publish` is set (a cluster of one has nobody to tell) and kept in
-// sh.tail_key.  Every thread of the workgroup must call it.
-template <int B>
-__device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ k_pool, int64_t phys, float* pages_row,
-                                                   float* chunks_row, float* grids_row, int h, int H, int L, int P,
-                                                   const Geom& g, const double (&pr)[8], float* fresh,
+// the storage type per vector; a parent averages its children as they are stored), so the vectors are the ones
+// chess_summarize_tail writes.  They go to the summaries and to `fresh` (LDS, [3][128]: page, chunk, grid); their
+// scores against the probe are published as keys in tail_words[0..2] (grid, chunk, page) when `publish` is set (a
+// cluster of one has nobody to tell) and kept in sh.tail_key.  Every thread of the workgroup must call it.
+template <int B, class T>
+__device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ k_pool, int64_t phys, T* pages_row,
+                                                   T* chunks_row, T* grids_row, int h, int H, int L, int P,
+                                                   const Geom& g, const double (&pr)[8], T* fresh,
                                                    uint64_t* tail_words, bool publish, Shared& sh)
 {
     const int tid = threadIdx.x;
@@ -63,7 +63,7 @@ __device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ 
         // hierarchy of 8 x 8
         constexpr int kSib = 8;
         const int p_lo = tc * g.n_c, c_lo = tg * g.n_g;
-        float sp[kSib], sc[kSib];
+        T sp[kSib], sc[kSib];
 #pragma unroll
         for (int x = 0; x < kSib; ++x) {
             sp[x] = pages_row[(size_t)min(p_lo + x, tp) * kHeadDim + c];
@@ -72,30 +72,30 @@ __device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ 
         double acc_c = 0.0, acc_g = 0.0;
 #pragma unroll
         for (int x = 0; x < kSib; ++x) {
-            if (p_lo + x < tp) acc_c += (double)sp[x];
-            if (c_lo + x < tc) acc_g += (double)sc[x];
+            if (p_lo + x < tp) acc_c += loaded(sp[x]);
+            if (c_lo + x < tc) acc_g += loaded(sc[x]);
         }
         for (int j0 = p_lo + kSib; j0 < tp; j0 += kSib) {
 #pragma unroll
             for (int x = 0; x < kSib; ++x) sp[x] = pages_row[(size_t)min(j0 + x, tp) * kHeadDim + c];
 #pragma unroll
             for (int x = 0; x < kSib; ++x)
-                if (j0 + x < tp) acc_c += (double)sp[x];
+                if (j0 + x < tp) acc_c += loaded(sp[x]);
         }
         for (int j0 = c_lo + kSib; j0 < tc; j0 += kSib) {
 #pragma unroll
             for (int x = 0; x < kSib; ++x) sc[x] = chunks_row[(size_t)min(j0 + x, tc) * kHeadDim + c];
 #pragma unroll
             for (int x = 0; x < kSib; ++x)
-                if (j0 + x < tc) acc_g += (double)sc[x];
+                if (j0 + x < tc) acc_g += loaded(sc[x]);
         }
         double acc_p = 0.0;
 #pragma unroll
         for (int t = 0; t < B; ++t)
-            if (t < n_tok) acc_p += (double)__uint_as_float((uint32_t)kr[t] << 16);
-        const float vp = (float)(acc_p / (double)n_tok);
-        const float vc = (float)((acc_c + (double)vp) / (double)(tp - tc * g.n_c + 1));
-        const float vg = (float)((acc_g + (double)vc) / (double)(tc - tg * g.n_g + 1));
+            if (t < n_tok) acc_p += loaded(kr[t]);
+        const T vp = stored<T>(acc_p / (double)n_tok);
+        const T vc = stored<T>((acc_c + loaded(vp)) / (double)(tp - tc * g.n_c + 1));
+        const T vg = stored<T>((acc_g + loaded(vc)) / (double)(tc - tg * g.n_g + 1));
         pages_row[(size_t)tp * kHeadDim + c] = vp;
         chunks_row[(size_t)tc * kHeadDim + c] = vc;
         grids_row[(size_t)tg * kHeadDim + c] = vg;
@@ -107,14 +107,9 @@ __device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ 
     // scores of the three vectors, one 16-lane group each, with the arithmetic of score_rows
     const int g16 = tid >> 4, ln = tid & 15;
     if (g16 < 3) {
-        const float4* v = reinterpret_cast<const float4*>(fresh + g16 * kHeadDim);
-        const float4 va = v[ln], vb = v[16 + ln];
-        double d = 0.0;
-        d = fma(pr[0], (double)va.x, d); d = fma(pr[1], (double)va.y, d);
-        d = fma(pr[2], (double)va.z, d); d = fma(pr[3], (double)va.w, d);
-        d = fma(pr[4], (double)vb.x, d); d = fma(pr[5], (double)vb.y, d);
-        d = fma(pr[6], (double)vb.z, d); d = fma(pr[7], (double)vb.w, d);
-        d = row16_sum(d);
+        Vec<T> v;
+        v.load(fresh + g16 * kHeadDim, ln);
+        const double d = row16_sum(dot8<T>(pr, v));
         if (ln == 15) {
             const uint64_t key = order_key(d);
             const int level = 2 - g16;                            // fresh[0] is the page, fresh[2] the grid
@@ -125,15 +120,15 @@ __device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ 
     __syncthreads();
 }
 
-// grid = (C, H_kv, batch)
-template <int B>
+// grid = (C, H_kv, batch); T = storage type of the summaries (float or bf16 bits)
+template <int B, class T>
 __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))) void step_kernel(StepArgs a, Geom g, SelectParams sp, SelectWs ws)
 {
     constexpr int PPT = 32 / B;
     extern __shared__ unsigned long long lds_raw[];
     int32_t* ids_l = reinterpret_cast<int32_t*>(lds_raw);                                  // [max_sel] the page list
     int32_t* phys_l = ids_l + g.max_sel;                                                   // [max_sel] their physical pages
-    float* fresh = reinterpret_cast<float*>(reinterpret_cast<char*>(lds_raw) + a.union_off) - 3 * kHeadDim;   // [3][128]
+    T* fresh = reinterpret_cast<T*>(reinterpret_cast<char*>(lds_raw) + a.union_off - 3 * kHeadDim * sizeof(float));   // [3][128]
     char* un = reinterpret_cast<char*>(lds_raw) + a.union_off;
     uint64_t* keys = reinterpret_cast<uint64_t*>(un);                                      // selection's view
     int32_t* kept_grids = reinterpret_cast<int32_t*>(keys + sp.cap_keys);
@@ -146,18 +141,15 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     const int lane = tid & 63, wave = tid >> 6, m16 = lane & 15, grp = lane >> 4;
     const int G = g.group, H = g.n_kv_heads;
     Prof prof;
-    prof.mark();
+    prof.mark(0);
     const size_t row = (size_t)b * H + h;
     const uint16_t* q_rows = a.q + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     float* out_rows = a.out + ((size_t)b * g.n_q_heads + (size_t)h * G) * kHeadDim;
     const int L_raw = a.seq_lens[b];
     const int k_fixed = fixed_budget(sp, g, b);
     double pr[8];
-    if (sp.probe == CHESS_PROBE_QUERY) load_probe(q_rows, G, pr);     // requested before anything waits on the length
-    for (int i = tid; i < kBins; i += kSelThreads) sh.hist[i] = 0;   // as cut_in_registers wants it
-    if (tid == 0) sh.n_mem = 0;
-    if (tid < 3) sh.tail_key[tid] = 0ull;
-    if (tid == 0) sh.poll_limit = sp.poll_limit;
+    if (sp.probe == CHESS_PROBE_QUERY) load_probe<T>(q_rows, G, pr);  // requested before anything waits on the length
+    init_shared(sh, sp.poll_limit);
     const int L = min(max(L_raw, 0), g.max_pages * B);
     const int P = (L + B - 1) / B;
     const int s = sp.sink, w = sp.window;
@@ -170,25 +162,25 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
         }
         return;
     }
-    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor(a.pages + row * g.max_pages * kHeadDim, P, w, pr);
+    T* pages_row = static_cast<T*>(a.pages) + row * g.max_pages * kHeadDim;
+    T* chunks_row = static_cast<T*>(a.chunks) + row * g.max_chunks * kHeadDim;
+    T* grids_row = static_cast<T*>(a.grids) + row * g.max_grids * kHeadDim;
+    if (sp.probe == CHESS_PROBE_ANCHOR) load_anchor<T>(pages_row, P, w, pr);
     // member 0 refreshes the tail units: its block-table entry is requested now
     const bool tail_on = a.refresh_tail != 0;
     uint64_t* tail_words = tail_on ? ws.tail + row * 4 : nullptr;
-    float* pages_row = a.pages + row * g.max_pages * kHeadDim;
-    float* chunks_row = a.chunks + row * g.max_chunks * kHeadDim;
-    float* grids_row = a.grids + row * g.max_grids * kHeadDim;
     int tail_phys = 0;
     if (tail_on && m == 0) tail_phys = bt_row[P - 1];
     auto refresh_tail = [&]() {
-        refresh_tail_units<B>(a.k_pool, tail_phys, pages_row, chunks_row, grids_row, h, H, L, P, g, pr, fresh, tail_words, C > 1, sh);
+        refresh_tail_units<B, T>(a.k_pool, tail_phys, pages_row, chunks_row, grids_row, h, H, L, P, g, pr, fresh, tail_words, C > 1, sh);
     };
     __syncthreads();
-    prof.mark();                                                      // prologue done
+    prof.mark(1);                                                     // prologue done
 
     // ---- the page list, in every member's LDS
-    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g, sp);
+    const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g);
     CascadeResult res;
-    res.n_kp = 0; res.n1 = 0; res.n2 = 0; res.n3 = 0;
+    res.n_kp = 0; res.n_a = 0; res.n_p = 0; res.overflow = false;
     int n_sel;
     if (P <= s + w) {                                                 // safety pages cover the sequence
         n_sel = min(P, g.max_sel);
@@ -201,13 +193,14 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
         int safety_phys = 0;
         if (safety_early && tid < s + w) safety_phys = bt_row[safety_lp];
         // kept pages and their physical pages go straight to their places in the list, behind the sinks
-        const bool ok = cascade<true>(pages_row, chunks_row, grids_row, pr, P, g, sp, pubs, m, C, true, keys, kept_grids,
-                                      kept_chunks, ids_l + s, sh, &res, prof, tail_words, refresh_tail, k_fixed, bt_row,
-                                      phys_by_slot, phys_l + s);
+        const bool ok = cascade<true, T>(pages_row, chunks_row, grids_row, pr, P, g, sp, pubs, m, C, true, keys, kept_grids,
+                                         kept_chunks, ids_l + s, sh, &res, prof, tail_words, refresh_tail, k_fixed, bt_row,
+                                         phys_by_slot, phys_l + s);
         if (!ok) {
-            if (tid == 0) __hip_atomic_store(ws.error, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (tid == 0) __hip_atomic_fetch_or(ws.error, kErrWait, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             return;
         }
+        if (res.overflow && m == 0 && tid == 0) __hip_atomic_fetch_or(ws.error, kErrOverflow, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         // union with the safety pages: sinks, kept pages, window -- already ascending
         const int n_kp = res.n_kp;
         n_sel = s + n_kp + w;
@@ -230,7 +223,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
         if (a.page_ids) for (int i = tid; i < g.max_sel; i += kSelThreads) a.page_ids[row * g.max_sel + i] = i < n_sel ? ids_l[i] : -1;
         if (a.n_selected && tid == 0) a.n_selected[row] = n_sel;
     }
-    prof.mark();                                                      // list built
+    prof.mark(14);                                                    // list built
 
     // ---- attention over this member's tiles of the list: split m of C
     const int n_tiles = (n_sel + PPT - 1) / PPT;
@@ -243,23 +236,32 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     acc.init(q_rows, G, m16, grp);
     run_tiles<B, true, true>(acc, t, stride, n_tiles, n_sel, raw_cur, raw_nxt, ids_l, max(n_sel, 1), bt_row, phys_l, a.k_pool, a.v_pool, H, h, L, P,
                  a.scale_log2, m16, grp);
-    prof.mark();                                                      // tiles done
+    prof.mark(15);                                                    // tiles done
     if (!combine_waves<kStepWaves>(acc.o, acc.m_run, acc.l_run, dl, G, C, m, row, out_rows, a.ws_acc, a.ws_ml)) return;
-    prof.mark();                                                      // partial published
-    if (!arrive_last(a.arrivals + row, C, &sh.flag)) return;
-    prof.mark();                                                      // last to arrive
+    prof.mark(16);                                                    // partial published
+    // (profiling builds keep two timelines per row: member 0's and that of the member that merges)
+    if (!arrive_last(a.arrivals + row, C, &sh.flag)) {
+#ifdef CHESS_PROF
+        prof.mark(17);
+        if (tid == 0 && m == 0) prof.store(ws.prof + (row * 2) * Prof::kSlots);
+#endif
+        return;
+    }
+    prof.mark(17);                                                    // last to arrive
     merge_splits<kStepWaves>(G, C, row, out_rows, a.ws_acc, a.ws_ml);
     if (C > 1) clear_published(pubs, res, tail_words);                    // every member is done with the key words
 #ifdef CHESS_PROF
-    prof.mark();
-    if (tid == 0)
-        for (int i = 1; i < prof.n; ++i) ws.prof[row * 48 + i] = (int)(prof.t[i] - prof.t[i - 1]);
+    prof.mark(18);
+    if (tid == 0) prof.store(ws.prof + (row * 2 + 1) * Prof::kSlots);
+    if (tid == 0 && m == 0) prof.store(ws.prof + (row * 2) * Prof::kSlots);
 #endif
 }
 
-static void (*step_kernel_of(int page_size))(StepArgs, Geom, SelectParams, SelectWs)
+using StepKernel = void (*)(StepArgs, Geom, SelectParams, SelectWs);
+static StepKernel step_kernel_of(int page_size, bool bf16)
 {
-    return page_size == 16 ? step_kernel<16> : step_kernel<32>;
+    if (bf16) return page_size == 16 ? step_kernel<16, uint16_t> : step_kernel<32, uint16_t>;
+    return page_size == 16 ? step_kernel<16, float> : step_kernel<32, float>;
 }
 
 // Dynamic LDS of the fused kernel and where its shared region starts.
@@ -272,12 +274,12 @@ size_t step_lds_bytes(const SelectParams& sp, int max_sel, int* union_off)
     return list + (sel > dec ? sel : dec);
 }
 
-hipError_t step_occupancy(int page_size, int lds_bytes, int* blocks_per_cu)
+hipError_t step_occupancy(int page_size, bool bf16, int lds_bytes, int* blocks_per_cu)
 {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kernel_of(page_size)),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(step_kernel_of(page_size, bf16)),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, step_kernel_of(page_size), kSelThreads, lds_bytes);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, step_kernel_of(page_size, bf16), kSelThreads, lds_bytes);
 }
 
 hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int cluster, const SelectParams& sp,
@@ -292,7 +294,7 @@ hipError_t launch_step(chess_ctx* ctx, const StepLaunch& sl, int batch, int clus
     a.union_off = union_off;
     a.refresh_tail = sl.refresh_tail;
     const dim3 grid(cluster, g.n_kv_heads, batch), block(kSelThreads);
-    return launch(step_kernel_of(g.page_size), grid, block, lds_bytes, stream, a, g, sp, ws);
+    return launch(step_kernel_of(g.page_size, ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16), grid, block, lds_bytes, stream, a, g, sp, ws);
 }
 
 }  // namespace chess

@@ -10,6 +10,7 @@ import torch
 import oracle
 import paper_2602_20732_amd as pk
 import workload
+import helpers
 from helpers import geom_of, host_arrays
 
 
@@ -17,7 +18,13 @@ def config_of(sp: workload.WorkloadSpec, max_selected=None, max_batch=None) -> p
     return pk.Config(n_q_heads=sp.n_q_heads, n_kv_heads=sp.n_kv_heads, page_size=sp.page_size,
                      max_batch=sp.batch if max_batch is None else max_batch, max_pages_per_seq=sp.max_pages,
                      max_selected_pages=sp.max_selected if max_selected is None else max_selected,
-                     pages_per_chunk=sp.pages_per_chunk, chunks_per_grid=sp.chunks_per_grid)
+                     pages_per_chunk=sp.pages_per_chunk, chunks_per_grid=sp.chunks_per_grid,
+                     summary_dtype=helpers.SUMMARY_DTYPE)
+
+
+def host_views(lib: pk.Chess, summaries, n=None):
+    """The three summary arrays of a buffer as float32 numpy arrays (a bf16 value converts exactly)."""
+    return tuple((t if n is None else t[:n]).float().cpu().numpy() for t in lib.summary_views(summaries))
 
 
 def gpu_plan(op: oracle.Plan) -> pk.SelectPlan:
@@ -81,7 +88,7 @@ def run_gpu(lib: pk.Chess, wl: workload.Workload, plan: oracle.Plan, dense: bool
     lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids2, nsel2, out2, ws2)
     torch.cuda.synchronize()
     assert lib.workspace_error(ws) == 0 and lib.workspace_error(ws2) == 0, "a kernel gave up a bounded wait"
-    pv, cv, gv = (t[:batch].cpu().numpy() for t in lib.summary_views(summ))
+    pv, cv, gv = host_views(lib, summ, batch)
     return GpuRun(pv, cv, gv, ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dn.cpu().numpy(),
                   ids2.cpu().numpy(), nsel2.cpu().numpy(), out2.cpu().numpy())
 

@@ -10,9 +10,13 @@ import oracle
 import workload
 
 
-def geom_of(sp: workload.WorkloadSpec, max_pages=None) -> oracle.Geometry:
+SUMMARY_DTYPE = 0     # storage type of the summaries in the running test (0 = fp32, 1 = bf16); tests/conftest.py sets it
+
+
+def geom_of(sp: workload.WorkloadSpec, max_pages=None, summary_dtype=None) -> oracle.Geometry:
     return oracle.Geometry(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.page_size, sp.pages_per_chunk,
-                           sp.chunks_per_grid, sp.max_pages if max_pages is None else max_pages)
+                           sp.chunks_per_grid, sp.max_pages if max_pages is None else max_pages,
+                           SUMMARY_DTYPE if summary_dtype is None else summary_dtype)
 
 
 def plan_of(sp: workload.WorkloadSpec, **kw) -> oracle.Plan:

@@ -13,7 +13,7 @@
 #include <stdlib.h>
 #include <string.h>
 
-typedef struct { int32_t n_q_heads, n_kv_heads, head_dim, page_size, pages_per_chunk, chunks_per_grid, max_pages; } geom_t;
+typedef struct { int32_t n_q_heads, n_kv_heads, head_dim, page_size, pages_per_chunk, chunks_per_grid, max_pages, summary_dtype; } geom_t;
 typedef struct { int32_t plan, sink_pages, window_pages, budget_pages, budget_bp, over_chunk, over_grid, rho_g_bp, rho_c_bp,
                  rho_p_bp, probe, cut_rule; } plan_t;
 

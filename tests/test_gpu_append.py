@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2602_20732_amd as pk
 import workload
-from gpu_common import config_of, gpu_plan, to_device
+from gpu_common import host_views, config_of, gpu_plan, to_device
 from helpers import bf16_to_f64, geom_of, logical_kv, plan_of
 
 pytestmark = pytest.mark.gpu
@@ -65,7 +65,7 @@ def test_append_grows_the_cache_and_the_step_follows_it():
                     assert np.array_equal(got_k, ref_k) and np.array_equal(got_v, ref_v), (step, b, h)
             # summaries kept current by the per-step refresh == the oracle's full pass over the grown prefix
             rp, rc, rg = oracle.summarize(K, bt, sl, g)
-            pv, cv, gv = (t[:3].cpu().numpy() for t in lib.summary_views(summ))
+            pv, cv, gv = host_views(lib, summ, 3)
             for b in range(3):
                 P = -(-int(sl[b]) // B); nc = -(-P // 4); ng = -(-nc // 4)
                 assert np.array_equal(pv[b, :, :P], rp[b, :, :P]) and np.array_equal(cv[b, :, :nc], rc[b, :, :nc])

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2602_20732_amd as pk
 import workload
-from gpu_common import config_of, gpu_plan, host_subset, to_device
+from gpu_common import host_views, config_of, gpu_plan, host_subset, to_device
 from helpers import geom_of, plan_of
 
 pytestmark = pytest.mark.gpu
@@ -54,7 +54,7 @@ def run_case(name, sample, dense_seq=0, seed=None, layer=0):
     assert torch.equal(ids3, ids) and torch.equal(nsel3, nsel), (name, "fused step with refresh_tail: page lists differ")
     out2_h = out2.cpu().numpy()
     out3_h = out3.cpu().numpy()
-    pv, cv, gv = (t.cpu().numpy() for t in lib.summary_views(summ))
+    pv, cv, gv = host_views(lib, summ)
     ids_h, nsel_h, out_h, dense_h = ids.cpu().numpy(), nsel.cpu().numpy(), out.cpu().numpy(), dense.cpu().numpy()
     assert np.isfinite(out_h).all() and np.isfinite(dense_h).all()
 

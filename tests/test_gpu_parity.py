@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2602_20732_amd as pk
 import workload
-from gpu_common import (assert_summaries_equal, classify_selection, config_of, gpu_plan, run_gpu, run_oracle,
+from gpu_common import (assert_summaries_equal, classify_selection, config_of, gpu_plan, host_views, run_gpu, run_oracle,
                         to_device)
 from helpers import geom_of, host_arrays, plan_of
 
@@ -146,7 +146,7 @@ def test_fused_step_refreshes_the_tail_summaries(cluster):
                             refresh_tail=True)
             torch.cuda.synchronize()
             assert lib.workspace_error(ws) == 0
-            got = GpuRunLike(*(t[:len(lens)].cpu().numpy() for t in lib.summary_views(summ)))
+            got = GpuRunLike(*host_views(lib, summ, len(lens)))
             assert_summaries_equal(got, ref, sp, lens)
             assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
             assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
@@ -299,7 +299,8 @@ def test_recent_pages_catch_up_matches_full_pass(recent):
     lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
     full, inc = lib.new_summaries(), lib.new_summaries()
     lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, full)
-    inc.view(torch.float32).fill_(123.0)
+    for t in lib.summary_views(inc):
+        t.fill_(123.0)
     lib.summarize(wl.k_pool, wl.block_table, torch.tensor(lens0, dtype=torch.int32, device="cuda"), inc)
     lib.summarize_recent(wl.k_pool, wl.block_table, wl.seq_lens, recent, inc)
     torch.cuda.synchronize()
@@ -507,4 +508,96 @@ def test_shared_device_switch_never_waits():
     oanc = oracle.anchor(ref.pages, ref.host[4], geom_of(sp), plan.window_pages)
     sids, sn = oracle.select_shared([oanc], [ref.pages], [ref.chunks], [ref.grids], ref.host[4], geom_of(sp), plan, sp.max_selected)
     assert all(np.array_equal(ids[:, h].cpu().numpy(), sids) for h in range(sp.n_kv_heads))
+    lib.close()
+
+
+@pytest.mark.parametrize("schedule,cluster", [(1, 1), (1, 3), (2, 1), (2, 3), (2, 8)])
+def test_schedules_give_the_same_page_lists(schedule, cluster):
+    """The two schedules of the levels -- lazy (three phases) and merged (all chunks scored with the grids) -- forced
+    in turn: select, the fused step with its tail refresh (window 0 as well, so that the tail page competes), ragged
+    lengths, a budget that keeps every grid (no grid cut) and ratios that prune hard."""
+    sp = RAGGED
+    lens = [3000, 1237, 641, 16 * 16 + 1, 16]
+    wl = workload.generate(sp, 83, seq_lens=lens)
+    d = to_device(wl)
+    for plan in (plan_of(sp), plan_of(sp, window_pages=0, sink_pages=0), plan_of(sp, budget_pages=40),
+                 plan_of(sp, plan=oracle.PLAN_RATIO, rho_g_bp=3000, rho_c_bp=3000, rho_p_bp=1000)):
+        lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+        lib.debug_force_schedule(schedule)
+        lib.debug_force_cluster(cluster)
+        ref = run_oracle(wl, plan, sp.max_pages, dense=False)
+        summ, ws = lib.new_summaries(), lib.new_workspace()
+        lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+        for refresh in (False, True):
+            ids = torch.full((len(lens), sp.n_kv_heads, sp.max_pages), -7, dtype=torch.int32, device="cuda")
+            nsel = torch.full((len(lens), sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+            out = torch.full((len(lens), sp.n_q_heads, 128), float("nan"), device="cuda")
+            if refresh:
+                pv, cv, gv = lib.summary_views(summ)
+                for b, L in enumerate(lens):
+                    tp = -(-L // 16) - 1
+                    pv[b, :, tp] = 5.0; cv[b, :, tp // 4] = -9.0; gv[b, :, tp // 16] = 3.0
+                lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws,
+                                refresh_tail=True)
+            else:
+                lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
+            torch.cuda.synchronize()
+            assert lib.workspace_error(ws) == 0
+            assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel), (plan, refresh)
+            if refresh:
+                assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
+                assert_summaries_equal(GpuRunLike(*host_views(lib, summ, len(lens))), ref, sp, lens)
+        lib.close()
+
+
+@pytest.mark.parametrize("cluster,general", [(1, False), (3, False), (2, True)])
+def test_threshold_rule_keeps_every_tie_at_the_cut(cluster, general):
+    """CHESS_CUT_THRESHOLD (Alg. 1 stage 2 as printed, S >= tau): tied groups at every level's cut (three distinct key
+    rows dealt by page number) are kept whole, through every cut path, against the oracle's threshold mode; on
+    continuous scores the rule changes nothing; a list that outgrows its row raises the overflow bit of the
+    workspace's error word."""
+    sp = workload.WorkloadSpec("groups", 2, (8192, 8192), 4, 1, 16, ("fixed", 128), (1, 1), 1, 2, budget_pages=5,
+                               pages_per_chunk=2, chunks_per_grid=2)
+    wl = workload.generate(sp, 9, seq_lens=[8192, 5000])
+    rows = [wl.k_pool[wl.block_table[0, j].item(), 0, 0].clone() for j in (0, 1, 2)]
+    for b in range(2):
+        for j in range(-(-int(wl.seq_lens[b]) // 16)):
+            wl.k_pool[wl.block_table[b, j].item(), 0, :] = rows[j % 3]
+    for bp in (5000, 3000):
+        plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=1, window_pages=2, rho_g_bp=bp, rho_c_bp=5000, rho_p_bp=bp,
+                           cut_rule=oracle.CUT_THRESHOLD)
+        lib = pk.Chess(config_of(sp, max_selected=sp.max_pages))
+        lib.debug_force_general_cut(general)
+        gpu = run_gpu(lib, wl, plan, dense=False, cluster=cluster)
+        ref = run_oracle(wl, plan, sp.max_pages, dense=False)
+        assert np.array_equal(gpu.ids, ref.ids) and np.array_equal(gpu.nsel, ref.nsel)
+        assert np.array_equal(gpu.step_ids, ref.ids) and np.array_equal(gpu.step_nsel, ref.nsel)
+        count = run_oracle(wl, oracle.Plan(**{**plan.__dict__, "cut_rule": oracle.CUT_COUNT}), sp.max_pages, dense=False)
+        assert (ref.nsel >= count.nsel).all() and (ref.nsel > count.nsel).any(), "the ties must add pages somewhere"
+        lib.close()
+    # continuous scores: nothing ties, both rules agree
+    wl2 = workload.generate(RAGGED, 77, seq_lens=RAGGED_LENS)
+    lib = pk.Chess(config_of(RAGGED, max_selected=RAGGED.max_pages))
+    lib.debug_force_general_cut(general)
+    a = run_gpu(lib, wl2, plan_of(RAGGED, cut_rule=oracle.CUT_THRESHOLD), dense=False, cluster=cluster)
+    ref2 = run_oracle(wl2, plan_of(RAGGED), RAGGED.max_pages, dense=False)
+    assert np.array_equal(a.ids, ref2.ids) and np.array_equal(a.nsel, ref2.nsel)
+    lib.close()
+    # all keys identical, a row too short for all the ties: the list is cut short and the overflow bit is raised
+    sp3 = workload.WorkloadSpec("ties", 1, (2048, 2048), 4, 1, 16, ("fixed", 128), (1, 1), 1, 2, budget_pages=5,
+                                pages_per_chunk=2, chunks_per_grid=2)
+    wl3 = workload.generate(sp3, 3)
+    wl3.k_pool[:] = wl3.k_pool[wl3.block_table[0, 0].item(), 0, 0].clone()
+    d3 = to_device(wl3)
+    lib = pk.Chess(config_of(sp3, max_selected=20))
+    lib.debug_force_general_cut(general)
+    lib.debug_force_cluster(cluster)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d3.k_pool, d3.block_table, d3.seq_lens, summ)
+    ids = torch.full((1, 1, 20), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((1, 1), -7, dtype=torch.int32, device="cuda")
+    lib.select(d3.q, summ, d3.seq_lens, gpu_plan(plan_of(sp3, cut_rule=oracle.CUT_THRESHOLD)), ids, nsel, ws)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) & 2, "every page ties: 125 candidates cannot fit 17 places"
+    assert int(nsel[0, 0]) == 20 and ids[0, 0].tolist() == list(range(0, 18)) + [126, 127]
     lib.close()

@@ -11,7 +11,7 @@ import torch
 import oracle
 import paper_2602_20732_amd as pk
 import workload
-from gpu_common import assert_summaries_equal, classify_selection, config_of, gpu_plan, run_oracle, to_device
+from gpu_common import host_views, assert_summaries_equal, classify_selection, config_of, gpu_plan, run_oracle, to_device
 from helpers import plan_of
 
 pytestmark = pytest.mark.gpu
@@ -80,7 +80,7 @@ def test_random_shape(seed):
     assert lib.workspace_error(ws) == 0
 
     class Got:
-        pages, chunks, grids = (t[:batch].cpu().numpy() for t in lib.summary_views(summ))
+        pages, chunks, grids = host_views(lib, summ, batch)
     assert_summaries_equal(Got, ref, sp, lens)
     for name, i, n, o in (("three calls", ids, nsel, out), ("fused step", ids2, nsel2, out2)):
         gi, gn, go = i.cpu().numpy(), n.cpu().numpy(), o.cpu().numpy()

@@ -147,7 +147,8 @@ def test_shared_scope_at_benchmark_shapes(batch, lo, hi, n_layers, sample):
     summs, probes = [], []
     for _ in range(n_layers):
         s = lib.new_summaries()
-        s.view(torch.float32).normal_(generator=gen)
+        for t in lib.summary_views(s):
+            t.normal_(generator=gen)
         summs.append(s)
         probes.append(torch.empty((batch, sp.n_kv_heads, 128), device="cuda"))
     lib.anchor(summs, sl, plan.window_pages, probes)
@@ -163,7 +164,7 @@ def test_shared_scope_at_benchmark_shapes(batch, lo, hi, n_layers, sample):
         pv, cv, gv = [], [], []
         for s in summs:
             p, c, gr = lib.summary_views(s)
-            pv.append(p[b:b + 1].cpu().numpy()); cv.append(c[b:b + 1].cpu().numpy()); gv.append(gr[b:b + 1].cpu().numpy())
+            pv.append(p[b:b + 1].float().cpu().numpy()); cv.append(c[b:b + 1].float().cpu().numpy()); gv.append(gr[b:b + 1].float().cpu().numpy())
         one = lens[b:b + 1].numpy()
         oanc = [oracle.anchor(p, one, g, plan.window_pages) for p in pv]
         for a, o in zip(probes, oanc):

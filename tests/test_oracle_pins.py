@@ -131,6 +131,73 @@ def test_partial_units_average_over_existing_members(ragged):
             assert not pv[b, h, P:].any() and not cv[b, h, nc:].any() and not gv[b, h, ng:].any()
 
 
+# ------------------------------------------------------------------ bf16 storage of the summaries
+def test_bf16_summaries_are_the_rounded_means(ragged):
+    """The bf16 switch: a stored page vector is the fp32 mean rounded to nearest-even bf16 -- which is what torch's
+    own conversion gives, from the fp32 mean and from the fp64 mean alike -- and a chunk / grid vector is the
+    rounded mean of the STORED child vectors (not of the exact ones).  Everything built here with numpy + torch."""
+    import torch
+    sp, wl, (K, V, Q, bt, sl) = ragged
+    g32, g16 = geom_of(sp), geom_of(sp, summary_dtype=oracle.SUMMARY_BF16)
+    pv32, cv32, gv32 = oracle.summarize(K, bt, sl, g32)
+    pv, cv, gv = oracle.summarize(K, bt, sl, g16)
+    to_bf = lambda a: torch.as_tensor(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
+    assert np.array_equal(pv, to_bf(pv32))
+    B, Nc, Ng = sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
+    differs = 0
+    for b in range(sp.batch):
+        L = int(sl[b]); P = -(-L // B); nc = -(-P // Nc); ng = -(-nc // Ng)
+        for h in range(sp.n_kv_heads):
+            Kl, _ = logical_kv(K, V, bt, L, b, h)
+            means = np.stack([Kl[j * B:min((j + 1) * B, L)].mean(0) for j in range(P)])          # fp64, numpy's own summation
+            assert np.abs(to_bf(means.astype(np.float64)) - pv[b, h, :P]).max() <= 2.0 ** -7 * np.abs(means).max()   # <= 1 bf16 ulp (summation order)
+            cref = np.stack([pv[b, h, c * Nc:min(P, (c + 1) * Nc)].astype(np.float64).mean(0) for c in range(nc)])
+            assert np.array_equal(cv[b, h, :nc], to_bf(cref.astype(np.float32)))
+            gref = np.stack([cv[b, h, k * Ng:min(nc, (k + 1) * Ng)].astype(np.float64).mean(0) for k in range(ng)])
+            assert np.array_equal(gv[b, h, :ng], to_bf(gref.astype(np.float32)))
+            differs += int((cv[b, h, :nc] != to_bf(cv32[b, h, :nc])).sum())
+            assert (pv[b, h, :P].view(np.uint32) & 0xffff == 0).all()
+    assert differs > 0, "averaging stored children must differ somewhere from rounding the fp32 chunk means"
+    # the scores and the selection read the stored values: flat plan == stable argsort of numpy's dots with them
+    ps, _, _ = oracle.scores(Q, pv, cv, gv, sl, g16)
+    k, s, w = 9, sp.sink_pages, sp.window_pages
+    ids, nsel = oracle.select(Q, pv, cv, gv, sl, g16, plan_of(sp, plan=oracle.PLAN_FLAT, budget_pages=k), s + w + k)
+    for b in range(sp.batch):
+        P = -(-int(sl[b]) // B)
+        for h in range(sp.n_kv_heads):
+            probe = bf16_to_f64(Q[b, h * sp.group:(h + 1) * sp.group]).sum(0)
+            sc = pv[b, h, :P].astype(np.float64) @ probe
+            np.testing.assert_allclose(ps[b, h, :P], sc, rtol=1e-12, atol=1e-12)
+            cand = np.arange(s, P - w)
+            top = cand[np.argsort(-sc[cand], kind="stable")][:k]
+            assert ids[b, h, :nsel[b, h]].tolist() == sorted(set(range(s)) | set(top.tolist()) | set(range(P - w, P)))
+
+
+def test_bf16_summaries_keep_table1_budgets():
+    """The keep-counts are integer arithmetic on the hierarchy's shape: the storage type of the vectors does not
+    enter (Table 1's budgets are reproduced in both modes)."""
+    P, Nc, Ng = 640, 8, 8
+    rng = np.random.default_rng(4)
+    Klog = rng.standard_normal((P, 1, 16)).astype(np.float32)
+    K, V, bt = pack_pools(Klog, Klog, 1)
+    Q = f32_to_bf16_bits(rng.standard_normal((1, 1, 16)).astype(np.float32))
+    sl = np.array([P], np.int32)
+    for line in open(os.path.join(GOLDEN, "table1_budgets.txt")):
+        f = line.split("#")[0].split()
+        if len(f) < 5:
+            continue
+        rho = [int(round(float(x) * 10000)) for x in f[1:4]]
+        counts = []
+        for dt in (oracle.SUMMARY_F32, oracle.SUMMARY_BF16):
+            g = oracle.Geometry(1, 1, 16, 1, Nc, Ng, P, dt)
+            pv, cv, gv = oracle.summarize(K, bt, sl, g)
+            plan = oracle.Plan(plan=oracle.PLAN_RATIO, sink_pages=0, window_pages=0, rho_g_bp=rho[0], rho_c_bp=rho[1], rho_p_bp=rho[2])
+            _, nsel, _, _, cnt = oracle.select(Q, pv, cv, gv, sl, g, plan, P, detail=True)
+            counts.append((int(nsel[0, 0]), cnt[0, 0].tolist()))
+        assert counts[0] == counts[1]
+        assert abs(100.0 * counts[1][0] / P - float(f[4])) <= 1.0       # the printed budget, to the percent
+
+
 # ------------------------------------------------------------------ P2: flat plan == brute-force top-k
 @pytest.mark.parametrize("which", ["cfg1", "ragged"])
 def test_flat_plan_is_bruteforce_topk(which, cfg1, ragged):

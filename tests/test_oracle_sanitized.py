@@ -31,7 +31,8 @@ def _records(path):
     return out
 
 
-def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
+@pytest.mark.parametrize("summary_dtype", [oracle.SUMMARY_F32, oracle.SUMMARY_BF16])
+def test_oracle_is_clean_under_asan_and_ubsan(tmp_path, summary_dtype):
     exe = str(tmp_path / "oracle_sanitized")
     cmd = ["gcc", "-O1", "-g", "-fno-fast-math", "-ffp-contract=off", "-fsanitize=address,undefined",
            "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan",
@@ -46,7 +47,7 @@ def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
                                pages_per_chunk=4, chunks_per_grid=4)
     wl = workload.generate(sp, 77, seq_lens=[3000, 1237, 16])          # the last one is covered by its safety pages
     K, V, Q, bt, sl = host_arrays(wl)
-    g = geom_of(sp)
+    g = geom_of(sp, summary_dtype=summary_dtype)
     per = (9, 0, 2)
     plans = [plan_of(sp),
              plan_of(sp, plan=oracle.PLAN_RATIO, rho_g_bp=5000, rho_c_bp=4000, rho_p_bp=3000, cut_rule=oracle.CUT_THRESHOLD),
@@ -63,7 +64,7 @@ def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
     inp = tmp_path / "in.bin"
     with open(inp, "wb") as f:
         f.write(rec(np.array([g.n_q_heads, g.n_kv_heads, g.head_dim, g.page_size, g.pages_per_chunk, g.chunks_per_grid,
-                              g.max_pages], np.int32)))
+                              g.max_pages, g.summary_dtype], np.int32)))
         f.write(rec(np.array([[p.plan, p.sink_pages, p.window_pages, p.budget_pages, p.budget_bp, p.over_chunk, p.over_grid,
                                p.rho_g_bp, p.rho_c_bp, p.rho_p_bp, p.probe, p.cut_rule] for p in plans], np.int32)))
         f.write(rec(sl.astype(np.int32)) + rec(bt.astype(np.int32)) + rec(K) + rec(V) + rec(Q))

@@ -15,6 +15,7 @@ from gpu_common import config_of, gpu_plan, to_device
 from helpers import geom_of, host_arrays, plan_of
 
 pytestmark = pytest.mark.gpu
+SUMMARY_DTYPE_SWEEP = False       # nothing here reads or writes summary vectors
 
 
 def _lists(lib, d, plan, batch, sp):
