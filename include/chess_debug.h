@@ -26,9 +26,9 @@ int chess_debug_force_schedule(chess_ctx* ctx, int32_t schedule);
 int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on);
 
 /* Test hook: the number of polls after which a workgroup of chess_select / chess_decode_step gives up waiting for
- * the keys of the other members of its cluster (0 restores the default, 32768, about 30 ms).  With a limit of 1 or
- * 2 the waits fail on purpose: every workgroup still leaves normally, the workspace's error flag is raised, the
- * results are undefined and the workspace must be re-initialised. */
+ * the keys of the other members of its cluster (0 restores the default, 32768, about 30 ms).  With a negative value
+ * every such wait is given up before its first poll, on purpose: every workgroup still leaves normally, the
+ * workspace's error flag is raised, the results are undefined and the workspace must be re-initialised. */
 int chess_debug_set_poll_limit(chess_ctx* ctx, int32_t polls);
 
 /* Test hook: force the split-K shape of the decode entry points (n_splits in [1, 256] with n_splits * G <= 1024,

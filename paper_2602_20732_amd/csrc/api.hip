@@ -317,12 +317,15 @@ static int64_t choose_cluster(const chess_ctx* ctx, int64_t pairs, int64_t capac
 
 // Which schedule the levels run on (select_device.h).  merged: all chunks are scored with the grids, which saves a
 // dependent memory phase and an exchange for n_c - k_g N_g more chunk vectors; it pays while the launch is bound by
-// its chain of memory round trips rather than by bytes, i.e. while the (sequence, head) pairs do not outnumber the
-// compute units several times over.  Otherwise lazy, and every member scores all grids itself when they are few.
+// its chain of memory round trips rather than by bytes.  Otherwise lazy, and every member scores all grids itself
+// when they are few.
 static void choose_schedule(const chess_ctx* ctx, int64_t pairs, int64_t cluster, chess::SelectParams* sp)
 {
     const int svec = kHeadDim * (ctx->cfg.summary_dtype == CHESS_SUMMARY_BF16 ? 2 : 4);
-    sp->merged = ctx->force_schedule > 0 ? ctx->force_schedule == 2 : pairs <= 2 * (int64_t)ctx->n_cu;
+    // measured on MI355X: merged wins when several workgroups share a (sequence, head) (an exchange is saved, not only
+    // a phase) and all chunk vectors of the launch stay below about 24 MB (cfg4a: bf16 summaries yes, fp32 no)
+    const int64_t chunk_bytes = pairs * ctx->geom.max_chunks * svec;
+    sp->merged = ctx->force_schedule > 0 ? ctx->force_schedule == 2 : (cluster > 1 && chunk_bytes <= (24LL << 20));
     sp->local_grids = pairs * cluster * ctx->geom.max_grids * svec <= (4LL << 20);   // repeated grid reads stay small
 }
 
@@ -343,7 +346,7 @@ static int prepare_select(chess_ctx* ctx, const chess_select_plan* plan, chess::
     sp.cap_kg = (int32_t)bd.kg;
     sp.cap_kc = (int32_t)bd.kc;
     sp.probe = plan->probe;
-    sp.poll_limit = ctx->poll_limit > 0 ? ctx->poll_limit : (1 << 15);
+    sp.poll_limit = ctx->poll_limit > 0 ? ctx->poll_limit : ctx->poll_limit < 0 ? 0 : (1 << 15);   // < 0: every wait fails at once
     sp.general_cut = ctx->force_general_cut;
     sp.budget_per_seq = plan->plan == CHESS_PLAN_RATIO ? nullptr : plan->budget_per_seq;
     sp.keep_ties = plan->cut_rule == CHESS_CUT_THRESHOLD;
@@ -630,7 +633,7 @@ int chess_debug_force_general_cut(chess_ctx* ctx, int32_t on)
 
 int chess_debug_set_poll_limit(chess_ctx* ctx, int32_t polls)
 {
-    if (!ctx || polls < 0) return CHESS_EINVAL;
+    if (!ctx) return CHESS_EINVAL;
     ctx->poll_limit = polls;
     return CHESS_OK;
 }

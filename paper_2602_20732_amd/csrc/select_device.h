@@ -267,12 +267,15 @@ struct Prof {
     long long t[kSlots];
     __device__ __forceinline__ Prof() { for (int i = 0; i < kSlots; ++i) t[i] = 0; }
     __device__ __forceinline__ void mark(int i) { t[i] = wall_clock64(); }
+    // the clock once `value` has arrived in a register (waits for the load that produces it)
+    __device__ __forceinline__ void mark_after(int i, int value) { asm volatile("" ::"v"(value)); t[i] = wall_clock64(); }
     __device__ __forceinline__ void store(int32_t* dst) const
     {
         for (int i = 0; i < kSlots; ++i) dst[i] = t[i] != 0 ? (int32_t)(t[i] - t[0]) : -1;
     }
 #else
     __device__ __forceinline__ void mark(int) {}
+    __device__ __forceinline__ void mark_after(int, int) {}
 #endif
 };
 
@@ -526,6 +529,8 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
         int n = 0;
 #pragma unroll
         for (int x = 0; x < R; ++x) {
+            key[x] = 0ull;
+            if (x * kSelThreads >= n_slots) continue;             // uniform
             const int i = x * kSelThreads + tid;
             key[x] = (i < n_slots && active(i)) ? keys[i] : 0ull;
             const bool valid = key[x] != 0ull;
@@ -827,7 +832,7 @@ struct SlotRef {
 
 // Units a 16-lane group requests before it waits: one memory round trip covers kFly * 16 work slots of a workgroup.
 template <class T>
-constexpr int kFlyOf = sizeof(T) == 2 ? 16 : 12;
+constexpr int kFlyOf = sizeof(T) == 2 ? 12 : 9;      // (what the fused step's register budget holds without spilling)
 
 // Scores of the work slots [lo, hi).  `target(slot)` says which unit a slot is.  The key of a slot goes to
 // lds_keys[dest] (0 for no unit) when the level is local, else it is published in pub[dest].  (Two pointers of
@@ -844,12 +849,15 @@ __device__ __forceinline__ void score_rows(const T* __restrict__ grids_row, cons
         Vec<T> v[kFly];
 #pragma unroll
         for (int x = 0; x < kFly; ++x) {
+            unit[x] = -1;
+            dest[x] = -1;
+            if (s0 + kSelGroups * x >= hi) continue;  // uniform over the workgroup: rows of slots the share does not have
             const int slot = s0 + kSelGroups * x + g16;
             const SlotRef ref = target(min(slot, hi - 1));
             unit[x] = slot < hi ? ref.unit : -1;
             dest[x] = slot < hi ? ref.dest : -1;
-            // always load (unit 0 when the slot has no unit): a branch here would make the compiler wait
-            // for each vector before asking for the next
+            // no per-lane condition on the load (unit 0 when the slot has no unit): that would make the compiler
+            // wait for each vector before asking for the next
             const T* base = ref.array == 0 ? grids_row : ref.array == 1 ? chunks_row : pages_row;
             v[x].load(base + (size_t)max(ref.unit, 0) * kHeadDim, ln);
         }
@@ -879,9 +887,9 @@ __device__ __forceinline__ uint64_t poll_word(const uint64_t* word, int limit)
 // The published keys a level needs, into the LDS copy the cuts work on: item j of n lands in keys[dest_of(j)] (dest
 // -1: the item is skipped) and comes from pub[dest], except that dest ov_dest0 / ov_dest1 (if >= 0) come from
 // tail[ov_word0] / tail[ov_word1]: the keys of units the decode step has just refreshed, which one workgroup
-// publishes in words of their own.  The words are polled, eight per thread in flight, until every one of them is
-// there.  Ends with a workgroup barrier; returns false (to every thread) if a word did not arrive within the poll
-// limit.
+// publishes in words of their own.  The words are polled, up to eight per thread in flight, until every one of them
+// is there.  Ends with a workgroup barrier; returns false (to every thread) if a word did not arrive within the
+// poll limit.
 template <class DestOf>
 __device__ __forceinline__ bool pull_keys(const uint64_t* pub, const uint64_t* tail, int n, DestOf dest_of, int ov_dest0,
                                           int ov_word0, int ov_dest1, int ov_word1, uint64_t* keys, int limit)
@@ -893,25 +901,34 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, const uint64_t* t
         uint64_t v[kPer];
         int dest[kPer];
         const uint64_t* word[kPer];
+        const int n_here = min(kPer, (n - j0 + kSelThreads - 1) / kSelThreads);   // rounds of 256 words that exist (uniform)
 #pragma unroll
         for (int x = 0; x < kPer; ++x) {
-            const int j = j0 + x * kSelThreads + tid;
-            const int d = dest_of(min(j, n - 1));
-            dest[x] = j < n ? d : -1;
-            word[x] = pub + max(d, 0);
-            if (d >= 0 && d == ov_dest0) word[x] = tail + ov_word0;
-            if (d >= 0 && d == ov_dest1) word[x] = tail + ov_word1;
+            dest[x] = -1;
+            word[x] = pub;
+            if (x < n_here) {
+                const int j = j0 + x * kSelThreads + tid;
+                const int d = dest_of(min(j, n - 1));
+                dest[x] = j < n ? d : -1;
+                word[x] = pub + max(d, 0);
+                if (d >= 0 && d == ov_dest0) word[x] = tail + ov_word0;
+                if (d >= 0 && d == ov_dest1) word[x] = tail + ov_word1;
+            }
         }
         int polls = 0;
+        if (limit <= 0) { ok = false; break; }        // (a test asked for every wait to fail)
         while (true) {
             bool missing = false;
 #pragma unroll
-            for (int x = 0; x < kPer; ++x) v[x] = observe_u64(word[x]);       // unconditional: all stay in flight
+            for (int x = 0; x < kPer; ++x) {
+                v[x] = 1ull;
+                if (x < n_here) v[x] = observe_u64(word[x]);      // no per-lane condition: all stay in flight
+            }
 #pragma unroll
             for (int x = 0; x < kPer; ++x) missing = missing || (dest[x] >= 0 && v[x] == 0ull);
             if (__ballot(missing) == 0ull) break;
             if (++polls >= limit) { ok = false; break; }
-            __builtin_amdgcn_s_sleep(1);
+            __builtin_amdgcn_s_sleep(2);
         }
 #pragma unroll
         for (int x = 0; x < kPer; ++x)
@@ -928,14 +945,25 @@ __device__ __forceinline__ void load_probe(const uint16_t* __restrict__ q_rows, 
     const int ln = threadIdx.x & 15;
 #pragma unroll
     for (int i = 0; i < 8; ++i) pr[i] = 0.0;
-    for (int r = 0; r < group; ++r) {
-        const uint16_t* row = q_rows + (size_t)r * kHeadDim;
-        const uint2 a = *reinterpret_cast<const uint2*>(row + Vec<T>::lane_dim(ln, 0));
-        const uint2 c = *reinterpret_cast<const uint2*>(row + Vec<T>::lane_dim(ln, 4));
-        pr[0] += (double)__uint_as_float(a.x << 16); pr[1] += (double)__uint_as_float(a.x & 0xffff0000u);
-        pr[2] += (double)__uint_as_float(a.y << 16); pr[3] += (double)__uint_as_float(a.y & 0xffff0000u);
-        pr[4] += (double)__uint_as_float(c.x << 16); pr[5] += (double)__uint_as_float(c.x & 0xffff0000u);
-        pr[6] += (double)__uint_as_float(c.y << 16); pr[7] += (double)__uint_as_float(c.y & 0xffff0000u);
+    // four rows per request (a row beyond the group repeats the last one and is not added): the usual groups of up
+    // to four query heads cost one memory round trip, not one per row
+    for (int r0 = 0; r0 < group; r0 += 4) {
+        uint2 a[4], c[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const uint16_t* row = q_rows + (size_t)min(r0 + x, group - 1) * kHeadDim;
+            a[x] = *reinterpret_cast<const uint2*>(row + Vec<T>::lane_dim(ln, 0));
+            c[x] = *reinterpret_cast<const uint2*>(row + Vec<T>::lane_dim(ln, 4));
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            if (r0 + x < group) {
+                pr[0] += (double)__uint_as_float(a[x].x << 16); pr[1] += (double)__uint_as_float(a[x].x & 0xffff0000u);
+                pr[2] += (double)__uint_as_float(a[x].y << 16); pr[3] += (double)__uint_as_float(a[x].y & 0xffff0000u);
+                pr[4] += (double)__uint_as_float(c[x].x << 16); pr[5] += (double)__uint_as_float(c[x].x & 0xffff0000u);
+                pr[6] += (double)__uint_as_float(c[x].y << 16); pr[7] += (double)__uint_as_float(c[x].y & 0xffff0000u);
+            }
+        }
     }
 }
 
@@ -1071,8 +1099,9 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
         const bool local = C == 1 || (level == 0 && !merged && sp.local_grids != 0 && n_work <= kSelGroups * 8);
         if (n_work > 0) {
             // (the member that refreshes the tail units has a chain of dependent loads of its own to get through
-            // before the first cut: it takes no share of the first phase, the others split it)
-            const bool spare0 = tail_on && !local && level == 0;
+            // before the first cut: it takes no share of the first phase if the others can still cover it in one
+            // memory round trip each)
+            const bool spare0 = tail_on && !local && level == 0 && C > 1 && ceil_div_i(n_work, C - 1) <= Scorer::kTrip;
             const int sharers = spare0 ? C - 1 : C, mine = spare0 ? m - 1 : m;
             const int per = local ? n_work : ceil_div_i(ceil_div_i(n_work, sharers), Scorer::kShareRound) * Scorer::kShareRound;
             const int lo = local ? 0 : (mine < 0 ? n_work : min(n_work, mine * per)), hi = min(n_work, lo + per);
@@ -1178,7 +1207,8 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
 // The scorer of one (sequence, KV head): a level's vectors are rows of one array, the probe is in registers.
 template <class T>
 struct HeadScorer {
-    static constexpr int kShareRound = 16;           // whole rows of 16-lane groups
+    static constexpr int kShareRound = 1;
+    static constexpr int kTrip = kSelGroups * kFlyOf<T>;   // slots a member scores per memory round trip
     const T* pages_row;
     const T* chunks_row;
     const T* grids_row;

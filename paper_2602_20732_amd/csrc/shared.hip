@@ -49,6 +49,7 @@ constexpr int kSharedSlots = 8;                      // slots a workgroup scores
 template <class T>
 struct SharedScorer {
     static constexpr int kShareRound = 1;
+    static constexpr int kTrip = kSharedSlots;
     const SharedTable& tab;
     int b;
     const Geom& g;

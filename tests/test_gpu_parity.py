@@ -394,7 +394,7 @@ def test_a_wait_that_is_given_up_raises_the_error_flag_and_every_kernel_still_en
     nsel = torch.full((1, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
     out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
     lib.debug_force_cluster(4)
-    lib.debug_set_poll_limit(1)
+    lib.debug_set_poll_limit(-1)                          # every wait for other members' keys is given up at once
     lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids, nsel, ws)
     lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws)
     torch.cuda.synchronize()                              # returns: nobody is left waiting
@@ -476,7 +476,7 @@ def test_per_sequence_budgets(plan_kw):
 
 def test_shared_device_switch_never_waits():
     """chess_config.shared_device: every (sequence, KV head) is one workgroup's, so no launch waits for another
-    workgroup.  With a poll limit of 1 (any wait would give up at once and raise the error flag) select, the fused
+    workgroup.  With every wait set to fail at once (any wait would raise the error flag) select, the fused
     step with its tail refresh and the model-wide selection must still return the oracle's lists, flag clear."""
     sp = workload.spec("cfg2", scale=1 / 2)
     wl = workload.generate(sp, workload.default_seed("cfg2"))
@@ -485,7 +485,7 @@ def test_shared_device_switch_never_waits():
     d = to_device(wl)
     import dataclasses
     lib = pk.Chess(dataclasses.replace(config_of(sp), shared_device=True))
-    lib.debug_set_poll_limit(1)
+    lib.debug_set_poll_limit(-1)
     lib.debug_force_cluster(8)                                       # must not override the switch
     summ, ws = lib.new_summaries(), lib.new_workspace()
     lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
