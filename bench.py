@@ -14,8 +14,8 @@ from HIP-event timing of that kernel alone, the dense full-KV kernel of this lib
 and the CPU oracle timed on the host cores for the same step.  Further objects on the same line, each timed the
 same way: `us_per_step_spread` (p10 / median / p90 over separately timed replays), `summarize_full_pass`,
 `shared_scope` (the paper's model-wide selection over --shared-layers layers), `steady_state` (reuse and reselect
-steps of the paper's operating point), `trigger` (the Sec. 3.3 monitor), `selection_quality` (recall against the
-exact top-k; not a parity check).
+steps of the paper's operating point), `trigger` (the Sec. 3.3 monitor), `bf16_summaries` (the same step with the
+summary vectors stored as bf16: half the bytes the selection reads).
 """
 from __future__ import annotations
 
@@ -48,14 +48,17 @@ def parse():
     ap.add_argument("--fanout", default="", help="NcxNg: pages per chunk x chunks per grid instead of the workload's 8x8")
     ap.add_argument("--cluster", type=int, default=0,
                     help="tuning aid: force the workgroups per (sequence, KV head) of select / decode_step (0 = automatic)")
+    ap.add_argument("--summary-dtype", default="fp32", choices=["fp32", "bf16"],
+                    help="storage type of the summary vectors for the headline step (the other one is timed beside it)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
-def algorithmic_bytes(sp, seq_lens, nsel, counts):
-    """Bytes the method must move per step (one pool): select = vectors of the units it scores,
-    attention = K and V of the listed pages, summarize = the tail page + the child vectors re-read."""
+def algorithmic_bytes(sp, seq_lens, nsel, counts, elem=4):
+    """Bytes the method must move per step (one pool): select = vectors of the units it scores (lazily: all grids,
+    the chunks of kept grids, the pages of kept chunks), attention = K and V of the listed pages, summarize = the tail
+    page + the child vectors re-read.  elem = bytes per summary element (4: fp32, 2: bf16)."""
     d, B, Nc, Ng = sp.head_dim, sp.page_size, sp.pages_per_chunk, sp.chunks_per_grid
     sel = 0
     for b, L in enumerate(seq_lens):
@@ -63,9 +66,9 @@ def algorithmic_bytes(sp, seq_lens, nsel, counts):
         ng = -(-(-(-P // Nc)) // Ng)
         for h in range(sp.n_kv_heads):
             kg, kc, _ = counts[b][h]
-            sel += (ng + kg * Ng + kc * Nc) * d * 4
+            sel += (ng + kg * Ng + kc * Nc) * d * elem
     attn = int(nsel.sum()) * B * d * 2 * 2
-    summ = len(seq_lens) * sp.n_kv_heads * (B * d * 2 + (Nc + Ng + 3) * d * 4)
+    summ = len(seq_lens) * sp.n_kv_heads * (B * d * 2 + (Nc + Ng + 3) * d * elem)
     return {"select": sel, "attention": attn, "summarize": summ, "step": sel + attn + summ}
 
 
@@ -108,7 +111,7 @@ def shared_scope(lib, sp, seq_lens, lens, plan, n_layers, timed):
         kg = min(ng, -(-plan.over_grid * kct // Ng))
         kc = min(kct, kg * Ng, nc)
         units += (ng if kg < ng else 0) + (kg * Ng if kc < min(kg * Ng, nc) else 0) + kc * Nc + plan.window_pages
-    byts = units * n_layers * sp.n_kv_heads * d * 4
+    byts = units * n_layers * sp.n_kv_heads * d * (2 if lib.cfg.summary_dtype == 1 else 4)
     sel_ms = ms - ms_a
     return {"layers": n_layers, "us_per_selection": round(ms * 1e3, 1), "anchors_us": round(ms_a * 1e3, 1),
             "us_per_layer": round(ms * 1e3 / n_layers, 2), "algorithmic_bytes": byts,
@@ -170,44 +173,6 @@ def steady_state(lib, sp, plan, pools, summs, n_pools, n_q, out, ws, timed, step
             "kernel_launches": {"reuse_step": 1, "reselect_step": 2}}
 
 
-def selection_quality(lib, sp, plan, pool, summ, ws):
-    """What the coarse-to-fine pruning costs in accuracy on this synthetic workload (not a parity check: the reference
-    here is torch): recall of the cascade's pages against the exact top-k of all candidate page scores, and the
-    relative L2 distance between the sparse and the Full-KV attention outputs."""
-    import torch
-    wl, qs = pool
-    H, G, B = sp.n_kv_heads, sp.group, sp.page_size
-    ids = torch.empty((sp.batch, H, sp.max_selected), dtype=torch.int32, device="cuda")
-    nsel = torch.empty((sp.batch, H), dtype=torch.int32, device="cuda")
-    out = torch.empty((sp.batch, sp.n_q_heads, sp.head_dim), device="cuda")
-    dense = torch.empty_like(out)
-    lib.select(qs[0], summ, wl.seq_lens, plan, ids, nsel, ws)
-    lib.sparse_decode(qs[0], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out, ws)
-    lib.dense_decode(qs[0], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, dense, ws)
-    torch.cuda.synchronize()
-    pages = lib.summary_views(summ)[0]
-    probe = qs[0].double().view(sp.batch, H, G, sp.head_dim).sum(2)
-    hit = tot = 0
-    for b in range(sp.batch):
-        P = -(-int(wl.seq_lens[b]) // B)
-        lo, hi = plan.sink_pages, P - plan.window_pages
-        if hi <= lo:
-            continue
-        k = min(sp.budget_for(P), hi - lo)
-        sc = torch.einsum("hpd,hd->hp", pages[b, :, lo:hi].double(), probe[b])
-        top = sc.topk(k, dim=1).indices + lo
-        for h in range(H):
-            got = set(ids[b, h, :int(nsel[b, h])].tolist())
-            hit += len(got & set(top[h].tolist()))
-            tot += k
-    rel = float((out - dense).norm() / dense.norm())
-    return {"recall_vs_exact_topk": round(hit / max(tot, 1), 4), "sparse_vs_dense_rel_l2": round(rel, 4),
-            "reference": "torch (fp64 page scores, top-k over all candidate pages)",
-            "note": "properties of the method at this budget on the synthetic topics (a KV head's 4 query heads draw "
-                    "up to 16 topic segments, more pages than a 1 % budget holds), not implementation error: "
-                    "parity with the oracle is what the tests check"}
-
-
 def trigger_monitor(lib, sp, timed, vocab=151936):
     """Sec. 3.3 monitor per decode step: entropy of the batch's logits rows (bf16, a 152K vocabulary) + page statistics."""
     import torch
@@ -228,13 +193,17 @@ def trigger_monitor(lib, sp, timed, vocab=151936):
             "vocab": vocab, "kernel_launches_per_step": 1}
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch of the step kernel from the committed rocprofv3 counter summary, or None."""
-    path = os.path.join(ROOT, "profiles", "step_kernel_hbm_traffic.txt")
+TRAFFIC_FILE = os.path.join("profiles", "step_kernel_hbm_traffic.txt")
+
+
+def measured_traffic(workload_name, summary_dtype):
+    """HBM bytes per launch of the step kernel from the committed rocprofv3 counter summary (a separate run of this
+    script under rocprofv3 --pmc, see the file's header: not measured in this run), or None."""
+    key = workload_name + ("_bf16" if summary_dtype == "bf16" else "")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, TRAFFIC_FILE)):
             f = line.split()
-            if len(f) >= 5 and f[0] == workload_name:
+            if len(f) >= 5 and f[0] == key:
                 return int((float(f[1]) * float(f[3]) + float(f[2]) * float(f[4])) * 1024)
     except OSError:
         pass
@@ -278,8 +247,10 @@ def main():
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
+    dt_code = {"fp32": pk.SUMMARY_F32, "bf16": pk.SUMMARY_BF16}
+    other_dtype = "bf16" if args.summary_dtype == "fp32" else "fp32"
     cfg = pk.Config(sp.n_q_heads, sp.n_kv_heads, sp.page_size, sp.batch, sp.max_pages, sp.max_selected,
-                    sp.pages_per_chunk, sp.chunks_per_grid)
+                    sp.pages_per_chunk, sp.chunks_per_grid, summary_dtype=dt_code[args.summary_dtype])
     lib = pk.Chess(cfg)
     lib.debug_force_cluster(args.cluster)
     plan = pk.SelectPlan(sink_pages=sp.sink_pages, window_pages=sp.window_pages, budget_pages=sp.budget_pages,
@@ -436,19 +407,45 @@ def main():
         nc = -(-P // Nc)
         kg = min(-(-nc // Ng), -(-plan.over_grid * kct // Ng))
         counts.append([(kg, min(kct, kg * Ng, nc), k)] * sp.n_kv_heads)
-    ab = algorithmic_bytes(sp, lens, nsel_h, counts)
+    elem = {"fp32": 4, "bf16": 2}
+    ab = algorithmic_bytes(sp, lens, nsel_h, counts, elem[args.summary_dtype])
     fused_us = kern["decode_step"]["us_per_step"]
+
+    # the same step with the summaries stored the other way (its own context and summary buffers, same inputs)
+    import dataclasses
+    lib2 = pk.Chess(dataclasses.replace(cfg, summary_dtype=dt_code[other_dtype]))
+    lib2.debug_force_cluster(args.cluster)
+    summs2 = []
+    for wl, _ in pools:
+        s2 = lib2.new_summaries()
+        lib2.summarize(wl.k_pool, wl.block_table, wl.seq_lens, s2)
+        summs2.append(s2)
+    ws2 = lib2.new_workspace()
+    torch.cuda.synchronize()
+
+    def only_fused_other(i):
+        wl, qs = pools[i % n_pools]
+        lib2.decode_step(qs[(i // n_pools) % n_q], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summs2[i % n_pools],
+                         plan, ids, nsel, out, ws2, refresh_tail=True)
+
+    ms_other, _ = timed(only_fused_other, args.steps, min(args.warmup, 8), not args.eager)
+    if lib2.workspace_error(ws2) != 0:
+        raise RuntimeError("a kernel gave up a bounded wait during the timed steps (was the device shared?)")
+    ab_other = algorithmic_bytes(sp, lens, nsel.cpu().numpy(), counts, elem[other_dtype])
+    del summs2, ws2
+    lib2.close()
     achieved = ab["step"] / (fused_us * 1e-6) / 1e9
     dec_us = kern3["sparse_decode"]["us_per_step"]
     result = {
         "metric": "sparse decode attn us/step (tail summarize + select + sparse attention + merge), 1% KV budget",
         "value": round(ms_step * 1e3, 3), "unit": "us/step", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_step, 6), "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 K/V/q, fp32 accumulate, fp64 scores", "data": "synthetic",
+        "dtype": "bf16 K/V/q, fp32 accumulate, fp64 scores, %s summaries" % args.summary_dtype, "data": "synthetic",
         "config": {"workload": args.workload, "batch": sp.batch, "context": list(sp.ctx), "n_q_heads": sp.n_q_heads,
                    "n_kv_heads": sp.n_kv_heads, "page_size": sp.page_size, "budget_bp": sp.budget_bp,
                    "budget_pages": sp.budget_pages, "sink_pages": sp.sink_pages, "window_pages": sp.window_pages,
-                   "pages_per_chunk": Nc, "chunks_per_grid": Ng, "kv_pools_rotated": n_pools,
+                   "pages_per_chunk": Nc, "chunks_per_grid": Ng, "summary_dtype": args.summary_dtype,
+                   "kv_pools_rotated": n_pools,
                    "query_sets_per_pool": n_q, "launch": "eager" if args.eager else "hip_graph"},
         "step_gbs": round(ab["step"] / (ms_step * 1e-3) / 1e9, 1),
         "step_frac_of_hbm_peak": round(ab["step"] / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
@@ -460,13 +457,20 @@ def main():
                         "sparse_decode_gbs": round(ab["attention"] / (dec_us * 1e-6) / 1e9, 1)},
         "roofline": {"bound": "hbm", "kernel": "step_kernel (tail refresh + selection levels + sparse attention over the list + split merge)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload)},
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(args.workload, args.summary_dtype),
+                     "traffic_source": "committed counter summary " + TRAFFIC_FILE + " (rocprofv3 --pmc runs of this script, "
+                                       "not this run; the runs behind it rotate over fewer KV pools, see the file's header)"},
+        other_dtype + "_summaries": {"us_per_step": round(ms_other * 1e3, 3), "algorithmic_bytes": ab_other,
+                                     "gbs": round(ab_other["step"] / (ms_other * 1e-3) / 1e9, 1),
+                                     "frac_of_hbm_peak": round(ab_other["step"] / (ms_other * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                                     "timed_as": "the fused step alone in its own HIP graph, like roofline.achieved"},
         "setup_seconds": round(gen_s, 1),
     }
 
     B_, d_ = sp.page_size, sp.head_dim
-    full_bytes = sum(-(-L // B_) for L in lens) * sp.n_kv_heads * (B_ * d_ * 2 + d_ * 4) \
-        + sum(-(-(-(-L // B_)) // sp.pages_per_chunk) for L in lens) * sp.n_kv_heads * d_ * 4
+    e_ = elem[args.summary_dtype]
+    full_bytes = sum(-(-L // B_) for L in lens) * sp.n_kv_heads * (B_ * d_ * 2 + d_ * e_) \
+        + sum(-(-(-(-L // B_)) // sp.pages_per_chunk) for L in lens) * sp.n_kv_heads * d_ * e_
     result["summarize_full_pass"] = {"us": round(ms_full * 1e3, 1), "bytes": full_bytes,
                                      "gbs": round(full_bytes / (ms_full * 1e-3) / 1e9, 1),
                                      "frac_of_hbm_peak": round(full_bytes / (ms_full * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
@@ -478,7 +482,6 @@ def main():
         result["stack_of_32_layers_us"] = round(ms_step * 1e3 * 32, 1)
 
     if not args.no_dense:
-        result["selection_quality"] = selection_quality(lib, sp, plan, pools[0], summs[0], ws)
         d_steps = max(8, min(args.steps, 32))
         d_ms, _ = timed(dense_step, d_steps, 2, not args.eager)
         dense_bytes = sum(-(-L // B) for L in lens) * sp.n_kv_heads * B * sp.head_dim * 4
@@ -491,14 +494,16 @@ def main():
         raise RuntimeError("a kernel gave up a bounded wait during the timed steps (was the device shared?)")
 
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(sp, pools[0][0], plan)
+        result["cpu_baseline"] = cpu_baseline(sp, pools[0][0], plan, dt_code[args.summary_dtype])
 
     print(json.dumps(result))
 
 
-def cpu_baseline(sp, wl, plan):
-    """The oracle as it stands, single-threaded, on the host cores: full summarize + select + sparse
-    attention for a bounded sample of the batch (whole sequences), scaled to the batch."""
+def cpu_baseline(sp, wl, plan, summary_dtype=0):
+    """The oracle as it stands, on the host cores: full summarize + select + sparse attention for a bounded sample
+    of the batch (whole sequences), scaled to the batch.  `value` is one thread; `all_cores` runs the same sample
+    with one thread per sequence (the oracle is a plain C library called through ctypes, which releases the
+    interpreter lock, so the threads run in parallel)."""
     import numpy as np
 
     import oracle
@@ -506,7 +511,7 @@ def cpu_baseline(sp, wl, plan):
 
     n_seq = max(1, min(sp.batch, int(2 ** 21 // max(1, sp.ctx[1]))))      # ~2M tokens of summarize at most
     geom = oracle.Geometry(sp.n_q_heads, sp.n_kv_heads, sp.head_dim, sp.page_size, sp.pages_per_chunk,
-                           sp.chunks_per_grid, sp.max_pages)
+                           sp.chunks_per_grid, sp.max_pages, summary_dtype)
     oplan = oracle.Plan(sink_pages=plan.sink_pages, window_pages=plan.window_pages, budget_pages=plan.budget_pages,
                         budget_bp=plan.budget_bp)
     bt = wl.block_table[:n_seq].cpu()
@@ -543,7 +548,28 @@ def cpu_baseline(sp, wl, plan):
     t_sum, t_sel, t_att = (sum(p[i] for p in passes) / len(passes) for i in range(3))
     t0, t1, t2, t3 = 0.0, t_sum, t_sum + t_sel, t_sum + t_sel + t_att
     scale = sp.batch / n_seq
-    return {"value": round((t3 - t0) * scale * 1e6, 1), "unit": "us/step", "cores": 1, "kind": "oracle",
+
+    # the same sample on all cores: one thread per sequence
+    from concurrent.futures import ThreadPoolExecutor
+    try:
+        avail = len(os.sched_getaffinity(0))
+    except AttributeError:
+        avail = os.cpu_count() or 1
+    n_thr = max(1, min(n_seq, avail))
+
+    def one_seq(b):
+        sl1, bt1 = sl[b:b + 1], bt2[b:b + 1]
+        pv, cv, gv = oracle.summarize(K, bt1, sl1, geom)
+        ids, nsel = oracle.select(Q[b:b + 1], pv, cv, gv, sl1, geom, oplan, sp.max_selected)
+        oracle.attend(Q[b:b + 1], K, V, bt1, sl1, geom, ids, nsel)
+
+    tp0 = time.perf_counter()
+    with ThreadPoolExecutor(n_thr) as ex:
+        list(ex.map(one_seq, range(n_seq)))
+    t_par = time.perf_counter() - tp0
+    all_cores = {"value": round(t_par * scale * 1e6, 1), "unit": "us/step", "cores": n_thr,
+                 "sample": f"the same {n_seq} sequences, one thread each, one pass"}
+    return {"value": round((t3 - t0) * scale * 1e6, 1), "unit": "us/step", "cores": 1, "kind": "oracle", "all_cores": all_cores,
             "sample": f"{n_seq} of {sp.batch} sequences, mean of {len(passes)} passes, whole step (full-pass summarize {t1 - t0:.2f}s, select "
                       f"{t2 - t1:.3f}s, sparse attention {t3 - t2:.3f}s), scaled x{scale:g} to the batch; the oracle "
                       "has no incremental summarize, so its step re-summarizes the whole context",

@@ -96,7 +96,8 @@ bool plan_bounds(const chess_ctx* ctx, const chess_select_plan* pl, Bounds* out)
         b.kc = nc;
         b.kp = std::min<int64_t>(cand, std::max<int64_t>(0, (int64_t)g.max_sel - pl->sink_pages - pl->window_pages));
     }
-    b.slots = std::max<int64_t>(ng + nc, b.kc * g.n_c);       // grid and chunk keys by unit, side by side; then the page slots
+    // grid keys and, behind them, chunk keys by unit (merged) or N_g slots per kept grid (lazy); then the page slots
+    b.slots = std::max<int64_t>(ng + std::max<int64_t>(nc, b.kg * g.n_g), b.kc * g.n_c);
     b.lists = std::max<int64_t>(b.kg, b.kc);
     *out = b;
     return true;
@@ -186,6 +187,8 @@ int chess_create(const chess_config* cfg, chess_ctx** out)
     g.max_chunks = (int32_t)cdiv(g.max_pages, g.n_c);
     g.max_grids = (int32_t)cdiv(g.max_chunks, g.n_g);
     g.max_sel = cfg->max_selected_pages;
+    g.inv_nc = g.n_c > 1 ? (uint32_t)((0x100000000ull + g.n_c - 1) / g.n_c) : 0u;
+    g.inv_ng = g.n_g > 1 ? (uint32_t)((0x100000000ull + g.n_g - 1) / g.n_g) : 0u;
     c->sm_scale = cfg->sm_scale > 0.f ? cfg->sm_scale : 1.0f / std::sqrt((float)kHeadDim);
 
     int dev = 0, v = 0;

@@ -21,6 +21,7 @@ struct Geom {
     int32_t n_c, n_g;                // pages per chunk, chunks per grid
     int32_t max_pages, max_chunks, max_grids;   // row strides of block table / summary arrays
     int32_t max_sel;                 // row stride of page_ids
+    uint32_t inv_nc, inv_ng;         // ceil(2^32 / n_c), ceil(2^32 / n_g) (0 for 1): divisions by n_c / n_g as a multiply-high
 };
 
 struct SelectParams {

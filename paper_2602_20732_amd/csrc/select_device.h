@@ -81,9 +81,8 @@ __device__ __forceinline__ int opaque_tid()
     return t;
 }
 
-// x / fan without a division: inv = ceil(2^32 / fan) (unused for fan = 1); exact for x < 2^24 and fan <= 256 (the
+// x / fan without a division: inv = ceil(2^32 / fan), computed by the host (unused for fan = 1); exact for x < 2^24 and fan <= 256 (the
 // error term x * e / 2^32 with e = fan * inv - 2^32 < fan stays below 1 / fan)
-__device__ __forceinline__ uint32_t inv_of(int fan) { return fan > 1 ? (uint32_t)((0x100000000ull + fan - 1) / fan) : 0u; }
 __device__ __forceinline__ int div_by(int x, int fan, uint32_t inv) { return fan > 1 ? (int)__umulhi((unsigned)x, inv) : x; }
 
 // Inclusive scan over the 64 lanes of a wave with DPP row shifts and row broadcasts (no LDS).
@@ -511,9 +510,14 @@ __device__ __forceinline__ void rank_members(uint64_t mine, int my_slot, int cnt
 // The kBins bins are LINEAR in key_float between the smallest and the largest key: a monotone map, so a higher bin
 // means a strictly larger score.  A scan from the top finds the bin the k-th largest key falls in, and the few
 // keys of that bin are ranked exactly by (key, slot).
-template <int R>
+//
+// kPre: the thread's keys come in `pre` (the pull left them in registers, together with every wave's bounds and count
+// in sh.st_*, before its closing barrier): nothing is re-read and the first barrier here falls away.  Only for
+// levels in which every slot competes.
+template <int R, bool kPre = false>
 __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, const ActiveRule& active, const KeepRule& k_of,
-                                                bool keep_ties, const EmitRule& emit, int cap, bool mark, Shared& sh)
+                                                bool keep_ties, const EmitRule& emit, int cap, bool mark, Shared& sh,
+                                                const uint64_t (&pre)[4])
 {
     static_assert(kBins == 16 * kWave, "a lane owns 16 bins");
     static_assert(R * kSelWaves <= kMaxRuns && R * kSelWaves <= 128, "run prefix is held in two values per lane");
@@ -524,7 +528,10 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
 
     // this thread's keys; every wave leaves the bounds and the count of what it sees
     uint64_t key[R];
-    {
+    if constexpr (kPre) {
+#pragma unroll
+        for (int x = 0; x < R; ++x) key[x] = pre[x < 4 ? x : 0];
+    } else {
         unsigned a = ~0u, b = 0u;
         int n = 0;
 #pragma unroll
@@ -542,8 +549,8 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
         a = wave_minmax32<true>(a);
         b = wave_minmax32<false>(b);
         if (lane == 63) { sh.st_min[wave] = a; sh.st_max[wave] = b; sh.st_cnt[wave] = n; }
+        __syncthreads();
     }
-    __syncthreads();
     unsigned lo_h = ~0u, hi_h = 0u;
     int n_valid = 0;
 #pragma unroll
@@ -797,15 +804,18 @@ __device__ __forceinline__ int cut_one_lane_each(uint64_t* keys, int n_slots, co
 // The cut of one level whose keys are complete in `keys` (LDS; the caller's barrier has made them visible): picks
 // the path by the level's size.  Returns the number kept (what would have been emitted; positions at or beyond
 // `cap` are not written: the caller treats a count above cap as an overflow).  Every thread must call it.
+// have_pre: the pull handed this thread's four keys over in registers (pull_keys_regs), in `pre`.
 __device__ __forceinline__ int cut_level(uint64_t* keys, int n_slots, const ActiveRule& active, const KeepRule& k_of,
-                                         bool keep_ties, bool general, const EmitRule& emit, int cap, bool mark, Shared& sh)
+                                         bool keep_ties, bool general, const EmitRule& emit, int cap, bool mark, Shared& sh,
+                                         bool have_pre, const uint64_t (&pre)[4])
 {
     int n = -1;
     if (!general) {
         if (n_slots <= kWave) n = cut_one_lane_each(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
         else if (n_slots <= 4 * kWave) n = cut_by_one_wave<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
-        else if (n_slots <= 4 * kSelThreads) n = cut_in_registers<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
-        else if (n_slots <= kRegsLarge * kSelThreads) n = cut_in_registers<kRegsLarge>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
+        else if (n_slots <= 4 * kSelThreads && have_pre) n = cut_in_registers<4, true>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
+        else if (n_slots <= 4 * kSelThreads) n = cut_in_registers<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
+        else if (n_slots <= kRegsLarge * kSelThreads) n = cut_in_registers<kRegsLarge>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
     }
     if (n >= 0) return n;
     // general path on the LDS copy of the keys: slots that do not compete are emptied first
@@ -937,6 +947,62 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, const uint64_t* t
     return __syncthreads_and(ok) != 0;
 }
 
+// The same for a level of at most 1024 slots whose keys sit in slot order (item j lands in keys[j]): thread t polls
+// words t, t + 256, t + 512, t + 768 and KEEPS them in key[0..3] (0 = empty or beyond n) for the cut that follows,
+// and every wave leaves the bounds (upper key halves) and the count of what it saw in sh.st_* before the closing
+// barrier, so that cut_in_registers can start at once.
+__device__ __forceinline__ bool pull_keys_regs(const uint64_t* pub, const uint64_t* tail, int n, int ov_dest0, int ov_word0,
+                                               int ov_dest1, int ov_word1, uint64_t* keys, uint64_t (&key)[4], int limit, Shared& sh)
+{
+    bool ok = limit > 0;
+    const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6;
+    const uint64_t* word[4];
+    const int n_here = (n + kSelThreads - 1) / kSelThreads;      // uniform
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        key[x] = 0ull;
+        word[x] = pub;
+        if (x < n_here) {
+            const int j = x * kSelThreads + tid;
+            const int d = min(j, n - 1);
+            word[x] = pub + d;
+            if (d == ov_dest0) word[x] = tail + ov_word0;
+            if (d == ov_dest1) word[x] = tail + ov_word1;
+        }
+    }
+    int polls = 0;
+    while (ok) {
+        bool missing = false;
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            key[x] = 1ull;
+            if (x < n_here) key[x] = observe_u64(word[x]);    // no per-lane condition: all stay in flight
+        }
+#pragma unroll
+        for (int x = 0; x < 4; ++x) missing = missing || key[x] == 0ull;
+        if (__ballot(missing) == 0ull) break;
+        if (++polls >= limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(2);
+    }
+    unsigned a = ~0u, b = 0u;
+    int cnt = 0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const int j = x * kSelThreads + tid;
+        if (j >= n || key[x] == kAbsentKey || !ok) key[x] = 0ull;
+        if (x < n_here && j < n) keys[j] = key[x];
+        const bool valid = key[x] != 0ull;
+        const unsigned hi = (unsigned)(key[x] >> 32);
+        a = valid ? min(a, hi) : a;
+        b = valid ? max(b, hi) : b;
+        cnt += __popcll(__ballot(valid));
+    }
+    a = wave_minmax32<true>(a);
+    b = wave_minmax32<false>(b);
+    if (lane == 63) { sh.st_min[wave] = a; sh.st_max[wave] = b; sh.st_cnt[wave] = cnt; }
+    return __syncthreads_and(ok) != 0;
+}
+
 // The probe of a (sequence, KV head): the sum of the group's query rows in fp64, g ascending (Eq. 4 with
 // Eq. 1's Flatten restricted to the group); this lane's dims as Vec<T> arranges them.
 template <class T>
@@ -977,7 +1043,7 @@ struct GridPhaseTarget {            // level 0: grids [0, n_g), then (merged) al
         return SlotRef{slot < ng ? 0 : 1, slot < ng ? slot : slot - ng, slot};
     }
 };
-struct ChunkPhaseTarget {           // level 1 (lazy): N_g slots per kept grid; chunk keys by unit, behind the grid keys
+struct ChunkPhaseTarget {           // level 1 (lazy): N_g slots per kept grid; chunk keys by slot, behind the grid keys
     const int32_t* parents;
     int fan, ng, nc;
     uint32_t inv;
@@ -985,7 +1051,7 @@ struct ChunkPhaseTarget {           // level 1 (lazy): N_g slots per kept grid; 
     {
         const int pi = div_by(slot, fan, inv);
         const int u = parents[pi] * fan + (slot - pi * fan);
-        return SlotRef{1, u < nc ? u : -1, u < nc ? ng + u : -1};
+        return SlotRef{1, u < nc ? u : -1, ng + slot};
     }
 };
 struct PagePhaseTarget {            // level 2: N_c slots per kept chunk; sink and window pages have no unit; keys by slot
@@ -1008,14 +1074,14 @@ struct CascadeResult {
 
 // Where the published words of one (sequence, KV head) -- one sequence under the model-wide scope -- start.
 struct PubLayout {
-    uint64_t* units;       // grid keys [0, n_g), then chunk keys [n_g, n_g + n_c): by unit
+    uint64_t* units;       // grid keys [0, n_g); behind them the chunk keys: by unit (merged) or N_g slots per kept grid (lazy)
     uint64_t* pages;       // page slots: N_c per kept chunk
 };
 __device__ __forceinline__ PubLayout pub_layout(uint64_t* row_words, const Geom& g)
 {
     PubLayout p;
     p.units = row_words;
-    p.pages = row_words + g.max_grids + g.max_chunks;
+    p.pages = row_words + g.max_grids + g.max_grids * g.n_g;     // (chunk slots of the lazy schedule: N_g per kept grid)
     return p;
 }
 
@@ -1052,23 +1118,26 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
                                         int32_t* phys_by_slot = nullptr, int32_t* sel_phys = nullptr)
 {
     const int s = sp.sink, w = sp.window;
-    const int nc = ceil_div_i(P, g.n_c), ng = ceil_div_i(nc, g.n_g);
+    const uint32_t inv_ng = g.inv_ng, inv_nc = g.inv_nc;                 // (divisions by N_c / N_g: multiply-high, exact below 2^24)
+    const int nc = div_by(P + g.n_c - 1, g.n_c, inv_nc), ng = div_by(nc + g.n_g - 1, g.n_g, inv_ng);
     const int k_budget = k_fixed > 0 ? k_fixed : clamp_i(ceil_bp(P, sp.budget_bp), 1, P);
-    const int kc_target = ceil_div_i(sp.over_chunk * k_budget, g.n_c);
+    const int kc_target = div_by(min(sp.over_chunk * k_budget, 1 << 23) + g.n_c - 1, g.n_c, inv_nc);
     const bool ratio = sp.plan == CHESS_PLAN_RATIO, flat = sp.plan == CHESS_PLAN_FLAT;
     const bool general = sp.general_cut != 0, keep_ties = sp.keep_ties != 0;
-    const uint32_t inv_ng = inv_of(g.n_g), inv_nc = inv_of(g.n_c);
     res->n_kp = 0; res->n_a = 0; res->n_p = 0; res->overflow = false;
 
-    const KeepRule rule_g{ratio ? sp.rho_g_bp : 0, flat ? kKeepAll : ceil_div_i(sp.over_grid * kc_target, g.n_g), sp.cap_kg};
-    const KeepRule rule_c{ratio ? sp.rho_c_bp : 0, flat ? kKeepAll : kc_target, sp.cap_kc};
-    const KeepRule rule_p{ratio ? sp.rho_p_bp : 0, k_budget, g.max_sel - s - w};
+    // how many units a level keeps (built where they are used: three of them alive across the loop cost registers)
+    auto rule_of = [&](int level) {
+        if (level == 0) return KeepRule{ratio ? sp.rho_g_bp : 0, flat ? kKeepAll : div_by(min(sp.over_grid * kc_target, 1 << 23) + g.n_g - 1, g.n_g, inv_ng), sp.cap_kg};
+        if (level == 1) return KeepRule{ratio ? sp.rho_c_bp : 0, flat ? kKeepAll : kc_target, sp.cap_kc};
+        return KeepRule{ratio ? sp.rho_p_bp : 0, k_budget, g.max_sel - s - w};
+    };
 
     // A grid level that keeps every grid needs no scores at all, and neither does a chunk level that keeps every
     // chunk of all the grids: the kept list is the list of the units that exist.  Large budgets and ratios near 1
     // end up here.
-    const bool all_grids = !general && rule_g(ng) >= ng;
-    const bool all_chunks = all_grids && rule_c(nc) >= nc;
+    const bool all_grids = !general && rule_of(0)(ng) >= ng;
+    const bool all_chunks = all_grids && rule_of(1)(nc) >= nc;
     // merged: the chunks are scored together with the grids (one memory phase and one exchange fewer)
     const bool merged = sp.merged != 0 && !all_grids;
     const bool tail_on = tail_words != nullptr;
@@ -1109,7 +1178,7 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
             if (level == 0) scorer(lo, hi, target0, local, keys, pub);
             else if (level == 1) scorer(lo, hi, target1, local, keys, pub);
             else scorer(lo, hi, target2, local, keys, pub);
-            if (!local) { if (level == 2) res->n_p = n_work; else res->n_a = ng + nc; }
+            if (!local) { if (level == 2) res->n_p = n_work; else res->n_a = max(res->n_a, level == 0 ? n_work : ng + n_work); }
         }
         // kPhys: the block-table entries of every page slot are requested now, behind this member's vectors, and
         // parked in LDS once the level's keys have been pulled (loads return in order: no wait of their own)
@@ -1132,12 +1201,16 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
         // the tail grid is unit n_g - 1, the tail chunk unit n_c - 1 (key slot n_g + n_c - 1); the tail page is the
         // last slot of the last kept chunk, if it competes at all (no window)
         int ov_dest0 = -1, ov_word0 = 0, ov_dest1 = -1, ov_word1 = 0;
+        uint64_t pulled[4] = {0ull, 0ull, 0ull, 0ull};
+        bool have_pulled = false;
+        const bool merged_phase = merged && level == 0;
         if (tail_on && n_work > 0) {
             if (level == 0) {
                 ov_dest0 = ng - 1; ov_word0 = 0;
                 if (merged) { ov_dest1 = ng + nc - 1; ov_word1 = 1; }
             } else if (level == 1) {
-                ov_dest0 = ng + nc - 1; ov_word0 = 1;
+                // (lazy: the tail chunk is the last existing slot of the last kept grid, if that is the tail grid)
+                if (n_kg > 0 && kept_grids[n_kg - 1] == ng - 1) { ov_dest0 = ng + (n_kg - 1) * g.n_g + (nc - 1 - (ng - 1) * g.n_g); ov_word0 = 1; }
             } else if (w == 0 && n_kc > 0 && kept_chunks[n_kc - 1] == nc - 1) {
                 ov_dest0 = (n_kc - 1) * g.n_c + (P - 1 - (nc - 1) * g.n_c); ov_word0 = 2;
             }
@@ -1157,14 +1230,23 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
                 if (sh.flag == 0) return false;
             }
         } else if (n_work > 0) {
+            // (every non-local phase keeps its keys in slot order; a phase of up to 1024 slots hands them to the cut
+            // in registers)
+            const int off = level == 1 ? ng : 0;
+            const int od0 = ov_dest0 >= 0 ? ov_dest0 - off : -1, od1 = ov_dest1 >= 0 ? ov_dest1 - off : -1;
             bool ok;
-            if (level == 1) ok = pull_keys(pub, tail_words, n_work, [&](int j) { return target1(j).dest; }, ov_dest0, ov_word0, ov_dest1, ov_word1, keys, sh.poll_limit);
-            else ok = pull_keys(pub, tail_words, n_work, [](int j) { return j; }, ov_dest0, ov_word0, ov_dest1, ov_word1, keys, sh.poll_limit);
+            if (n_work <= 4 * kSelThreads && !merged_phase) {
+                ok = pull_keys_regs(pub + off, tail_words, n_work, od0, ov_word0, od1, ov_word1, keys + off, pulled, sh.poll_limit, sh);
+                have_pulled = true;
+            } else {
+                ok = pull_keys(pub + off, tail_words, n_work, [](int j) { return j; }, od0, ov_word0, od1, ov_word1, keys + off, sh.poll_limit);
+            }
             if (!ok) return false;
         }
         if (kPhys && level == 2) {
 #pragma unroll
             for (int x = 0; x < kRegsLarge; ++x) {
+                if (x * kSelThreads >= n_work) break;             // uniform
                 const int i = x * kSelThreads + tid_l;
                 if (i < n_work) phys_by_slot[i] = entry[kPhys ? x : 0];
             }
@@ -1185,15 +1267,19 @@ __device__ __forceinline__ bool cascade_with(const Scorer& scorer, int P, const 
             __syncthreads();
             n_kept = nc;
         } else {
+            // chunk keys: by unit, competing only under a kept grid (merged), or N_g slots per kept grid (lazy)
             uint64_t* lk = level == 1 ? keys + ng : keys;
-            const int n_slots = level == 0 ? ng : level == 1 ? nc : n_work;
-            const ActiveRule active{level == 1 ? keys : nullptr, g.n_g, inv_ng};
-            const KeepRule& rule = level == 0 ? rule_g : level == 1 ? rule_c : rule_p;
+            const int n_slots = level == 0 ? ng : level == 1 ? (merged ? nc : n_work) : n_work;
+            const ActiveRule active{(level == 1 && merged) ? keys : nullptr, g.n_g, inv_ng};
+            const KeepRule rule = rule_of(level);
+            const bool by_parent = level == 2 || (level == 1 && !merged);
             const EmitRule emit{level == 0 ? kept_grids : level == 1 ? kept_chunks : sel_pages,
-                                level == 2 ? kept_chunks : nullptr, g.n_c, inv_nc,
+                                by_parent ? (level == 1 ? kept_grids : kept_chunks) : nullptr, level == 1 ? g.n_g : g.n_c,
+                                level == 1 ? inv_ng : inv_nc,
                                 (kPhys && level == 2) ? sel_phys : nullptr, (kPhys && level == 2) ? phys_by_slot : nullptr};
             const int cap = level == 0 ? sp.cap_kg : level == 1 ? sp.cap_kc : g.max_sel - s - w;
-            n_kept = cut_level(lk, n_slots, active, rule, keep_ties, general, emit, cap, level == 0, sh);
+            n_kept = cut_level(lk, n_slots, active, rule, keep_ties, general, emit, cap, level == 0 && merged, sh,
+                               have_pulled, pulled);
             if (n_kept > cap) { res->overflow = true; n_kept = cap; }
         }
         prof.mark(4 + 4 * level);

@@ -49,7 +49,7 @@ __device__ __forceinline__ void refresh_tail_units(const uint16_t* __restrict__ 
                                                    uint64_t* tail_words, bool publish, Shared& sh)
 {
     const int tid = threadIdx.x;
-    const int tp = P - 1, tc = tp / g.n_c, tg = tc / g.n_g;
+    const int tp = P - 1, tc = div_by(tp, g.n_c, g.inv_nc), tg = div_by(tc, g.n_g, g.inv_ng);
     const int n_tok = L - tp * B;
     if (tid < kHeadDim) {
         const int c = tid;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(2))
     __syncthreads();
     prof.mark(1);                                                     // prologue done
 
-    // ---- the page list, in every member's LDS
+        // ---- the page list, in every member's LDS
     const PubLayout pubs = pub_layout(ws.keys + row * ws.key_stride, g);
     CascadeResult res;
     res.n_kp = 0; res.n_a = 0; res.n_p = 0; res.overflow = false;
