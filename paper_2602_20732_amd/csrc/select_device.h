@@ -537,7 +537,7 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
 #pragma unroll
         for (int x = 0; x < R; ++x) {
             key[x] = 0ull;
-            if (x * kSelThreads >= n_slots) continue;             // uniform
+            if (R > 4 && x * kSelThreads >= n_slots) continue;    // uniform (a branch per key only pays when there are many)
             const int i = x * kSelThreads + tid;
             key[x] = (i < n_slots && active(i)) ? keys[i] : 0ull;
             const bool valid = key[x] != 0ull;
@@ -596,7 +596,7 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
     unsigned sure = 0, maybe = 0;
 #pragma unroll
     for (int x = 0; x < R; ++x) {
-        if (x * kSelThreads >= n_slots) break;                    // uniform
+        if (R > 4 && x * kSelThreads >= n_slots) break;           // uniform
         const bool a = all ? key[x] != 0 : bin[x] > cutbin;
         const bool e = !all && bin[x] == cutbin;
         if (e) {
@@ -648,7 +648,7 @@ __device__ __forceinline__ int cut_in_registers(uint64_t* keys, int n_slots, con
     }
 #pragma unroll
     for (int x = 0; x < R; ++x) {
-        if (x * kSelThreads >= n_slots) break;                    // uniform
+        if (R > 4 && x * kSelThreads >= n_slots) break;           // uniform
         const int run = x * kSelWaves + wave;
         const int base = x * kSelWaves < kWave ? __builtin_amdgcn_readlane(e0, run) : __builtin_amdgcn_readlane(e1, run - kWave);
         const bool a = (sure >> x) & 1, e = (maybe >> x) & 1;
@@ -861,13 +861,13 @@ __device__ __forceinline__ void score_rows(const T* __restrict__ grids_row, cons
         for (int x = 0; x < kFly; ++x) {
             unit[x] = -1;
             dest[x] = -1;
-            if (s0 + kSelGroups * x >= hi) continue;  // uniform over the workgroup: rows of slots the share does not have
             const int slot = s0 + kSelGroups * x + g16;
             const SlotRef ref = target(min(slot, hi - 1));
             unit[x] = slot < hi ? ref.unit : -1;
             dest[x] = slot < hi ? ref.dest : -1;
-            // no per-lane condition on the load (unit 0 when the slot has no unit): that would make the compiler
-            // wait for each vector before asking for the next
+            // no condition on the load, per lane or per row of slots (unit 0 when the slot has no unit; rows the share
+            // does not have repeat its last slot): a per-lane condition would make the compiler wait for each vector
+            // before asking for the next, and a branch per row costs more than the repeated, cache-resident loads
             const T* base = ref.array == 0 ? grids_row : ref.array == 1 ? chunks_row : pages_row;
             v[x].load(base + (size_t)max(ref.unit, 0) * kHeadDim, ln);
         }
@@ -911,29 +911,23 @@ __device__ __forceinline__ bool pull_keys(const uint64_t* pub, const uint64_t* t
         uint64_t v[kPer];
         int dest[kPer];
         const uint64_t* word[kPer];
-        const int n_here = min(kPer, (n - j0 + kSelThreads - 1) / kSelThreads);   // rounds of 256 words that exist (uniform)
+        // (no branch around items beyond n: they repeat the last word, which costs a few coalesced requests; a branch per
+        // item costs more)
 #pragma unroll
         for (int x = 0; x < kPer; ++x) {
-            dest[x] = -1;
-            word[x] = pub;
-            if (x < n_here) {
-                const int j = j0 + x * kSelThreads + tid;
-                const int d = dest_of(min(j, n - 1));
-                dest[x] = j < n ? d : -1;
-                word[x] = pub + max(d, 0);
-                if (d >= 0 && d == ov_dest0) word[x] = tail + ov_word0;
-                if (d >= 0 && d == ov_dest1) word[x] = tail + ov_word1;
-            }
+            const int j = j0 + x * kSelThreads + tid;
+            const int d = dest_of(min(j, n - 1));
+            dest[x] = j < n ? d : -1;
+            word[x] = pub + max(d, 0);
+            if (d >= 0 && d == ov_dest0) word[x] = tail + ov_word0;
+            if (d >= 0 && d == ov_dest1) word[x] = tail + ov_word1;
         }
         int polls = 0;
         if (limit <= 0) { ok = false; break; }        // (a test asked for every wait to fail)
         while (true) {
             bool missing = false;
 #pragma unroll
-            for (int x = 0; x < kPer; ++x) {
-                v[x] = 1ull;
-                if (x < n_here) v[x] = observe_u64(word[x]);      // no per-lane condition: all stay in flight
-            }
+            for (int x = 0; x < kPer; ++x) v[x] = observe_u64(word[x]);       // unconditional: all stay in flight
 #pragma unroll
             for (int x = 0; x < kPer; ++x) missing = missing || (dest[x] >= 0 && v[x] == 0ull);
             if (__ballot(missing) == 0ull) break;
@@ -957,12 +951,11 @@ __device__ __forceinline__ bool pull_keys_regs(const uint64_t* pub, const uint64
     bool ok = limit > 0;
     const int tid = opaque_tid(), lane = tid & 63, wave = tid >> 6;
     const uint64_t* word[4];
-    const int n_here = (n + kSelThreads - 1) / kSelThreads;      // uniform
 #pragma unroll
     for (int x = 0; x < 4; ++x) {
         key[x] = 0ull;
         word[x] = pub;
-        if (x < n_here) {
+        {
             const int j = x * kSelThreads + tid;
             const int d = min(j, n - 1);
             word[x] = pub + d;
@@ -975,8 +968,7 @@ __device__ __forceinline__ bool pull_keys_regs(const uint64_t* pub, const uint64
         bool missing = false;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            key[x] = 1ull;
-            if (x < n_here) key[x] = observe_u64(word[x]);    // no per-lane condition: all stay in flight
+            key[x] = observe_u64(word[x]);                    // unconditional (a word beyond n repeats the last one): all stay in flight
         }
 #pragma unroll
         for (int x = 0; x < 4; ++x) missing = missing || key[x] == 0ull;
@@ -990,7 +982,7 @@ __device__ __forceinline__ bool pull_keys_regs(const uint64_t* pub, const uint64
     for (int x = 0; x < 4; ++x) {
         const int j = x * kSelThreads + tid;
         if (j >= n || key[x] == kAbsentKey || !ok) key[x] = 0ull;
-        if (x < n_here && j < n) keys[j] = key[x];
+        if (j < n) keys[j] = key[x];
         const bool valid = key[x] != 0ull;
         const unsigned hi = (unsigned)(key[x] >> 32);
         a = valid ? min(a, hi) : a;
