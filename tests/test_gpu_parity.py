@@ -601,3 +601,38 @@ def test_threshold_rule_keeps_every_tie_at_the_cut(cluster, general):
     assert lib.workspace_error(ws) & 2, "every page ties: 125 candidates cannot fit 17 places"
     assert int(nsel[0, 0]) == 20 and ids[0, 0].tolist() == list(range(0, 18)) + [126, 127]
     lib.close()
+
+
+@pytest.mark.parametrize("schedule,cluster", [(1, 0), (2, 0), (2, 5)])
+def test_long_context_with_more_than_1024_chunks(schedule, cluster):
+    """200K tokens in 16-token pages: 12500 pages, 1563 chunks, 196 grids.  Under the merged schedule the chunk cut
+    runs over more than 1024 unit-ordered keys with the kept-grid mask (the many-keys-per-thread cut); the tail
+    refresh rides along; ragged second sequence."""
+    sp = workload.WorkloadSpec("long", 2, (1000, 200000), 8, 2, 16, ("geometric", 256), (1, 3), 1, 4, budget_bp=100)
+    wl = workload.generate(sp, 91, seq_lens=[200000, 70001])
+    plan = plan_of(sp)
+    ref = run_oracle(wl, plan, sp.max_selected, dense=False)
+    d = to_device(wl)
+    lib = pk.Chess(config_of(sp))
+    lib.debug_force_schedule(schedule)
+    lib.debug_force_cluster(cluster)
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
+    pv, cv, gv = lib.summary_views(summ)
+    for b, L in enumerate([200000, 70001]):
+        tp = -(-L // 16) - 1
+        pv[b, :, tp] = 3.0; cv[b, :, tp // 8] = -2.0; gv[b, :, tp // 64] = 9.0
+    ids = torch.full((2, sp.n_kv_heads, sp.max_selected), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((2, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((2, sp.n_q_heads, 128), float("nan"), device="cuda")
+    lib.decode_step(d.q, d.k_pool, d.v_pool, d.block_table, d.seq_lens, summ, gpu_plan(plan), ids, nsel, out, ws, refresh_tail=True)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    assert np.array_equal(ids.cpu().numpy(), ref.ids) and np.array_equal(nsel.cpu().numpy(), ref.nsel)
+    assert np.abs(out.cpu().numpy() - ref.out).max() <= ATOL_TIGHT
+    ids2, nsel2 = torch.full_like(ids, -7), torch.full_like(nsel, -7)
+    lib.select(d.q, summ, d.seq_lens, gpu_plan(plan), ids2, nsel2, ws)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    assert torch.equal(ids2, ids) and torch.equal(nsel2, nsel)
+    lib.close()
