@@ -1,8 +1,11 @@
 """Seeded random shapes: geometry (page size, GQA group, hierarchy fan-outs), batch, ragged lengths, sink / window,
-plan and its parameters, probe, cluster size, general cut, in-launch tail refresh -- each drawn per case, the GPU
+plan and its parameters, probe, cluster size, general cut, in-launch tail refresh, schedule of the levels, cut rule,
+per-sequence budgets -- each drawn per case, the GPU
 (three calls and the fused step) against the oracle with the bars of test_gpu_parity.  The draws are fixed by the
 seed, so a failure names a reproducible case."""
 from __future__ import annotations
+
+import os
 
 import numpy as np
 import pytest
@@ -43,14 +46,21 @@ def draw(seed):
         kw.update(probe=oracle.PROBE_ANCHOR)
     sp = workload.WorkloadSpec(f"rand{seed}", batch, (0, hi), H * G, H, B, ("fixed", 96), (2, 2), s, w,
                                pages_per_chunk=nc, chunks_per_grid=ng)
-    return sp, lens, kw, int(rng.choice([0, 1, 2, 5])), bool(rng.random() < 0.25), bool(rng.random() < 0.5) and not anchor
+    cluster, general, refresh = int(rng.choice([0, 1, 2, 5])), bool(rng.random() < 0.25), bool(rng.random() < 0.5) and not anchor
+    # (drawn after everything else, so that the earlier draws of a seed stay what they were)
+    schedule = int(rng.choice([0, 1, 2]))
+    if rng.random() < 0.3:
+        kw.update(cut_rule=oracle.CUT_THRESHOLD)
+    if kind != oracle.PLAN_RATIO and rng.random() < 0.3:
+        kw.update(budget_per_seq=tuple(int(rng.choice([0, 1, 3, 17])) for _ in range(batch)))
+    return sp, lens, kw, cluster, general, refresh, schedule
 
 
-@pytest.mark.parametrize("seed", range(64))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("CHESS_RANDOM_SEEDS", "96"))))
 def test_random_shape(seed):
-    sp, lens, kw, cluster, general, refresh = draw(seed)
+    sp, lens, kw, cluster, general, refresh, schedule = draw(seed)
     print(f"[rand {seed}] page {sp.page_size} H {sp.n_kv_heads} G {sp.group} fan {sp.pages_per_chunk}x{sp.chunks_per_grid} "
-          f"lens {lens} plan {kw} cluster {cluster} general {general} refresh {refresh}", flush=True)
+          f"lens {lens} plan {kw} cluster {cluster} general {general} refresh {refresh} schedule {schedule}", flush=True)
     wl = workload.generate(sp, 500 + seed, seq_lens=lens)
     plan = plan_of(sp, **kw)
     max_sel = sp.max_pages
@@ -62,6 +72,7 @@ def test_random_shape(seed):
     lib.summarize(d.k_pool, d.block_table, d.seq_lens, summ)
     lib.debug_force_cluster(cluster)
     lib.debug_force_general_cut(general)
+    lib.debug_force_schedule(schedule)
     ids = torch.full((batch, sp.n_kv_heads, max_sel), -7, dtype=torch.int32, device="cuda")
     nsel = torch.full((batch, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
     out = torch.full((batch, sp.n_q_heads, 128), float("nan"), device="cuda")
