@@ -142,7 +142,8 @@ int chess_workspace_init(chess_ctx* ctx, void* workspace, void* stream);
  * Hierarchical summaries (Sec. 3.1).  Page vector = mean of the page's key rows (Eq. 1, per KV
  * head of this layer); chunk / grid vector = mean of the child vectors that exist (Eq. 2).  A
  * partial tail page is averaged over its own tokens.  Accumulation is fp64 in index order, one
- * rounding to fp32 per stored vector.
+ * rounding to fp32 per stored vector (with CHESS_SUMMARY_BF16 that fp32 value is rounded once more, to
+ * nearest-even bf16, and a parent averages its children as stored).
  * from_page: device int32 [batch] or NULL.  NULL recomputes everything.  Otherwise only pages
  * >= from_page[b] and the chunks / grids containing them are recomputed; vectors below that must
  * be valid from an earlier call on the same prefix.
@@ -182,7 +183,8 @@ int chess_summarize_recent(chess_ctx* ctx, const void* k_pool, const int32_t* bl
  * sum of the group's G query rows; a unit's score is probe . unit vector (fp64).  Level 1 keeps
  * the top k_g grids; level 2 ranks only chunks of kept grids and keeps k_c; level 3 ranks only
  * pages of kept chunks that are neither sink nor window pages and keeps k_p.  Rank order: score
- * descending, then index ascending.  Result: sinks, kept pages, window pages as one ascending
+ * descending, then index ascending (plan->cut_rule: exactly k units per level, or every unit that ties
+ * with the k-th).  Result: sinks, kept pages, window pages as one ascending
  * list of logical page numbers; if the sequence has at most s + w pages, all of them.
  * `plan` is a host pointer.  CHESS_EINVAL if s + w + (largest possible k_p) exceeds
  * max_selected_pages; CHESS_ENOTSUP if a level can have more candidates than fit in LDS.
