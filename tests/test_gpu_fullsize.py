@@ -165,3 +165,42 @@ def test_reuse_step_at_benchmark_shapes(name, sample):
     print(f"[{name}] reuse step, seq {sample}: max|out - oracle| = {err:.2e}")
     assert err <= ATOL
     lib.close()
+
+
+def test_cfg4a_threshold_rule_and_ragged_budgets():
+    """The benchmark shape with the switches a serving engine would use: a page budget per sequence (device array, some
+    entries falling back to the plan's 1 %) and the S >= tau cut rule; select, the fused step with its tail refresh, and
+    the attention over the list, whole sampled sequences against the oracle in the same modes."""
+    sp = workload.spec("cfg4a")
+    wl = workload.generate(sp, workload.default_seed("cfg4a") + 7, device="cuda")
+    per = (41, 0, 164, 82, 1, 120, 0, 60)
+    plan = plan_of(sp, budget_per_seq=per, cut_rule=oracle.CUT_THRESHOLD)
+    max_sel = sp.sink_pages + sp.window_pages + 164
+    lib = pk.Chess(config_of(sp, max_selected=max_sel))
+    summ, ws = lib.new_summaries(), lib.new_workspace()
+    ids = torch.full((sp.batch, sp.n_kv_heads, max_sel), -7, dtype=torch.int32, device="cuda")
+    nsel = torch.full((sp.batch, sp.n_kv_heads), -7, dtype=torch.int32, device="cuda")
+    out = torch.full((sp.batch, sp.n_q_heads, 128), float("nan"), device="cuda")
+    lib.summarize(wl.k_pool, wl.block_table, wl.seq_lens, summ)
+    gp = gpu_plan(plan)
+    lib.select(wl.q, summ, wl.seq_lens, gp, ids, nsel, ws)
+    ids2, nsel2 = torch.full_like(ids, -7), torch.full_like(nsel, -7)
+    lib.decode_step(wl.q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, summ, gp, ids2, nsel2, out, ws, refresh_tail=True)
+    torch.cuda.synchronize()
+    assert lib.workspace_error(ws) == 0
+    assert torch.equal(ids, ids2) and torch.equal(nsel, nsel2)
+    want = [sp.sink_pages + sp.window_pages + (k if k > 0 else sp.budget_for(sp.max_pages)) for k in per]
+    assert nsel.cpu().numpy().tolist() == [[n] * sp.n_kv_heads for n in want]
+    sample = [2, 4]
+    K, V, Q, bt, sl = host_subset(wl, sample)
+    g = geom_of(sp)
+    rp, rc, rg = oracle.summarize(K, bt, sl, g)
+    sub_plan = plan_of(sp, budget_per_seq=tuple(per[b] for b in sample), cut_rule=oracle.CUT_THRESHOLD)
+    rids, rn = oracle.select(Q, rp, rc, rg, sl, g, sub_plan, max_sel)
+    rout = oracle.attend(Q, K, V, bt, sl, g, rids, rn)
+    for i, b in enumerate(sample):
+        assert np.array_equal(ids[b].cpu().numpy(), rids[i]) and np.array_equal(nsel[b].cpu().numpy(), rn[i]), (b, "page lists")
+        err = np.abs(out[b].cpu().numpy() - rout[i]).max()
+        print(f"[cfg4a ragged budgets, threshold rule] seq {b}: k = {per[b]}, page lists exact, max|out - oracle| = {err:.2e}")
+        assert err <= ATOL
+    lib.close()

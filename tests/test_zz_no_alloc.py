@@ -81,6 +81,44 @@ def test_static_scratch_variant_equals_sparse_decode():
     lib3.close()
 
 
+def test_static_scratch_variant_in_a_hip_graph():
+    """The call allocates nothing and clears its counters with a fill kernel (not a memset node), so it can be captured:
+    every replay of the graph, with eager calls of the workspace variant and synchronisations in between and a different
+    query each time, gives the eager result bit for bit."""
+    sp = workload.spec("cfg2", scale=1 / 4)
+    wl = to_device(workload.generate(sp, workload.default_seed("cfg2")))
+    lib = pk.Chess(config_of(sp))
+    ids, nsel, ws = _lists(lib, wl, plan_of(sp), sp.batch, sp)
+    qs = [wl.q] + [workload.extra_queries(wl, v) for v in range(1, 4)]
+    eager = []
+    for q in qs:
+        out = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+        lib.sparse_decode(q, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out, ws)
+        torch.cuda.synchronize()
+        eager.append(out.clone())
+    q_in = torch.empty_like(wl.q)
+    out_g = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        q_in.copy_(qs[0])
+        lib.sparse_decode_static(q_in, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out_g)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            lib.sparse_decode_static(q_in, wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, out_g)
+        for rep in range(6):
+            i = rep % len(qs)
+            q_in.copy_(qs[i])
+            out_g.fill_(float("nan"))
+            graph.replay()
+            stream.synchronize()
+            assert torch.equal(out_g, eager[i]), f"replay {rep}"
+            scratch = torch.full((1, sp.n_q_heads, 128), float("nan"), device="cuda")      # eager work between the replays
+            lib.sparse_decode(qs[(i + 1) % len(qs)], wl.k_pool, wl.v_pool, wl.block_table, wl.seq_lens, ids, nsel, scratch, ws)
+            stream.synchronize()
+    lib.close()
+
+
 def test_static_scratch_variant_rejects_what_does_not_fit():
     """A shape whose partials exceed the array (16 query heads per KV head, 8 rows, 64 splits forced: 4.26 MB) is
     refused with CHESS_ESCRATCH before anything is launched; so are null pointers (CHESS_EINVAL)."""
