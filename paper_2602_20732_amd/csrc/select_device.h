@@ -114,6 +114,19 @@ __device__ __forceinline__ double row16_sum(double d)
     return d;
 }
 
+// Lane i of each row of 16 receives lane i + n of the row (n constant after unrolling; n = 0: the value itself).
+__device__ __forceinline__ unsigned row_shl_by(unsigned v, int n)
+{
+#define CHESS_SHL_CASE(k) case k: return (unsigned)__builtin_amdgcn_update_dpp(0, (int)v, 0x100 + k, 0xf, 0xf, false);
+    switch (n) {
+        CHESS_SHL_CASE(1) CHESS_SHL_CASE(2) CHESS_SHL_CASE(3) CHESS_SHL_CASE(4) CHESS_SHL_CASE(5) CHESS_SHL_CASE(6) CHESS_SHL_CASE(7)
+        CHESS_SHL_CASE(8) CHESS_SHL_CASE(9) CHESS_SHL_CASE(10) CHESS_SHL_CASE(11) CHESS_SHL_CASE(12) CHESS_SHL_CASE(13)
+        CHESS_SHL_CASE(14) CHESS_SHL_CASE(15)
+    default: return v;
+    }
+#undef CHESS_SHL_CASE
+}
+
 __device__ __forceinline__ uint64_t lane_read64(uint64_t v, int src)
 {
     const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, src);
@@ -871,14 +884,27 @@ __device__ __forceinline__ void score_rows(const T* __restrict__ grids_row, cons
             const T* base = ref.array == 0 ? grids_row : ref.array == 1 ? chunks_row : pages_row;
             v[x].load(base + (size_t)max(ref.unit, 0) * kHeadDim, ln);
         }
+        // The total of vector x ends up in lane 15 of its group; it is handed to lane x of the group, so that one key
+        // conversion and one store serve all the vectors of the trip (instead of one masked branch, conversion and
+        // store per vector).
+        static_assert(kFly <= 16, "a lane of the group per vector of a trip");
+        double mine = 0.0;
+        int my_unit = -1, my_dest = -1;
 #pragma unroll
         for (int x = 0; x < kFly; ++x) {
             if (s0 + kSelGroups * x >= hi) break;     // uniform over the workgroup
             const double d = row16_sum(dot8<T>(pr, v[x]));
-            if (ln == 15 && dest[x] >= 0) {
-                if (local) lds_keys[dest[x]] = unit[x] >= 0 ? order_key(d) : 0ull;
-                else publish_u64(pub + dest[x], unit[x] >= 0 ? order_key(d) : kAbsentKey);
+            const uint64_t b = (uint64_t)__double_as_longlong(d);
+            const unsigned lo = row_shl_by((unsigned)b, 15 - x), hi32 = row_shl_by((unsigned)(b >> 32), 15 - x);
+            if (ln == x) {
+                mine = __longlong_as_double((long long)(((uint64_t)hi32 << 32) | lo));
+                my_unit = unit[x];
+                my_dest = dest[x];
             }
+        }
+        if (my_dest >= 0) {
+            if (local) lds_keys[my_dest] = my_unit >= 0 ? order_key(mine) : 0ull;
+            else publish_u64(pub + my_dest, my_unit >= 0 ? order_key(mine) : kAbsentKey);
         }
     }
 }
