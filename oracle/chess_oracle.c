@@ -37,8 +37,9 @@
  *     per-head dots, Eq. 1's Flatten restricted to the group);
  *   - a partial tail page / last chunk / last grid is averaged over the
  *     members that exist;
- *   - the paper calls a summary a "compact vector" and gives no storage type: fp32 (the fp64 mean rounded once),
- *     or bf16 (that fp32 value rounded to nearest-even bf16; parents average the stored children): a switch;
+ *   - Sec. 3.1 calls a summary a compact vector and gives no storage type (Eq. 1-2 define the means only): fp32
+ *     (the fp64 mean rounded once), or bf16 (that fp32 value rounded to nearest-even bf16; Eq. 2's parents average the
+ *     children as stored, so that a refresh from stored siblings equals a full pass): a switch, default fp32;
  *   - "top rho fraction" keeps exactly ceil(rho * n) of the n units that are
  *     active at that level (the reading under which Table 1's budgets are the
  *     products of the three ratios); rank order is score descending, index
