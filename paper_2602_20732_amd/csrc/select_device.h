@@ -20,15 +20,17 @@
 //
 // There is no barrier between the members: a key word is 0 until its owner has published it (a slot without a unit
 // is published as 1), so a member polls the words it needs until none is 0.  One memory round trip serves as
-// both the wait and the transfer.  Every member then finds the cut itself (all compute the same thing).  A level
-// of up to 1024 slots is cut by ONE wave with no barrier inside: 16 keys per lane, bounds from the upper key
-// halves, a histogram over 1024 bins that are linear in the (fp32-rounded) score, a scan from the top, an exact
-// ranking by (key, slot) of the few keys in the bin the k-th largest falls in, ballots for the positions in the
-// ascending list of kept units.  Ties at the cut go to the lowest slots (= lowest indices: candidates are
-// enumerated in index order), or are all kept under the threshold rule.  Larger levels keep their keys four-plus
-// per thread over the whole workgroup (same steps, LDS lists between the waves); score distributions that pile
-// more than 64 keys into the bin at the cut (exact ties, mostly) take a general path: radix select on the bits
-// the keys do not share, then a ballot compaction.
+// both the wait and the transfer.  Every member then finds the cut itself (all compute the same thing): bounds
+// from the upper key halves, a histogram over 1024 bins that are linear in the (fp32-rounded) score, a scan from
+// the top, an exact ranking by (key, slot) of the few keys in the bin the k-th largest falls in, ballots for the
+// positions in the ascending list of kept units.  Ties at the cut go to the lowest slots (= lowest indices:
+// candidates are enumerated in index order), or are all kept under the threshold rule.  A level of up to 64 slots is
+// ranked by one wave with lane reads alone, up to 256 slots by one wave with four keys per lane and no barrier
+// inside; larger levels keep their keys four (up to 1024 slots; the polled keys arrive in registers) or seventeen
+// per thread over the whole workgroup, with LDS lists between the waves.  (One wave cutting 1024 keys, sixteen per
+// lane, was measured: 8-9 us instead of 3-4, a single wave being a long chain of dependent instructions.)  Score
+// distributions that pile more than 64 keys into the bin at the cut (exact ties, mostly) take a general path: radix
+// select on the bits the keys do not share, then a ballot compaction.
 //
 // The words are cleared again by the workgroup that is last to be done with them, so they are all 0 between
 // launches.  Polls are bounded: a wait that does not end raises the workspace's error flag and the workgroup
