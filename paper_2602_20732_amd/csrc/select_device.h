@@ -229,7 +229,7 @@ constexpr int kSelGroups = kSelThreads / 16;  // 16-lane groups of a workgroup
 constexpr int kFastMembers = 64;            // most keys the bin at the cut may hold on the histogram paths
 constexpr int kRegsLarge = (4352 + kSelThreads - 1) / kSelThreads;       // keys per thread of the largest level the register path holds
 constexpr int kMaxRuns = kRegsLarge * kSelWaves;  // its 64-slot runs
-constexpr int kOneWaveSlots = 16 * kWave;   // largest level one wave cuts by itself
+constexpr int kOneWaveSlots = 4 * kWave;    // largest level one wave cuts by itself
 
 struct Shared {
     int hist[kBins];
@@ -827,7 +827,7 @@ __device__ __forceinline__ int cut_level(uint64_t* keys, int n_slots, const Acti
     int n = -1;
     if (!general) {
         if (n_slots <= kWave) n = cut_one_lane_each(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
-        else if (n_slots <= 4 * kWave) n = cut_by_one_wave<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
+        else if (n_slots <= kOneWaveSlots) n = cut_by_one_wave<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh);
         else if (n_slots <= 4 * kSelThreads && have_pre) n = cut_in_registers<4, true>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
         else if (n_slots <= 4 * kSelThreads) n = cut_in_registers<4>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
         else if (n_slots <= kRegsLarge * kSelThreads) n = cut_in_registers<kRegsLarge>(keys, n_slots, active, k_of, keep_ties, emit, cap, mark, sh, pre);
